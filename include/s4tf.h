@@ -1,0 +1,249 @@
+/*
+ * s4tf.h -- C ABI of the MI355X (gfx950) training-step library.
+ *
+ * The library computes one differentiated training step of a convolutional network:
+ * forward pass, the pullbacks of every op in reverse order, and an in-place
+ * SGD-momentum update.  That is the loop the paper writes in Section 4.2 (figure
+ * "Training LeNet on a simple dataset"): `gradient(at: model) { softmaxCrossEntropy(
+ * logits: model(batch.data), labels: batch.label) }` followed by
+ * `optimizer.update(&model, along: gradients)`.  Every `*_vjp` entry point is one
+ * pullback in the sense of Section 2.1: it maps the cotangent of an op's output to the
+ * cotangents of its inputs and parameters; the tensors a pullback "captures" are passed
+ * back in by the caller.  The step has the type `(inout Model, Minibatch) -> Void` of
+ * Section 4.2: parameters and velocities are updated in place, no second copy of the
+ * model is made.
+ *
+ * General rules (all entry points)
+ *  - Every data pointer is a DEVICE pointer (HIP global memory) unless marked "host".
+ *    Descriptor structs are host memory and are read before the call returns.
+ *  - Layouts: activations NHWC; filters (R,S,C/groups,K) (the paper's
+ *    `filterShape: (5, 5, 1, 6)` = (H,W,Cin,Cout)); dense weights [in,out], y = xW + b.
+ *    Convolution is cross-correlation with symmetric zero padding,
+ *    P = floor((H + 2*pad - R)/stride) + 1.
+ *  - dtype is the storage type of activations, activation cotangents and the working
+ *    copy of conv filters: S4TF_F32 (float) or S4TF_BF16 (bfloat16, round to nearest
+ *    even on store, fp32 accumulation).  Parameter gradients, BatchNorm statistics,
+ *    gamma/beta, biases, the whole head, master weights and velocities are always fp32.
+ *  - Ownership: the caller allocates and frees every buffer, including workspaces.  The
+ *    library keeps no pointer after the work it enqueued has completed.
+ *  - Execution: all work is enqueued on `stream` (a hipStream_t passed as void*, NULL is
+ *    the default stream).  No entry point synchronises the host.
+ *  - Errors: every entry point returns an s4tf_status.  Arguments are validated before
+ *    anything is launched, so a non-OK return means nothing was written.  A message is
+ *    available from s4tf_last_error() (thread-local).  No exception crosses the ABI.
+ *  - Alignment: device pointers must be 16-byte aligned.  Outputs must not alias inputs
+ *    except where documented (param/velocity of s4tf_sgd_momentum, the in-place update
+ *    of s4tf_train_step).
+ *  - Workspaces: each op that needs scratch memory has a `*_workspace_bytes` query; the
+ *    caller passes at least that many bytes (16-byte aligned).  Contents are undefined
+ *    on entry and on return.
+ */
+#ifndef S4TF_H
+#define S4TF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  S4TF_OK = 0,
+  S4TF_ERR_NULL = -1,        /* a required pointer is NULL */
+  S4TF_ERR_SHAPE = -2,       /* non-positive size, empty output, inconsistent shapes */
+  S4TF_ERR_DTYPE = -3,       /* unknown dtype / activation code */
+  S4TF_ERR_UNSUPPORTED = -4, /* valid but not implemented (e.g. 1 < groups < C) */
+  S4TF_ERR_WORKSPACE = -5,   /* workspace missing or too small */
+  S4TF_ERR_DEVICE = -6,      /* HIP launch error */
+  S4TF_ERR_ALIGN = -7        /* pointer not 16-byte aligned */
+} s4tf_status;
+
+typedef enum { S4TF_F32 = 0, S4TF_BF16 = 1 } s4tf_dtype;
+typedef enum { S4TF_ACT_NONE = 0, S4TF_ACT_RELU = 1, S4TF_ACT_RELU6 = 2 } s4tf_act;
+
+/* Convolution.  x is (n,h,w,c), w is (r,s,c/groups,k), y is (n,p,q,k).  groups must be 1
+ * or c (depthwise, which also needs k == c).  act is applied to conv + bias in the
+ * forward pass (the `activation: relu` of the paper's Conv2D/Dense layers).
+ * accumulate_dx != 0 makes the pullback ADD the input cotangent to what dx already holds
+ * (the `inout` formulation of a pullback, Section 4.3) instead of overwriting it. */
+typedef struct {
+  int32_t n, h, w, c, k, r, s, stride, pad, groups;
+  int32_t dtype; /* s4tf_dtype */
+  int32_t act;   /* s4tf_act */
+  int32_t accumulate_dx;
+} s4tf_conv_desc;
+
+/* BatchNorm (training mode, biased variance, eps inside the square root) + optional
+ * residual add + activation over an (n,h,w,c) tensor. */
+typedef struct {
+  int32_t n, h, w, c;
+  float eps;
+  int32_t act;   /* s4tf_act */
+  int32_t dtype; /* s4tf_dtype */
+  int32_t accumulate_dres; /* pullback adds into dresidual instead of overwriting */
+} s4tf_bn_desc;
+
+/* Head: global average pool over (h,w), dense c -> classes, mean softmax cross-entropy. */
+typedef struct {
+  int32_t n, h, w, c, classes;
+  int32_t dtype; /* storage type of x and dx; W, b, loss and their gradients are fp32 */
+} s4tf_head_desc;
+
+typedef enum { S4TF_POOL_AVG2 = 0, S4TF_POOL_MAX3S2 = 1 } s4tf_pool_kind;
+/* AVG2: 2x2 window, stride 2, no padding (the paper's AvgPool2D(poolSize: (2,2),
+ * strides: (2,2))).  MAX3S2: 3x3 window, stride 2, padding 1, padding never wins. */
+typedef struct {
+  int32_t n, h, w, c;
+  int32_t kind;  /* s4tf_pool_kind */
+  int32_t dtype; /* s4tf_dtype */
+  int32_t accumulate_dx;
+} s4tf_pool_desc;
+
+/* Thread-local message for the last non-OK status returned on this thread ("" if none).
+ * Host pointer to static storage; valid until the next library call on the thread. */
+const char* s4tf_last_error(void);
+
+/* ---- conv2d (Conv2D / Dense of the paper's Section 4.1 figure) -------------------------
+ * fwd:  y[n,p,q,k] = act(bias[k] + sum_{r,s,c} x[n,p*stride+r-pad,q*stride+s-pad,c] w[r,s,c,k])
+ * vjp:  dz = dy * act'(y)  (act' evaluated on the stored output: 0<y for relu, 0<y<6 for relu6)
+ *       dx[n,h,w,c] (+)= sum_{r,s,k} dz[n,p,q,k] w[r,s,c,k]  over (p,q) with p*stride+r-pad = h ...
+ *       dw[r,s,c,k]  = sum_{n,p,q} x[n,p*stride+r-pad,q*stride+s-pad,c] dz[n,p,q,k]   (fp32)
+ *       dbias[k]     = sum_{n,p,q} dz[n,p,q,k]                                          (fp32)
+ * x, w, y, dy, dx have the descriptor's dtype.  bias/dbias may be NULL.  y may be NULL in
+ * vjp when act is NONE.  dx may be NULL (no consumer, e.g. the first layer).  dw and dbias
+ * are overwritten.  A dense layer is the case h = w = r = s = 1. */
+size_t s4tf_conv2d_fwd_workspace_bytes(const s4tf_conv_desc* d);
+size_t s4tf_conv2d_vjp_workspace_bytes(const s4tf_conv_desc* d);
+int s4tf_conv2d_fwd(const s4tf_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
+                    void* workspace, size_t workspace_bytes, void* stream);
+int s4tf_conv2d_vjp(const s4tf_conv_desc* d, const void* x, const void* w, const void* y,
+                    const void* dy, void* dx, float* dw, float* dbias, void* workspace,
+                    size_t workspace_bytes, void* stream);
+
+/* ---- BatchNorm + residual + activation ------------------------------------------------
+ * fwd:  per channel over m = n*h*w: mean, var (biased), invstd = 1/sqrt(var + eps);
+ *       xhat = (x - mean)*invstd;  z = gamma*xhat + beta (+ residual);  y = act(z);
+ *       save_mean[c], save_invstd[c] are written for the pullback.
+ * vjp:  dz = dy*act'(y);  dresidual (+)= dz;  dbeta = sum dz;  dgamma = sum dz*xhat;
+ *       dx = gamma*invstd*(dz - dbeta/m - xhat*dgamma/m)
+ * residual / dresidual may be NULL.  gamma, beta, statistics and their gradients are fp32
+ * arrays of c elements.  y may be NULL in vjp when act is NONE. */
+size_t s4tf_bn_relu_workspace_bytes(const s4tf_bn_desc* d);
+int s4tf_bn_relu_fwd(const s4tf_bn_desc* d, const void* x, const void* residual, const float* gamma,
+                     const float* beta, void* y, float* save_mean, float* save_invstd,
+                     void* workspace, size_t workspace_bytes, void* stream);
+int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const float* gamma,
+                     const float* save_mean, const float* save_invstd, const void* dy, void* dx,
+                     void* dresidual, float* dgamma, float* dbeta, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+/* ---- pooling ---------------------------------------------------------------------------
+ * AVG2 fwd: mean of the window; vjp: dy/4 to each of the four inputs.
+ * MAX3S2 fwd: maximum of the in-range window; vjp: the whole dy goes to the first maximum
+ * in row-major window order (needs x). x may be NULL in vjp for AVG2. */
+int s4tf_pool2d_fwd(const s4tf_pool_desc* d, const void* x, void* y, void* stream);
+int s4tf_pool2d_vjp(const s4tf_pool_desc* d, const void* x, const void* dy, void* dx, void* stream);
+
+/* ---- head: global-avg-pool + dense + softmax cross-entropy, value and pullback --------
+ * (`softmaxCrossEntropy(logits:labels:)` of the paper's training loop, reduced to the
+ * scalar `gradient(at:in:)` requires by a mean over the batch.)
+ *   pbar[n,c] = mean_{h,w} x[n,h,w,c];  z = pbar W + b;
+ *   loss = -(1/n) sum_n log softmax(z_n)[labels[n]]      (max-subtracted, fp32)
+ *   dz = (softmax(z) - onehot(labels))/n;  dW = pbar^T dz;  db = sum_n dz;
+ *   dx[n,h,w,c] = (dz W^T)[n,c] / (h*w)
+ * W is fp32 [c,classes], b fp32 [classes], labels int32 [n] in [0,classes) (a label out
+ * of range contributes no -1 term and no loss; it is the caller's error).  loss is one
+ * fp32 device scalar.  dx may be NULL.  logits (nullable) receives z as fp32 [n,classes]. */
+size_t s4tf_pool_dense_xent_workspace_bytes(const s4tf_head_desc* d);
+int s4tf_pool_dense_xent_fwd_vjp(const s4tf_head_desc* d, const void* x, const float* W, const float* b,
+                                 const int32_t* labels, float* loss, void* dx, float* dW, float* db,
+                                 float* logits, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
+/* ---- SGD with momentum, in place (`optimizer.update(&model, along: gradients)`) -------
+ *   velocity <- momentum*velocity + grad;   param <- param - lr*velocity
+ *   param_lowp[i] <- bf16(param[i])  when param_lowp is not NULL (working copy)
+ * count may be 0 (no-op). param and velocity are updated in place. */
+int s4tf_sgd_momentum(size_t count, float* param, float* velocity, const float* grad, void* param_lowp,
+                      float lr, float momentum, void* stream);
+
+/* ---- whole step -------------------------------------------------------------------------
+ * A network is a static list of ops in topological order; op i produces tensor i+1,
+ * tensor 0 is the batch.  `in`/`res` name earlier tensors.  The last op must be the head
+ * and every other tensor needs at least one consumer. */
+typedef enum {
+  S4TF_OP_CONV = 0,       /* uses k,r,s,stride,pad,groups,has_bias,act */
+  S4TF_OP_BN = 1,         /* uses res (-1: none), act, eps */
+  S4TF_OP_AVGPOOL2 = 2,
+  S4TF_OP_MAXPOOL3S2 = 3,
+  S4TF_OP_FLATTEN = 4,    /* (n,h,w,c) -> (n,1,1,h*w*c), a reinterpretation, no copy */
+  S4TF_OP_HEAD = 5        /* uses k = classes */
+} s4tf_op_kind;
+
+typedef struct {
+  int32_t kind; /* s4tf_op_kind */
+  int32_t in;   /* input tensor id */
+  int32_t res;  /* residual tensor id for BN, else -1 */
+  int32_t k, r, s, stride, pad, groups, has_bias;
+  int32_t act;  /* s4tf_act */
+  float eps;
+} s4tf_op;
+
+typedef struct {
+  int32_t n, h, w, c;   /* batch tensor shape */
+  int32_t dtype;        /* s4tf_dtype of activations */
+  int32_t n_ops;
+  const s4tf_op* ops;   /* host array */
+  float momentum;
+} s4tf_net_desc;
+
+/* Parameters live in one flat fp32 arena; each op's tensors sit at the offsets
+ * s4tf_net_param_layout reports (op order; conv: filter then bias; BN: gamma then beta;
+ * head: W then b; every tensor starts at a multiple of 8 elements, padding is zero and
+ * stays zero).  grad has the same layout and is overwritten by the step.  lowp is the
+ * bf16 working copy of the arena (same offsets); required when dtype is BF16 (it must
+ * hold bf16(master) on entry and is refreshed by the update), ignored otherwise. */
+typedef struct {
+  float* master;   /* inout */
+  float* velocity; /* inout */
+  float* grad;     /* out */
+  void* lowp;      /* inout, bf16, nullable for F32 nets */
+  size_t count;    /* elements in each arena, = s4tf_net_param_count */
+} s4tf_params;
+
+typedef struct {
+  const void* x;         /* (n,h,w,c) in the net's dtype */
+  const int32_t* labels; /* int32 [n] */
+  float* loss;           /* out: one fp32 device scalar */
+  void* workspace;       /* activation stash, cotangents, scratch */
+  size_t workspace_bytes;
+  void* stream;
+} s4tf_batch;
+
+/* Host-side queries.  offsets/sizes (host arrays, 2 entries per op, nullable) receive the
+ * arena offset and element count of the op's first and second parameter tensor (size 0 if
+ * absent).  Return 0 / write nothing if the descriptor is invalid (see s4tf_last_error). */
+size_t s4tf_net_param_count(const s4tf_net_desc* net);
+int s4tf_net_param_layout(const s4tf_net_desc* net, int64_t* offsets, int64_t* sizes);
+size_t s4tf_train_step_workspace_bytes(const s4tf_net_desc* net);
+
+/* One training step: forward, loss, pullbacks in reverse op order (cotangents of a tensor
+ * with several consumers are summed in reverse consumer order), then one SGD-momentum
+ * update of the whole arena.  Enqueues on batch->stream; never synchronises. */
+int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_batch* batch, float lr);
+
+/* ---- measurement hook -------------------------------------------------------------------
+ * While enabled, every kernel launch made by this thread's calls is bracketed by a pair of
+ * HIP events on its stream.  s4tf_profile_collect synchronises those events and adds up
+ * elapsed milliseconds and launch counts per kernel class into host arrays of
+ * S4TF_PROF_CLASSES entries, then clears the record. Class names: s4tf_profile_class_name. */
+#define S4TF_PROF_CLASSES 16
+int s4tf_profile_enable(int on);
+int s4tf_profile_collect(double* ms, int64_t* launches);
+const char* s4tf_profile_class_name(int cls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S4TF_H */

@@ -1,0 +1,331 @@
+"""ctypes binding of libs4tf.so: the same entry points as include/s4tf.h, argument marshalling
+only.  PyTorch is used for device memory and streams; every step of the path runs in the
+library's HIP kernels.  There is no CPU fallback: if the library cannot be loaded, importing
+the entry points raises."""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libs4tf.so")
+
+S4TF_F32, S4TF_BF16 = 0, 1
+ACT = {"none": 0, "relu": 1, "relu6": 2}
+POOL_AVG2, POOL_MAX3S2 = 0, 1
+OP_CONV, OP_BN, OP_AVGPOOL2, OP_MAXPOOL3S2, OP_FLATTEN, OP_HEAD = range(6)
+PROF_CLASSES = 16
+
+c_i32, c_f32, c_vp, c_sz = ctypes.c_int32, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, c_i32) for n in ("n", "h", "w", "c", "k", "r", "s", "stride", "pad", "groups", "dtype",
+                                     "act", "accumulate_dx")]
+
+
+class BnDesc(ctypes.Structure):
+    _fields_ = [("n", c_i32), ("h", c_i32), ("w", c_i32), ("c", c_i32), ("eps", c_f32), ("act", c_i32),
+                ("dtype", c_i32), ("accumulate_dres", c_i32)]
+
+
+class HeadDesc(ctypes.Structure):
+    _fields_ = [(n, c_i32) for n in ("n", "h", "w", "c", "classes", "dtype")]
+
+
+class PoolDesc(ctypes.Structure):
+    _fields_ = [(n, c_i32) for n in ("n", "h", "w", "c", "kind", "dtype", "accumulate_dx")]
+
+
+class Op(ctypes.Structure):
+    _fields_ = [(n, c_i32) for n in ("kind", "in_", "res", "k", "r", "s", "stride", "pad", "groups", "has_bias",
+                                     "act")] + [("eps", c_f32)]
+
+
+class NetDesc(ctypes.Structure):
+    _fields_ = [("n", c_i32), ("h", c_i32), ("w", c_i32), ("c", c_i32), ("dtype", c_i32), ("n_ops", c_i32),
+                ("ops", ctypes.POINTER(Op)), ("momentum", c_f32)]
+
+
+class Params(ctypes.Structure):
+    _fields_ = [("master", c_vp), ("velocity", c_vp), ("grad", c_vp), ("lowp", c_vp), ("count", c_sz)]
+
+
+class Batch(ctypes.Structure):
+    _fields_ = [("x", c_vp), ("labels", c_vp), ("loss", c_vp), ("workspace", c_vp), ("workspace_bytes", c_sz),
+                ("stream", c_vp)]
+
+
+_lib = None
+
+
+class S4tfError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("s4tf status %d: %s" % (status, message))
+        self.status = status
+
+
+def lib():
+    """Load libs4tf.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    L = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER
+    L.s4tf_last_error.restype = ctypes.c_char_p
+    L.s4tf_last_error.argtypes = []
+    for name in ("s4tf_conv2d_fwd_workspace_bytes", "s4tf_conv2d_vjp_workspace_bytes"):
+        getattr(L, name).restype = c_sz
+        getattr(L, name).argtypes = [P(ConvDesc)]
+    L.s4tf_bn_relu_workspace_bytes.restype = c_sz
+    L.s4tf_bn_relu_workspace_bytes.argtypes = [P(BnDesc)]
+    L.s4tf_pool_dense_xent_workspace_bytes.restype = c_sz
+    L.s4tf_pool_dense_xent_workspace_bytes.argtypes = [P(HeadDesc)]
+    L.s4tf_conv2d_fwd.argtypes = [P(ConvDesc), c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    L.s4tf_conv2d_vjp.argtypes = [P(ConvDesc), c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    L.s4tf_bn_relu_fwd.argtypes = [P(BnDesc), c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    L.s4tf_bn_relu_vjp.argtypes = [P(BnDesc)] + [c_vp] * 11 + [c_sz, c_vp]
+    L.s4tf_pool2d_fwd.argtypes = [P(PoolDesc), c_vp, c_vp, c_vp]
+    L.s4tf_pool2d_vjp.argtypes = [P(PoolDesc), c_vp, c_vp, c_vp, c_vp]
+    L.s4tf_pool_dense_xent_fwd_vjp.argtypes = [P(HeadDesc)] + [c_vp] * 10 + [c_sz, c_vp]
+    L.s4tf_sgd_momentum.argtypes = [c_sz, c_vp, c_vp, c_vp, c_vp, c_f32, c_f32, c_vp]
+    L.s4tf_net_param_count.restype = c_sz
+    L.s4tf_net_param_count.argtypes = [P(NetDesc)]
+    L.s4tf_net_param_layout.argtypes = [P(NetDesc), P(ctypes.c_int64), P(ctypes.c_int64)]
+    L.s4tf_train_step_workspace_bytes.restype = c_sz
+    L.s4tf_train_step_workspace_bytes.argtypes = [P(NetDesc)]
+    L.s4tf_train_step.argtypes = [P(NetDesc), P(Params), P(Batch), c_f32]
+    L.s4tf_profile_enable.argtypes = [ctypes.c_int]
+    L.s4tf_profile_collect.argtypes = [P(ctypes.c_double), P(ctypes.c_int64)]
+    L.s4tf_profile_class_name.restype = ctypes.c_char_p
+    L.s4tf_profile_class_name.argtypes = [ctypes.c_int]
+    for name in ("s4tf_conv2d_fwd", "s4tf_conv2d_vjp", "s4tf_bn_relu_fwd", "s4tf_bn_relu_vjp", "s4tf_pool2d_fwd",
+                 "s4tf_pool2d_vjp", "s4tf_pool_dense_xent_fwd_vjp", "s4tf_sgd_momentum", "s4tf_net_param_layout",
+                 "s4tf_train_step", "s4tf_profile_enable", "s4tf_profile_collect"):
+        getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def last_error():
+    return lib().s4tf_last_error().decode()
+
+
+def _check(status):
+    if status != 0:
+        raise S4tfError(status, last_error())
+
+
+def _p(t):
+    """Device pointer of a torch tensor (or pass through ints / None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+# ---- entry points, named as in s4tf.h ----------------------------------------------------------------
+def s4tf_conv2d_fwd_workspace_bytes(d):
+    return int(lib().s4tf_conv2d_fwd_workspace_bytes(ctypes.byref(d)))
+
+
+def s4tf_conv2d_vjp_workspace_bytes(d):
+    return int(lib().s4tf_conv2d_vjp_workspace_bytes(ctypes.byref(d)))
+
+
+def s4tf_conv2d_fwd(d, x, w, bias, y, workspace=None, stream=None):
+    _check(lib().s4tf_conv2d_fwd(ctypes.byref(d), _p(x), _p(w), _p(bias), _p(y), _p(workspace), _nbytes(workspace),
+                                 _stream(stream)))
+
+
+def s4tf_conv2d_vjp(d, x, w, y, dy, dx, dw, dbias, workspace=None, stream=None):
+    _check(lib().s4tf_conv2d_vjp(ctypes.byref(d), _p(x), _p(w), _p(y), _p(dy), _p(dx), _p(dw), _p(dbias),
+                                 _p(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def s4tf_bn_relu_workspace_bytes(d):
+    return int(lib().s4tf_bn_relu_workspace_bytes(ctypes.byref(d)))
+
+
+def s4tf_bn_relu_fwd(d, x, residual, gamma, beta, y, save_mean, save_invstd, workspace, stream=None):
+    _check(lib().s4tf_bn_relu_fwd(ctypes.byref(d), _p(x), _p(residual), _p(gamma), _p(beta), _p(y), _p(save_mean),
+                                  _p(save_invstd), _p(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def s4tf_bn_relu_vjp(d, x, y, gamma, save_mean, save_invstd, dy, dx, dresidual, dgamma, dbeta, workspace,
+                     stream=None):
+    _check(lib().s4tf_bn_relu_vjp(ctypes.byref(d), _p(x), _p(y), _p(gamma), _p(save_mean), _p(save_invstd), _p(dy),
+                                  _p(dx), _p(dresidual), _p(dgamma), _p(dbeta), _p(workspace), _nbytes(workspace),
+                                  _stream(stream)))
+
+
+def s4tf_pool2d_fwd(d, x, y, stream=None):
+    _check(lib().s4tf_pool2d_fwd(ctypes.byref(d), _p(x), _p(y), _stream(stream)))
+
+
+def s4tf_pool2d_vjp(d, x, dy, dx, stream=None):
+    _check(lib().s4tf_pool2d_vjp(ctypes.byref(d), _p(x), _p(dy), _p(dx), _stream(stream)))
+
+
+def s4tf_pool_dense_xent_workspace_bytes(d):
+    return int(lib().s4tf_pool_dense_xent_workspace_bytes(ctypes.byref(d)))
+
+
+def s4tf_pool_dense_xent_fwd_vjp(d, x, W, b, labels, loss, dx, dW, db, logits, workspace, stream=None):
+    _check(lib().s4tf_pool_dense_xent_fwd_vjp(ctypes.byref(d), _p(x), _p(W), _p(b), _p(labels), _p(loss), _p(dx),
+                                              _p(dW), _p(db), _p(logits), _p(workspace), _nbytes(workspace),
+                                              _stream(stream)))
+
+
+def s4tf_sgd_momentum(count, param, velocity, grad, param_lowp, lr, momentum, stream=None):
+    _check(lib().s4tf_sgd_momentum(count, _p(param), _p(velocity), _p(grad), _p(param_lowp), lr, momentum,
+                                   _stream(stream)))
+
+
+def s4tf_net_param_count(net_desc):
+    return int(lib().s4tf_net_param_count(ctypes.byref(net_desc)))
+
+
+def s4tf_net_param_layout(net_desc):
+    n = 2 * net_desc.n_ops
+    off = (ctypes.c_int64 * n)()
+    size = (ctypes.c_int64 * n)()
+    _check(lib().s4tf_net_param_layout(ctypes.byref(net_desc), off, size))
+    return list(off), list(size)
+
+
+def s4tf_train_step_workspace_bytes(net_desc):
+    return int(lib().s4tf_train_step_workspace_bytes(ctypes.byref(net_desc)))
+
+
+def s4tf_train_step(net_desc, params, batch, lr):
+    _check(lib().s4tf_train_step(ctypes.byref(net_desc), ctypes.byref(params), ctypes.byref(batch), lr))
+
+
+def s4tf_profile_enable(on):
+    _check(lib().s4tf_profile_enable(1 if on else 0))
+
+
+def s4tf_profile_collect():
+    ms = (ctypes.c_double * PROF_CLASSES)()
+    cnt = (ctypes.c_int64 * PROF_CLASSES)()
+    _check(lib().s4tf_profile_collect(ms, cnt))
+    return {lib().s4tf_profile_class_name(i).decode(): (ms[i], cnt[i]) for i in range(PROF_CLASSES) if cnt[i]}
+
+
+# ---- marshalling helpers --------------------------------------------------------------------------------
+def make_net_desc(net):
+    """s4tf_net_desc from the plain-dict description used by the workload generator.  Returns
+    (desc, keepalive) -- keep `keepalive` referenced as long as desc is used."""
+    ops = (Op * len(net["ops"]))()
+    for o, src in zip(ops, net["ops"]):
+        kind = src["kind"]
+        o.in_ = src["in"]
+        o.res = -1
+        o.groups, o.stride = 1, 1
+        if kind == "conv":
+            o.kind = OP_CONV
+            o.k, o.r, o.s, o.stride, o.pad, o.groups = src["k"], src["r"], src["s"], src["stride"], src["pad"], src["groups"]
+            o.has_bias = 1 if src["bias"] else 0
+            o.act = ACT[src["act"]]
+        elif kind == "bn":
+            o.kind = OP_BN
+            o.res = src["res"]
+            o.act = ACT[src["act"]]
+            o.eps = src["eps"]
+        elif kind == "avgpool2":
+            o.kind = OP_AVGPOOL2
+        elif kind == "maxpool3s2":
+            o.kind = OP_MAXPOOL3S2
+        elif kind == "flatten":
+            o.kind = OP_FLATTEN
+        elif kind == "head":
+            o.kind = OP_HEAD
+            o.k = src["classes"]
+        else:
+            raise ValueError(kind)
+    n, h, w, c = net["input"]
+    d = NetDesc(n, h, w, c, S4TF_BF16 if net["dtype"] == "bf16" else S4TF_F32, len(net["ops"]), ops, net["momentum"])
+    return d, ops
+
+
+class TrainState:
+    """Device buffers of one network: parameter arenas, workspace, loss scalar.  Marshalling
+    only: packs/unpacks the nested parameter lists of the workload generator into the flat
+    arena layout the library reports."""
+
+    def __init__(self, net, params, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.net = net
+        self.device = device
+        self.desc, self._keep = make_net_desc(net)
+        self.count = s4tf_net_param_count(self.desc)
+        if self.count == 0:
+            raise S4tfError(-2, last_error())
+        self.offsets, self.sizes = s4tf_net_param_layout(self.desc)
+        self.shapes = [[a.shape for a in p] for p in params]
+        arena = self.pack(params)
+        self.master = torch.from_numpy(arena).to(device)
+        self.velocity = torch.zeros(self.count, dtype=torch.float32, device=device)
+        self.grad = torch.zeros(self.count, dtype=torch.float32, device=device)
+        self.lowp = None
+        if net["dtype"] == "bf16":
+            self.lowp = torch.from_numpy(arena).to(torch.bfloat16).to(device)
+        self.ws_bytes = s4tf_train_step_workspace_bytes(self.desc)
+        self.workspace = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=device)
+        self.loss = torch.zeros(4, dtype=torch.float32, device=device)
+
+    def pack(self, params):
+        arena = np.zeros(self.count, np.float32)
+        for i, p in enumerate(params):
+            for j, a in enumerate(p):
+                off, size = self.offsets[2 * i + j], self.sizes[2 * i + j]
+                assert size == a.size, (i, j, size, a.size)
+                arena[off:off + size] = np.asarray(a, np.float32).reshape(-1)
+        return arena
+
+    def unpack(self, arena):
+        arena = np.asarray(arena)
+        out = []
+        for i, shp in enumerate(self.shapes):
+            out.append([arena[self.offsets[2 * i + j]:self.offsets[2 * i + j] + self.sizes[2 * i + j]].reshape(s)
+                        for j, s in enumerate(shp)])
+        return out
+
+    def upload_batch(self, x, labels):
+        torch = self.torch
+        xt = torch.from_numpy(np.ascontiguousarray(x, np.float32))
+        if self.net["dtype"] == "bf16":
+            xt = xt.to(torch.bfloat16)
+        return xt.to(self.device), torch.from_numpy(np.ascontiguousarray(labels, np.int32)).to(self.device)
+
+    def step(self, x_dev, labels_dev, lr=None, stream=None):
+        lr = self.net["lr"] if lr is None else lr
+        p = Params(_p(self.master), _p(self.velocity), _p(self.grad), _p(self.lowp), self.count)
+        b = Batch(_p(x_dev), _p(labels_dev), _p(self.loss), _p(self.workspace), self.ws_bytes, _stream(stream))
+        s4tf_train_step(self.desc, p, b, lr)
+
+    def results(self):
+        """Synchronise and download loss, gradients, parameters and velocities (nested lists)."""
+        self.torch.cuda.synchronize()
+        return {"loss": float(self.loss[0].item()), "grads": self.unpack(self.grad.cpu().numpy()),
+                "params": self.unpack(self.master.cpu().numpy()),
+                "velocity": self.unpack(self.velocity.cpu().numpy())}

@@ -1,0 +1,579 @@
+// The C ABI: argument validation, per-op entry points, and the whole-step scheduler that
+// runs forward, pullbacks in reverse op order and the optimizer update on one stream
+// (the paper's Section 4.2 training loop; a step is `(inout Model, Minibatch) -> Void`).
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "s4tf_internal.h"
+
+namespace s4tf {
+
+// ---- thread-local error text ----------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+int fail(int status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return status;
+}
+void clear_error() { g_err[0] = 0; }
+
+// ---- per-class kernel timing -----------------------------------------------------------------------
+struct ProfRec {
+  int cls;
+  hipEvent_t e0, e1;
+};
+static thread_local bool g_prof_on = false;
+static thread_local std::vector<ProfRec>* g_prof = nullptr;
+
+ProfScope::ProfScope(int c, hipStream_t s) : cls(c), stream(s), rec(nullptr) {
+  if (!g_prof_on) return;
+  if (!g_prof) g_prof = new std::vector<ProfRec>();
+  ProfRec r;
+  r.cls = c;
+  if (hipEventCreate(&r.e0) != hipSuccess) return;
+  if (hipEventCreate(&r.e1) != hipSuccess) { (void)hipEventDestroy(r.e0); return; }
+  (void)hipEventRecord(r.e0, s);
+  g_prof->push_back(r);
+  rec = reinterpret_cast<void*>(g_prof->size());  // index + 1 of this scope's record
+}
+ProfScope::~ProfScope() {
+  if (rec && g_prof) (void)hipEventRecord((*g_prof)[reinterpret_cast<size_t>(rec) - 1].e1, stream);
+}
+
+static const char* kProfNames[S4TF_PROF_CLASSES] = {
+    "conv_fwd_igemm", "conv_dgrad_igemm", "conv_wgrad_igemm", "wgrad_splitk_reduce", "dwconv_fwd",
+    "dwconv_dgrad", "dwconv_wgrad", "bn_stats", "bn_apply", "bn_vjp_reduce", "bn_vjp_apply", "pool",
+    "head", "sgd", "elementwise", "other"};
+
+// ---- validation ---------------------------------------------------------------------------------------
+static bool dtype_ok(int t) { return t == S4TF_F32 || t == S4TF_BF16; }
+static bool act_ok(int a) { return a == S4TF_ACT_NONE || a == S4TF_ACT_RELU || a == S4TF_ACT_RELU6; }
+static const long long kMaxElems = (1LL << 31) - 1;  // per-tensor element limit of the kernels' int math
+
+int check_conv_desc(const s4tf_conv_desc* d) {
+  if (!d) return fail(S4TF_ERR_NULL, "conv descriptor is NULL");
+  if (!dtype_ok(d->dtype) || !act_ok(d->act)) return fail(S4TF_ERR_DTYPE, "conv: bad dtype %d or act %d", d->dtype, d->act);
+  if (d->n <= 0 || d->h <= 0 || d->w <= 0 || d->c <= 0 || d->k <= 0 || d->r <= 0 || d->s <= 0 || d->stride <= 0 ||
+      d->pad < 0 || d->groups <= 0)
+    return fail(S4TF_ERR_SHAPE, "conv: sizes must be positive (pad >= 0)");
+  if (d->h + 2 * d->pad < d->r || d->w + 2 * d->pad < d->s) return fail(S4TF_ERR_SHAPE, "conv: filter larger than padded input");
+  if (d->c % d->groups || d->k % d->groups) return fail(S4TF_ERR_SHAPE, "conv: c and k must be multiples of groups");
+  if (d->groups != 1 && !(d->groups == d->c && d->k == d->c))
+    return fail(S4TF_ERR_UNSUPPORTED, "conv: groups must be 1 or c with k == c (depthwise)");
+  ConvGeom g = conv_geom(*d);
+  if ((long long)d->n * d->h * d->w * d->c > kMaxElems || (long long)d->n * g.P * g.Q * d->k > kMaxElems ||
+      (long long)d->r * d->s * d->c * d->k > kMaxElems)
+    return fail(S4TF_ERR_SHAPE, "conv: a tensor exceeds 2^31-1 elements");
+  return S4TF_OK;
+}
+int check_bn_desc(const s4tf_bn_desc* d) {
+  if (!d) return fail(S4TF_ERR_NULL, "bn descriptor is NULL");
+  if (!dtype_ok(d->dtype) || !act_ok(d->act)) return fail(S4TF_ERR_DTYPE, "bn: bad dtype %d or act %d", d->dtype, d->act);
+  if (d->n <= 0 || d->h <= 0 || d->w <= 0 || d->c <= 0) return fail(S4TF_ERR_SHAPE, "bn: sizes must be positive");
+  if (!(d->eps >= 0.f)) return fail(S4TF_ERR_SHAPE, "bn: eps must be >= 0");
+  if ((long long)d->n * d->h * d->w * d->c > kMaxElems) return fail(S4TF_ERR_SHAPE, "bn: tensor exceeds 2^31-1 elements");
+  return S4TF_OK;
+}
+int check_pool_desc(const s4tf_pool_desc* d) {
+  if (!d) return fail(S4TF_ERR_NULL, "pool descriptor is NULL");
+  if (!dtype_ok(d->dtype)) return fail(S4TF_ERR_DTYPE, "pool: bad dtype %d", d->dtype);
+  if (d->kind != S4TF_POOL_AVG2 && d->kind != S4TF_POOL_MAX3S2) return fail(S4TF_ERR_DTYPE, "pool: bad kind %d", d->kind);
+  if (d->n <= 0 || d->h <= 0 || d->w <= 0 || d->c <= 0) return fail(S4TF_ERR_SHAPE, "pool: sizes must be positive");
+  if (d->kind == S4TF_POOL_AVG2 && (d->h < 2 || d->w < 2)) return fail(S4TF_ERR_SHAPE, "avg pool needs h, w >= 2");
+  if ((long long)d->n * d->h * d->w * d->c > kMaxElems) return fail(S4TF_ERR_SHAPE, "pool: tensor exceeds 2^31-1 elements");
+  return S4TF_OK;
+}
+int check_head_desc(const s4tf_head_desc* d) {
+  if (!d) return fail(S4TF_ERR_NULL, "head descriptor is NULL");
+  if (!dtype_ok(d->dtype)) return fail(S4TF_ERR_DTYPE, "head: bad dtype %d", d->dtype);
+  if (d->n <= 0 || d->h <= 0 || d->w <= 0 || d->c <= 0 || d->classes <= 0) return fail(S4TF_ERR_SHAPE, "head: sizes must be positive");
+  if ((long long)d->n * d->h * d->w * d->c > kMaxElems || (long long)d->c * d->classes > kMaxElems)
+    return fail(S4TF_ERR_SHAPE, "head: tensor exceeds 2^31-1 elements");
+  return S4TF_OK;
+}
+
+static int need(const void* p, const char* name) {
+  if (!p) return fail(S4TF_ERR_NULL, "%s is NULL", name);
+  if (!aligned16(p)) return fail(S4TF_ERR_ALIGN, "%s is not 16-byte aligned", name);
+  return S4TF_OK;
+}
+static int opt(const void* p, const char* name) {
+  if (p && !aligned16(p)) return fail(S4TF_ERR_ALIGN, "%s is not 16-byte aligned", name);
+  return S4TF_OK;
+}
+#define CHECK(expr)                \
+  do {                             \
+    int rc_ = (expr);              \
+    if (rc_ != S4TF_OK) return rc_; \
+  } while (0)
+
+static int check_ws(const void* ws, size_t have, size_t want) {
+  if (want == 0) return S4TF_OK;
+  if (!ws) return fail(S4TF_ERR_WORKSPACE, "workspace of %zu bytes required", want);
+  if (!aligned16(ws)) return fail(S4TF_ERR_ALIGN, "workspace is not 16-byte aligned");
+  if (have < want) return fail(S4TF_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", have, want);
+  return S4TF_OK;
+}
+
+// ---- conv dispatch (dense vs depthwise) ---------------------------------------------------------------
+static size_t conv_vjp_ws_parts(const s4tf_conv_desc& d, size_t* dz_bytes) {
+  ConvGeom g = conv_geom(d);
+  size_t dz = d.act != S4TF_ACT_NONE ? align_up((size_t)g.N * g.P * g.Q * g.K * dtype_size(d.dtype), 256) : 0;
+  if (dz_bytes) *dz_bytes = dz;
+  size_t wg = d.groups == 1 ? igemm_wgrad_workspace(g, d.dtype) : dwconv_wgrad_workspace(g);
+  return dz + align_up(wg, 256);
+}
+
+static int conv_fwd_impl(const s4tf_conv_desc& d, const void* x, const void* w, const float* bias, void* y, hipStream_t st) {
+  ConvGeom g = conv_geom(d);
+  if (d.groups == 1) return igemm_fwd(g, d.dtype, x, w, bias, d.act, y, st);
+  return dwconv_fwd(g, d.dtype, x, w, bias, d.act, y, st);
+}
+// dz: cotangent after the activation pullback
+static int conv_vjp_impl(const s4tf_conv_desc& d, const void* x, const void* w, const void* dz, void* dx, float* dw,
+                         float* dbias, void* wg_ws, size_t wg_bytes, hipStream_t st) {
+  ConvGeom g = conv_geom(d);
+  if (dbias) CHECK(colsum(d.dtype, dz, (size_t)g.N * g.P * g.Q, g.K, dbias, st));
+  if (d.groups == 1) {
+    if (dx) CHECK(igemm_dgrad(g, d.dtype, dz, w, dx, d.accumulate_dx, st));
+    return igemm_wgrad(g, d.dtype, x, dz, dw, wg_ws, wg_bytes, st);
+  }
+  if (dx) CHECK(dwconv_dgrad(g, d.dtype, dz, w, dx, d.accumulate_dx, st));
+  return dwconv_wgrad(g, d.dtype, x, dz, dw, wg_ws, st);
+}
+
+// ---- whole-step planning -------------------------------------------------------------------------------
+struct TensorPlan {
+  int n, h, w, c;
+  size_t elems;
+  size_t act_off, grad_off;  // bytes into the workspace
+  int consumers;
+  int alias_of;  // flatten: shares buffers with this tensor, else -1
+  int root;      // the tensor whose buffers this one uses (itself unless an alias chain); 0 = the batch
+};
+struct NetPlan {
+  std::vector<TensorPlan> t;
+  std::vector<int64_t> poff, psize;  // 2 per op
+  std::vector<size_t> stat_off;      // per op: save_mean/invstd (BN)
+  size_t param_count;
+  size_t scratch_off, scratch_bytes, total_bytes;
+};
+
+static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
+  if (!net) return fail(S4TF_ERR_NULL, "net descriptor is NULL");
+  if (!net->ops || net->n_ops <= 0) return fail(S4TF_ERR_NULL, "net has no ops");
+  if (!dtype_ok(net->dtype)) return fail(S4TF_ERR_DTYPE, "net: bad dtype %d", net->dtype);
+  if (net->n <= 0 || net->h <= 0 || net->w <= 0 || net->c <= 0) return fail(S4TF_ERR_SHAPE, "net: batch sizes must be positive");
+  const int nops = net->n_ops;
+  const size_t es = dtype_size(net->dtype);
+  pl.t.assign(nops + 1, TensorPlan());
+  pl.poff.assign(2 * nops, 0);
+  pl.psize.assign(2 * nops, 0);
+  pl.stat_off.assign(nops, 0);
+  pl.t[0] = TensorPlan{net->n, net->h, net->w, net->c, (size_t)net->n * net->h * net->w * net->c, 0, 0, 0, -1, 0};
+  size_t pcount = 0, off = 0, scratch = 0;
+  auto add_param = [&](int op, int slot, size_t n) {
+    pl.poff[2 * op + slot] = (int64_t)pcount;
+    pl.psize[2 * op + slot] = (int64_t)n;
+    pcount += align_up(n, 8);
+  };
+  for (int i = 0; i < nops; ++i) {
+    const s4tf_op& op = net->ops[i];
+    if (op.in < 0 || op.in > i) return fail(S4TF_ERR_SHAPE, "op %d: input tensor %d is not an earlier tensor", i, op.in);
+    if ((i == nops - 1) != (op.kind == S4TF_OP_HEAD)) return fail(S4TF_ERR_SHAPE, "op %d: the head must be the last op and only there", i);
+    const TensorPlan in = pl.t[op.in];
+    pl.t[op.in].consumers++;
+    TensorPlan out = TensorPlan{in.n, in.h, in.w, in.c, 0, 0, 0, 0, -1, i + 1};
+    switch (op.kind) {
+      case S4TF_OP_CONV: {
+        s4tf_conv_desc d = {in.n, in.h, in.w, in.c, op.k, op.r, op.s, op.stride, op.pad, op.groups, net->dtype, op.act, 0};
+        int rc = check_conv_desc(&d);
+        if (rc != S4TF_OK) return rc;
+        ConvGeom g = conv_geom(d);
+        out.h = g.P; out.w = g.Q; out.c = op.k;
+        add_param(i, 0, (size_t)op.r * op.s * (in.c / op.groups) * op.k);
+        if (op.has_bias) add_param(i, 1, (size_t)op.k);
+        size_t ws = op.groups == 1 ? igemm_wgrad_workspace(g, net->dtype) : dwconv_wgrad_workspace(g);
+        if (ws > scratch) scratch = ws;
+        break;
+      }
+      case S4TF_OP_BN: {
+        s4tf_bn_desc d = {in.n, in.h, in.w, in.c, op.eps, op.act, net->dtype, 0};
+        int rc = check_bn_desc(&d);
+        if (rc != S4TF_OK) return rc;
+        if (in.root == 0) return fail(S4TF_ERR_UNSUPPORTED, "op %d: BatchNorm directly on the batch is not supported", i);
+        if (op.res >= 0) {
+          if (op.res > i) return fail(S4TF_ERR_SHAPE, "op %d: residual tensor %d is not an earlier tensor", i, op.res);
+          const TensorPlan& r = pl.t[op.res];
+          if (r.n != in.n || r.h != in.h || r.w != in.w || r.c != in.c) return fail(S4TF_ERR_SHAPE, "op %d: residual shape differs", i);
+          pl.t[op.res].consumers++;
+        }
+        add_param(i, 0, (size_t)in.c);
+        add_param(i, 1, (size_t)in.c);
+        size_t ws = bn_workspace((size_t)in.n * in.h * in.w, in.c);
+        if (ws > scratch) scratch = ws;
+        break;
+      }
+      case S4TF_OP_AVGPOOL2:
+      case S4TF_OP_MAXPOOL3S2: {
+        s4tf_pool_desc d = {in.n, in.h, in.w, in.c, op.kind == S4TF_OP_AVGPOOL2 ? S4TF_POOL_AVG2 : S4TF_POOL_MAX3S2, net->dtype, 0};
+        int rc = check_pool_desc(&d);
+        if (rc != S4TF_OK) return rc;
+        if (op.kind == S4TF_OP_AVGPOOL2) { out.h = in.h / 2; out.w = in.w / 2; }
+        else { out.h = (in.h - 1) / 2 + 1; out.w = (in.w - 1) / 2 + 1; }
+        break;
+      }
+      case S4TF_OP_FLATTEN:
+        out.c = in.h * in.w * in.c; out.h = 1; out.w = 1;
+        out.alias_of = op.in;
+        out.root = in.root;
+        break;
+      case S4TF_OP_HEAD: {
+        s4tf_head_desc d = {in.n, in.h, in.w, in.c, op.k, net->dtype};
+        int rc = check_head_desc(&d);
+        if (rc != S4TF_OK) return rc;
+        add_param(i, 0, (size_t)in.c * op.k);
+        add_param(i, 1, (size_t)op.k);
+        size_t ws = head_workspace(d);
+        if (ws > scratch) scratch = ws;
+        out.h = 1; out.w = 1; out.c = op.k;
+        break;
+      }
+      default:
+        return fail(S4TF_ERR_DTYPE, "op %d: unknown kind %d", i, op.kind);
+    }
+    out.elems = (size_t)out.n * out.h * out.w * out.c;
+    pl.t[i + 1] = out;
+  }
+  // consumers: every tensor except the head's output needs one; BN inputs and flatten inputs exactly one
+  for (int i = 0; i < nops; ++i) {
+    const s4tf_op& op = net->ops[i];
+    if (i + 1 < nops && pl.t[i + 1].consumers == 0) return fail(S4TF_ERR_SHAPE, "tensor %d (output of op %d) has no consumer", i + 1, i);
+    if ((op.kind == S4TF_OP_BN || op.kind == S4TF_OP_FLATTEN) && pl.t[op.in].root != 0 && pl.t[op.in].consumers != 1)
+      return fail(S4TF_ERR_UNSUPPORTED, "op %d: the input of a BN/flatten op must have no other consumer", i);
+  }
+  // workspace: activations, cotangents, BN statistics, shared scratch
+  for (int i = 1; i < nops; ++i) {  // tensor nops is the head's (virtual) output
+    TensorPlan& t = pl.t[i];
+    if (t.root != i) {  // an alias: buffers of its root (none if the root is the batch)
+      t.act_off = pl.t[t.root].act_off;
+      t.grad_off = pl.t[t.root].grad_off;
+      continue;
+    }
+    t.act_off = off; off += align_up(t.elems * es, 256);
+    t.grad_off = off; off += align_up(t.elems * es, 256);
+  }
+  for (int i = 0; i < nops; ++i)
+    if (net->ops[i].kind == S4TF_OP_BN) {
+      pl.stat_off[i] = off;
+      off += align_up((size_t)2 * pl.t[net->ops[i].in].c * sizeof(float), 256);
+    }
+  pl.scratch_off = off;
+  pl.scratch_bytes = align_up(scratch, 256);
+  pl.total_bytes = off + pl.scratch_bytes;
+  pl.param_count = pcount;
+  return S4TF_OK;
+}
+
+}  // namespace s4tf
+
+using namespace s4tf;
+
+extern "C" {
+
+const char* s4tf_last_error(void) { return g_err; }
+
+// ---- conv ----------------------------------------------------------------------------------------------
+size_t s4tf_conv2d_fwd_workspace_bytes(const s4tf_conv_desc* d) {
+  clear_error();
+  (void)check_conv_desc(d);
+  return 0;
+}
+size_t s4tf_conv2d_vjp_workspace_bytes(const s4tf_conv_desc* d) {
+  clear_error();
+  if (check_conv_desc(d) != S4TF_OK) return 0;
+  return conv_vjp_ws_parts(*d, nullptr);
+}
+
+int s4tf_conv2d_fwd(const s4tf_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  (void)workspace; (void)workspace_bytes;
+  CHECK(check_conv_desc(d));
+  CHECK(need(x, "x")); CHECK(need(w, "w")); CHECK(need(y, "y")); CHECK(opt(bias, "bias"));
+  return conv_fwd_impl(*d, x, w, bias, y, (hipStream_t)stream);
+}
+
+int s4tf_conv2d_vjp(const s4tf_conv_desc* d, const void* x, const void* w, const void* y, const void* dy,
+                    void* dx, float* dw, float* dbias, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  CHECK(check_conv_desc(d));
+  CHECK(need(x, "x")); CHECK(need(w, "w")); CHECK(need(dy, "dy")); CHECK(need(dw, "dw"));
+  CHECK(opt(dx, "dx")); CHECK(opt(dbias, "dbias"));
+  if (d->act != S4TF_ACT_NONE) CHECK(need(y, "y (required when act != NONE)"));
+  size_t dz_bytes = 0;
+  size_t want = conv_vjp_ws_parts(*d, &dz_bytes);
+  CHECK(check_ws(workspace, workspace_bytes, want));
+  hipStream_t st = (hipStream_t)stream;
+  const void* dz = dy;
+  char* wsb = static_cast<char*>(workspace);
+  if (d->act != S4TF_ACT_NONE) {
+    ConvGeom g = conv_geom(*d);
+    CHECK(act_vjp(d->dtype, d->act, y, dy, wsb, (size_t)g.N * g.P * g.Q * g.K, st));
+    dz = wsb;
+  }
+  return conv_vjp_impl(*d, x, w, dz, dx, dw, dbias, wsb ? wsb + dz_bytes : nullptr, want - dz_bytes, st);
+}
+
+// ---- batch norm ------------------------------------------------------------------------------------------
+size_t s4tf_bn_relu_workspace_bytes(const s4tf_bn_desc* d) {
+  clear_error();
+  if (check_bn_desc(d) != S4TF_OK) return 0;
+  return bn_workspace((size_t)d->n * d->h * d->w, d->c);
+}
+int s4tf_bn_relu_fwd(const s4tf_bn_desc* d, const void* x, const void* residual, const float* gamma,
+                     const float* beta, void* y, float* save_mean, float* save_invstd, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  clear_error();
+  CHECK(check_bn_desc(d));
+  CHECK(need(x, "x")); CHECK(need(gamma, "gamma")); CHECK(need(beta, "beta")); CHECK(need(y, "y"));
+  CHECK(need(save_mean, "save_mean")); CHECK(need(save_invstd, "save_invstd")); CHECK(opt(residual, "residual"));
+  CHECK(check_ws(workspace, workspace_bytes, bn_workspace((size_t)d->n * d->h * d->w, d->c)));
+  return bn_fwd(*d, x, residual, gamma, beta, y, save_mean, save_invstd, workspace, (hipStream_t)stream);
+}
+int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const float* gamma,
+                     const float* save_mean, const float* save_invstd, const void* dy, void* dx, void* dresidual,
+                     float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  CHECK(check_bn_desc(d));
+  CHECK(need(x, "x")); CHECK(need(gamma, "gamma")); CHECK(need(save_mean, "save_mean"));
+  CHECK(need(save_invstd, "save_invstd")); CHECK(need(dy, "dy")); CHECK(need(dx, "dx"));
+  CHECK(need(dgamma, "dgamma")); CHECK(need(dbeta, "dbeta")); CHECK(opt(dresidual, "dresidual"));
+  if (d->act != S4TF_ACT_NONE) CHECK(need(y, "y (required when act != NONE)"));
+  CHECK(check_ws(workspace, workspace_bytes, bn_workspace((size_t)d->n * d->h * d->w, d->c)));
+  return bn_vjp(*d, x, y, gamma, save_mean, save_invstd, dy, dx, dresidual, dgamma, dbeta, workspace, (hipStream_t)stream);
+}
+
+// ---- pooling ----------------------------------------------------------------------------------------------
+int s4tf_pool2d_fwd(const s4tf_pool_desc* d, const void* x, void* y, void* stream) {
+  clear_error();
+  CHECK(check_pool_desc(d));
+  CHECK(need(x, "x")); CHECK(need(y, "y"));
+  return pool_fwd(*d, x, y, (hipStream_t)stream);
+}
+int s4tf_pool2d_vjp(const s4tf_pool_desc* d, const void* x, const void* dy, void* dx, void* stream) {
+  clear_error();
+  CHECK(check_pool_desc(d));
+  CHECK(need(dy, "dy")); CHECK(need(dx, "dx"));
+  if (d->kind == S4TF_POOL_MAX3S2) CHECK(need(x, "x (required for max pool)"));
+  return pool_vjp(*d, x, dy, dx, (hipStream_t)stream);
+}
+
+// ---- head ---------------------------------------------------------------------------------------------------
+size_t s4tf_pool_dense_xent_workspace_bytes(const s4tf_head_desc* d) {
+  clear_error();
+  if (check_head_desc(d) != S4TF_OK) return 0;
+  return head_workspace(*d);
+}
+int s4tf_pool_dense_xent_fwd_vjp(const s4tf_head_desc* d, const void* x, const float* W, const float* b,
+                                 const int32_t* labels, float* loss, void* dx, float* dW, float* db, float* logits,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  CHECK(check_head_desc(d));
+  CHECK(need(x, "x")); CHECK(need(W, "W")); CHECK(need(b, "b")); CHECK(need(labels, "labels"));
+  CHECK(need(loss, "loss")); CHECK(need(dW, "dW")); CHECK(need(db, "db")); CHECK(opt(dx, "dx")); CHECK(opt(logits, "logits"));
+  CHECK(check_ws(workspace, workspace_bytes, head_workspace(*d)));
+  return head_fwd_vjp(*d, x, W, b, labels, loss, dx, dW, db, logits, workspace, (hipStream_t)stream);
+}
+
+// ---- optimizer ------------------------------------------------------------------------------------------------
+int s4tf_sgd_momentum(size_t count, float* param, float* velocity, const float* grad, void* param_lowp, float lr,
+                      float momentum, void* stream) {
+  clear_error();
+  if (count == 0) return S4TF_OK;
+  CHECK(need(param, "param")); CHECK(need(velocity, "velocity")); CHECK(need(grad, "grad")); CHECK(opt(param_lowp, "param_lowp"));
+  return sgd(count, param, velocity, grad, param_lowp, lr, momentum, (hipStream_t)stream);
+}
+
+// ---- whole step ---------------------------------------------------------------------------------------------------
+size_t s4tf_net_param_count(const s4tf_net_desc* net) {
+  clear_error();
+  NetPlan pl;
+  if (plan_net(net, pl) != S4TF_OK) return 0;
+  return pl.param_count;
+}
+int s4tf_net_param_layout(const s4tf_net_desc* net, int64_t* offsets, int64_t* sizes) {
+  clear_error();
+  NetPlan pl;
+  CHECK(plan_net(net, pl));
+  for (size_t i = 0; i < pl.poff.size(); ++i) {
+    if (offsets) offsets[i] = pl.poff[i];
+    if (sizes) sizes[i] = pl.psize[i];
+  }
+  return S4TF_OK;
+}
+size_t s4tf_train_step_workspace_bytes(const s4tf_net_desc* net) {
+  clear_error();
+  NetPlan pl;
+  if (plan_net(net, pl) != S4TF_OK) return 0;
+  return pl.total_bytes;
+}
+
+int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_batch* batch, float lr) {
+  clear_error();
+  NetPlan pl;
+  CHECK(plan_net(net, pl));
+  if (!params || !batch) return fail(S4TF_ERR_NULL, "params or batch is NULL");
+  CHECK(need(params->master, "params.master")); CHECK(need(params->velocity, "params.velocity"));
+  CHECK(need(params->grad, "params.grad")); CHECK(opt(params->lowp, "params.lowp"));
+  const bool bf16 = net->dtype == S4TF_BF16;
+  if (bf16 && !params->lowp) return fail(S4TF_ERR_NULL, "params.lowp is required for a bf16 net");
+  if (params->count != pl.param_count)
+    return fail(S4TF_ERR_SHAPE, "params.count is %zu, the net needs %zu", params->count, pl.param_count);
+  CHECK(need(batch->x, "batch.x")); CHECK(need(batch->labels, "batch.labels")); CHECK(need(batch->loss, "batch.loss"));
+  CHECK(check_ws(batch->workspace, batch->workspace_bytes, pl.total_bytes));
+
+  hipStream_t st = (hipStream_t)batch->stream;
+  char* ws = static_cast<char*>(batch->workspace);
+  const int nops = net->n_ops;
+  const int dt = net->dtype;
+  void* scratch = ws + pl.scratch_off;
+  auto act_ptr = [&](int t) -> const void* { return pl.t[t].root == 0 ? batch->x : (const void*)(ws + pl.t[t].act_off); };
+  auto out_ptr = [&](int t) -> void* { return ws + pl.t[t].act_off; };
+  auto grad_ptr = [&](int t) -> void* { return ws + pl.t[t].grad_off; };
+  auto conv_w = [&](int op) -> const void* {
+    return bf16 ? (const void*)(static_cast<bf16_t*>(params->lowp) + pl.poff[2 * op])
+                : (const void*)(params->master + pl.poff[2 * op]);
+  };
+  auto conv_desc = [&](int i, int accumulate) {
+    const s4tf_op& op = net->ops[i];
+    const TensorPlan& in = pl.t[op.in];
+    s4tf_conv_desc d = {in.n, in.h, in.w, in.c, op.k, op.r, op.s, op.stride, op.pad, op.groups, dt, op.act, accumulate};
+    return d;
+  };
+
+  // ---- forward ----
+  for (int i = 0; i < nops - 1; ++i) {
+    const s4tf_op& op = net->ops[i];
+    const TensorPlan& in = pl.t[op.in];
+    switch (op.kind) {
+      case S4TF_OP_CONV: {
+        s4tf_conv_desc d = conv_desc(i, 0);
+        const float* bias = op.has_bias ? params->master + pl.poff[2 * i + 1] : nullptr;
+        CHECK(conv_fwd_impl(d, act_ptr(op.in), conv_w(i), bias, out_ptr(i + 1), st));
+        break;
+      }
+      case S4TF_OP_BN: {
+        s4tf_bn_desc d = {in.n, in.h, in.w, in.c, op.eps, op.act, dt, 0};
+        float* stats = reinterpret_cast<float*>(ws + pl.stat_off[i]);
+        CHECK(bn_fwd(d, act_ptr(op.in), op.res >= 0 ? act_ptr(op.res) : nullptr, params->master + pl.poff[2 * i],
+                     params->master + pl.poff[2 * i + 1], out_ptr(i + 1), stats, stats + in.c, scratch, st));
+        break;
+      }
+      case S4TF_OP_AVGPOOL2:
+      case S4TF_OP_MAXPOOL3S2: {
+        s4tf_pool_desc d = {in.n, in.h, in.w, in.c, op.kind == S4TF_OP_AVGPOOL2 ? S4TF_POOL_AVG2 : S4TF_POOL_MAX3S2, dt, 0};
+        CHECK(pool_fwd(d, act_ptr(op.in), out_ptr(i + 1), st));
+        break;
+      }
+      default:
+        break;  // flatten: a reinterpretation
+    }
+  }
+  auto resolve = [&](int t) -> int { return pl.t[t].root; };
+
+  // ---- head: loss and the first cotangent ----
+  std::vector<char> written(nops + 1, 0);
+  {
+    const s4tf_op& op = net->ops[nops - 1];
+    const TensorPlan& in = pl.t[op.in];
+    s4tf_head_desc d = {in.n, in.h, in.w, in.c, op.k, dt};
+    const int src = resolve(op.in);
+    void* dx = src == 0 ? nullptr : grad_ptr(src);
+    CHECK(head_fwd_vjp(d, act_ptr(op.in), params->master + pl.poff[2 * (nops - 1)],
+                       params->master + pl.poff[2 * (nops - 1) + 1], batch->labels, batch->loss, dx,
+                       params->grad + pl.poff[2 * (nops - 1)], params->grad + pl.poff[2 * (nops - 1) + 1], nullptr,
+                       scratch, st));
+    written[src] = 1;
+  }
+  // ---- pullbacks in reverse op order ----
+  for (int i = nops - 2; i >= 0; --i) {
+    const s4tf_op& op = net->ops[i];
+    const TensorPlan& in = pl.t[op.in];
+    const int src = resolve(op.in);
+    const bool want_dx = src != 0;
+    void* dy = grad_ptr(i + 1);
+    switch (op.kind) {
+      case S4TF_OP_CONV: {
+        s4tf_conv_desc d = conv_desc(i, written[src] ? 1 : 0);
+        if (op.act != S4TF_ACT_NONE)  // in place: dy is not needed once dz exists
+          CHECK(act_vjp(dt, op.act, out_ptr(i + 1), dy, dy, pl.t[i + 1].elems, st));
+        CHECK(conv_vjp_impl(d, act_ptr(src), conv_w(i), dy, want_dx ? grad_ptr(src) : nullptr,
+                            params->grad + pl.poff[2 * i], op.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr,
+                            scratch, pl.scratch_bytes, st));
+        written[src] = 1;
+        break;
+      }
+      case S4TF_OP_BN: {
+        const int rsrc = op.res >= 0 ? resolve(op.res) : -1;
+        s4tf_bn_desc d = {in.n, in.h, in.w, in.c, op.eps, op.act, dt, (rsrc > 0 && written[rsrc]) ? 1 : 0};
+        float* stats = reinterpret_cast<float*>(ws + pl.stat_off[i]);
+        void* dxb = grad_ptr(src);  // src != 0: checked when the net was planned
+        void* dres = rsrc > 0 ? grad_ptr(rsrc) : nullptr;
+        CHECK(bn_vjp(d, act_ptr(src), out_ptr(i + 1), params->master + pl.poff[2 * i], stats, stats + in.c, dy, dxb,
+                     dres, params->grad + pl.poff[2 * i], params->grad + pl.poff[2 * i + 1], scratch, st));
+        written[src] = 1;
+        if (rsrc > 0) written[rsrc] = 1;
+        break;
+      }
+      case S4TF_OP_AVGPOOL2:
+      case S4TF_OP_MAXPOOL3S2: {
+        if (!want_dx) break;
+        s4tf_pool_desc d = {in.n, in.h, in.w, in.c, op.kind == S4TF_OP_AVGPOOL2 ? S4TF_POOL_AVG2 : S4TF_POOL_MAX3S2, dt,
+                            written[src] ? 1 : 0};
+        CHECK(pool_vjp(d, act_ptr(src), dy, grad_ptr(src), st));
+        written[src] = 1;
+        break;
+      }
+      default:  // flatten shares its buffers (and its cotangent) with its input
+        break;
+    }
+  }
+  // ---- optimizer: one launch over the whole arena ----
+  return sgd(params->count, params->master, params->velocity, params->grad, bf16 ? params->lowp : nullptr, lr,
+             net->momentum, st);
+}
+
+// ---- measurement hook ------------------------------------------------------------------------------------------------
+int s4tf_profile_enable(int on) {
+  g_prof_on = on != 0;
+  return S4TF_OK;
+}
+int s4tf_profile_collect(double* ms, int64_t* launches) {
+  clear_error();
+  if (!ms || !launches) return fail(S4TF_ERR_NULL, "ms or launches is NULL");
+  for (int i = 0; i < S4TF_PROF_CLASSES; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  if (!g_prof) return S4TF_OK;
+  int rc = S4TF_OK;
+  for (ProfRec& r : *g_prof) {
+    float t = 0.f;
+    if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&t, r.e0, r.e1) != hipSuccess)
+      rc = fail(S4TF_ERR_DEVICE, "profile: event read failed");
+    else if (r.cls >= 0 && r.cls < S4TF_PROF_CLASSES) { ms[r.cls] += (double)t; launches[r.cls] += 1; }
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  g_prof->clear();
+  return rc;
+}
+const char* s4tf_profile_class_name(int cls) {
+  return (cls >= 0 && cls < S4TF_PROF_CLASSES) ? kProfNames[cls] : "";
+}
+
+}  // extern "C"

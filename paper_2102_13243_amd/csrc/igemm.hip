@@ -1,0 +1,651 @@
+// Dense (groups == 1) convolution as implicit GEMM on the gfx950 matrix cores.
+//
+// The three passes of a convolution are each one GEMM  D[i][j] = sum_k A[i][k] * B[j][k]:
+//   forward  y [m=(n,p,q)][ko]      A = im2col(x)      k = (r,s,c)    B[ko][k]  = w[r,s,c,ko]
+//   dgrad    dx[m=(n,h,w)][c]       A = gather(dy)     k = (r,s,ko)   B[c][k]   = w[r,s,c,ko]
+//   wgrad    dw[i=(r,s,c)][ko]      A = im2col(x)^T    k = (n,p,q)    B[ko][k]  = dy[n,p,q,ko]
+// (the op and its pullback in the sense of the paper's Section 2.1; layouts NHWC / RSCK).
+// Nothing is materialised: the loaders compute addresses on the fly, stage a BM x BK and a
+// BN x BK tile in LDS (k contiguous, padded rows, double buffered) and four wavefronts of 64
+// lanes each own a 64x64 sub-tile made of 2x2 MFMA 32x32 blocks.  bf16 uses
+// v_mfma_f32_32x32x16_bf16 (8 k-values per lane), fp32 uses v_mfma_f32_32x32x2_f32.
+// Operands whose memory is contiguous along the GEMM row instead of along k (filters in the
+// forward pass, both operands of wgrad) are transposed in registers on their way into LDS.
+#include "s4tf_internal.h"
+
+namespace s4tf {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+enum { PASS_FWD = 0, PASS_DGRAD = 1, PASS_WGRAD = 2 };
+constexpr int NT = 256;      // threads per block: 4 wavefronts
+constexpr int NUM_XCD = 8;   // workgroup ids are dealt round-robin to the 8 XCDs
+
+template <typename T> struct Cfg;
+template <> struct Cfg<float> { static constexpr int VEC = 4, BK = 16, PAD = 1; };
+template <> struct Cfg<bf16_t> { static constexpr int VEC = 8, BK = 32, PAD = 8; };
+
+struct Args {
+  ConvGeom g;
+  const void* a;
+  const void* b;
+  void* out;
+  const float* bias;
+  int Mg, Ng, Kg;
+  int act, accumulate, simple;
+  int nk, nk_per_split;
+  long long split_stride;
+  int tiles_m, tiles_n, tiles_per_xcd;
+};
+
+__device__ inline uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ inline uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
+
+// ---- element index of operand A / B for (row, k), or -1 when it is padding ------------------
+template <int PASS> __device__ inline long long a_index(const ConvGeom& g, int row, int kk) {
+  if (PASS == PASS_FWD) {
+    int q = row % g.Q, t = row / g.Q, p = t % g.P, n = t / g.P;
+    int c = kk % g.C, t2 = kk / g.C, s = t2 % g.S, r = t2 / g.S;
+    int h = p * g.stride + r - g.pad, w = q * g.stride + s - g.pad;
+    if (h < 0 || h >= g.H || w < 0 || w >= g.W) return -1;
+    return (((long long)n * g.H + h) * g.W + w) * g.C + c;
+  } else if (PASS == PASS_DGRAD) {
+    int w = row % g.W, t = row / g.W, h = t % g.H, n = t / g.H;
+    int ko = kk % g.K, t2 = kk / g.K, s = t2 % g.S, r = t2 / g.S;
+    int hp = h + g.pad - r, wp = w + g.pad - s;
+    if (hp < 0 || wp < 0) return -1;
+    int p = hp / g.stride, q = wp / g.stride;
+    if (p * g.stride != hp || q * g.stride != wp || p >= g.P || q >= g.Q) return -1;
+    return (((long long)n * g.P + p) * g.Q + q) * g.K + ko;
+  } else {
+    int c = row % g.C, t2 = row / g.C, s = t2 % g.S, r = t2 / g.S;
+    int q = kk % g.Q, t = kk / g.Q, p = t % g.P, n = t / g.P;
+    int h = p * g.stride + r - g.pad, w = q * g.stride + s - g.pad;
+    if (h < 0 || h >= g.H || w < 0 || w >= g.W) return -1;
+    return (((long long)n * g.H + h) * g.W + w) * g.C + c;
+  }
+}
+template <int PASS> __device__ inline long long b_index(const ConvGeom& g, int col, int kk) {
+  if (PASS == PASS_DGRAD) {
+    int ko = kk % g.K, rs = kk / g.K;
+    return ((long long)rs * g.C + col) * g.K + ko;
+  }
+  return (long long)kk * g.K + col;  // filters as [(r,s,c)][ko], dy as [(n,p,q)][ko]
+}
+
+// ---- LDS tile stores ---------------------------------------------------------------------------
+template <typename T, int STRIDE> __device__ inline void store_kvec(T* tile, int row, int k0, uint4 v) {
+  if constexpr (sizeof(T) == 2) {
+    *reinterpret_cast<uint4*>(&tile[row * STRIDE + k0]) = v;
+  } else {
+    uint32_t* p = reinterpret_cast<uint32_t*>(&tile[row * STRIDE + k0]);
+    p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w;
+  }
+}
+__device__ inline uint32_t dword_of(const uint4& v, int i) {
+  return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
+}
+__device__ inline uint32_t half_of(const uint4& v, int e) {  // 16-bit element e of 8
+  uint32_t d = dword_of(v, e >> 1);
+  return (e & 1) ? (d >> 16) : (d & 0xffffu);
+}
+
+// ---- loaders --------------------------------------------------------------------------------
+// K-contiguous sources: a thread owns one 16-byte chunk column (kc) of ROWS/64 rows.
+template <typename T, int ROWS> struct KLoaderBase {
+  static constexpr int VEC = Cfg<T>::VEC, BK = Cfg<T>::BK, STRIDE = BK + Cfg<T>::PAD;
+  static constexpr int CPR = BK / VEC;       // chunks per row
+  static constexpr int RPP = NT / CPR;       // rows per pass
+  static constexpr int NP = (ROWS + RPP - 1) / RPP;
+  uint4 v[NP];
+  __device__ void store(T* tile, int tid) const {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      int row = tid / CPR + i * RPP;
+      if (ROWS % RPP == 0 || row < ROWS) store_kvec<T, STRIDE>(tile, row, (tid % CPR) * VEC, v[i]);
+    }
+  }
+};
+
+// forward A: rows are output pixels (n,p,q), k = (r,s,c)
+template <typename T, int ROWS> struct FwdALoader : KLoaderBase<T, ROWS> {
+  typedef KLoaderBase<T, ROWS> B_;
+  const T* x;
+  long long base[B_::NP];
+  int h0[B_::NP], w0[B_::NP];
+  bool rv[B_::NP];
+  int r, s, c;
+  __device__ void init(const Args& a, int row0, int tid, int kt0) {
+    x = static_cast<const T*>(a.a);
+    const ConvGeom& g = a.g;
+#pragma unroll
+    for (int i = 0; i < B_::NP; ++i) {
+      int row = row0 + tid / B_::CPR + i * B_::RPP;
+      rv[i] = row < a.Mg && (ROWS % B_::RPP == 0 || tid / B_::CPR + i * B_::RPP < ROWS);
+      int q = row % g.Q, t = row / g.Q, p = t % g.P, n = t / g.P;
+      base[i] = (long long)n * g.H * g.W * g.C;
+      h0[i] = p * g.stride - g.pad;
+      w0[i] = q * g.stride - g.pad;
+    }
+    int kk = kt0 * B_::BK + (tid % B_::CPR) * B_::VEC;
+    c = kk % g.C;
+    int t2 = kk / g.C;
+    s = t2 % g.S;
+    r = t2 / g.S;
+  }
+  __device__ void load(const Args& a) {
+    const ConvGeom& g = a.g;
+#pragma unroll
+    for (int i = 0; i < B_::NP; ++i) {
+      int h = h0[i] + r, w = w0[i] + s;
+      bool ok = rv[i] && r < g.R && h >= 0 && h < g.H && w >= 0 && w < g.W;
+      this->v[i] = ok ? ldg16(x + base[i] + ((long long)h * g.W + w) * g.C + c) : zero16();
+    }
+    c += B_::BK;
+    while (c >= g.C) {
+      c -= g.C;
+      if (++s == g.S) { s = 0; ++r; }
+    }
+  }
+};
+
+// dgrad A: rows are input pixels (n,h,w), k = (r,s,ko); gathers dy
+template <typename T, int ROWS> struct DgradALoader : KLoaderBase<T, ROWS> {
+  typedef KLoaderBase<T, ROWS> B_;
+  const T* dy;
+  long long base[B_::NP];
+  int hp0[B_::NP], wp0[B_::NP];
+  bool rv[B_::NP];
+  int r, s, ko;
+  __device__ void init(const Args& a, int row0, int tid, int kt0) {
+    dy = static_cast<const T*>(a.a);
+    const ConvGeom& g = a.g;
+#pragma unroll
+    for (int i = 0; i < B_::NP; ++i) {
+      int row = row0 + tid / B_::CPR + i * B_::RPP;
+      rv[i] = row < a.Mg && (ROWS % B_::RPP == 0 || tid / B_::CPR + i * B_::RPP < ROWS);
+      int w = row % g.W, t = row / g.W, h = t % g.H, n = t / g.H;
+      base[i] = (long long)n * g.P * g.Q * g.K;
+      hp0[i] = h + g.pad;
+      wp0[i] = w + g.pad;
+    }
+    int kk = kt0 * B_::BK + (tid % B_::CPR) * B_::VEC;
+    ko = kk % g.K;
+    int t2 = kk / g.K;
+    s = t2 % g.S;
+    r = t2 / g.S;
+  }
+  __device__ void load(const Args& a) {
+    const ConvGeom& g = a.g;
+#pragma unroll
+    for (int i = 0; i < B_::NP; ++i) {
+      int hp = hp0[i] - r, wp = wp0[i] - s;
+      bool ok = rv[i] && r < g.R && hp >= 0 && wp >= 0;
+      int p, q;
+      if (g.stride == 1) {
+        p = hp; q = wp;
+      } else if (g.stride == 2) {
+        ok = ok && (((hp | wp) & 1) == 0);
+        p = hp >> 1; q = wp >> 1;
+      } else {
+        p = hp / g.stride; q = wp / g.stride;
+        ok = ok && p * g.stride == hp && q * g.stride == wp;
+      }
+      ok = ok && p < g.P && q < g.Q;
+      this->v[i] = ok ? ldg16(dy + base[i] + ((long long)p * g.Q + q) * g.K + ko) : zero16();
+    }
+    ko += B_::BK;
+    while (ko >= g.K) {
+      ko -= g.K;
+      if (++s == g.S) { s = 0; ++r; }
+    }
+  }
+};
+
+// dgrad B: rows are input channels c, k = (r,s,ko); filters are contiguous along ko
+template <typename T, int ROWS> struct DgradBLoader : KLoaderBase<T, ROWS> {
+  typedef KLoaderBase<T, ROWS> B_;
+  const T* w;
+  int cidx[B_::NP];
+  bool rv[B_::NP];
+  int rs, ko;
+  __device__ void init(const Args& a, int row0, int tid, int kt0) {
+    w = static_cast<const T*>(a.b);
+#pragma unroll
+    for (int i = 0; i < B_::NP; ++i) {
+      cidx[i] = row0 + tid / B_::CPR + i * B_::RPP;
+      rv[i] = cidx[i] < a.Ng && (ROWS % B_::RPP == 0 || tid / B_::CPR + i * B_::RPP < ROWS);
+    }
+    int kk = kt0 * B_::BK + (tid % B_::CPR) * B_::VEC;
+    ko = kk % a.g.K;
+    rs = kk / a.g.K;
+  }
+  __device__ void load(const Args& a) {
+    const ConvGeom& g = a.g;
+#pragma unroll
+    for (int i = 0; i < B_::NP; ++i) {
+      bool ok = rv[i] && rs < g.R * g.S;
+      this->v[i] = ok ? ldg16(w + ((long long)rs * g.C + cidx[i]) * g.K + ko) : zero16();
+    }
+    ko += B_::BK;
+    while (ko >= g.K) { ko -= g.K; ++rs; }
+  }
+};
+
+// Row-contiguous sources.  A thread owns VEC adjacent rows at KP consecutive k positions and
+// scatters them into the k-contiguous LDS tile (bf16: packs KP values per row into one store).
+template <typename T, int ROWS> struct RLoaderBase {
+  static constexpr int VEC = Cfg<T>::VEC, BK = Cfg<T>::BK, STRIDE = BK + Cfg<T>::PAD;
+  static constexpr int RC = ROWS / VEC;                       // row chunks
+  static constexpr int KG = (NT / RC) < BK ? (NT / RC) : BK;  // k groups
+  static constexpr int KP = BK / KG;                          // k positions per thread
+  static_assert(KP == 1 || KP == 2 || KP == 4, "unsupported tile shape");
+  uint4 v[KP];
+  __device__ static bool active(int tid) { return tid < RC * KG; }
+  __device__ static int kgroup(int tid) { return tid % KG; }
+  __device__ static int rchunk(int tid) { return tid / KG; }
+  __device__ void store(T* tile, int tid) const {
+    if (!active(tid)) return;
+    int row0 = rchunk(tid) * VEC, k0 = kgroup(tid) * KP;
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        T* dst = &tile[(row0 + e) * STRIDE + k0];
+        if constexpr (KP == 1) {
+          *dst = (T)half_of(v[0], e);
+        } else if constexpr (KP == 2) {
+          *reinterpret_cast<uint32_t*>(dst) = half_of(v[0], e) | (half_of(v[1], e) << 16);
+        } else {
+          uint2 o;
+          o.x = half_of(v[0], e) | (half_of(v[1], e) << 16);
+          o.y = half_of(v[2], e) | (half_of(v[3], e) << 16);
+          *reinterpret_cast<uint2*>(dst) = o;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < KP; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          *reinterpret_cast<uint32_t*>(&tile[(row0 + e) * STRIDE + k0 + u]) = dword_of(v[u], e);
+    }
+  }
+};
+
+// plain [k][ld] matrix: filters in the forward pass ([(r,s,c)][ko]) and dy in wgrad ([(n,p,q)][ko])
+template <typename T, int ROWS> struct PlainRLoader : RLoaderBase<T, ROWS> {
+  typedef RLoaderBase<T, ROWS> B_;
+  const T* src;
+  int j0, kk;
+  bool rv;
+  __device__ void init(const Args& a, int row0, int tid, int kt0) {
+    src = static_cast<const T*>(a.b);
+    j0 = row0 + B_::rchunk(tid) * B_::VEC;
+    rv = B_::active(tid) && j0 < a.Ng;
+    kk = kt0 * B_::BK + B_::kgroup(tid) * B_::KP;
+  }
+  __device__ void load(const Args& a) {
+#pragma unroll
+    for (int u = 0; u < B_::KP; ++u) {
+      bool ok = rv && kk + u < a.Kg;
+      this->v[u] = ok ? ldg16(src + (long long)(kk + u) * a.g.K + j0) : zero16();
+    }
+    kk += B_::BK;
+  }
+};
+
+// wgrad A: rows are (r,s,c) (contiguous along c), k = output pixel (n,p,q); gathers x
+template <typename T, int ROWS> struct WgradALoader : RLoaderBase<T, ROWS> {
+  typedef RLoaderBase<T, ROWS> B_;
+  const T* x;
+  int r, s, c0;
+  bool rv;
+  int pn[B_::KP], pp[B_::KP], pq[B_::KP];
+  int m;  // pixel index of k position 0
+  __device__ void init(const Args& a, int row0, int tid, int kt0) {
+    x = static_cast<const T*>(a.a);
+    const ConvGeom& g = a.g;
+    int i0 = row0 + B_::rchunk(tid) * B_::VEC;
+    rv = B_::active(tid) && i0 < a.Mg;
+    c0 = i0 % g.C;
+    int t2 = i0 / g.C;
+    s = t2 % g.S;
+    r = t2 / g.S;
+    m = kt0 * B_::BK + B_::kgroup(tid) * B_::KP;
+#pragma unroll
+    for (int u = 0; u < B_::KP; ++u) {
+      int mm = m + u;
+      pq[u] = mm % g.Q;
+      int t = mm / g.Q;
+      pp[u] = t % g.P;
+      pn[u] = t / g.P;
+    }
+  }
+  __device__ void load(const Args& a) {
+    const ConvGeom& g = a.g;
+#pragma unroll
+    for (int u = 0; u < B_::KP; ++u) {
+      bool ok = rv && m + u < a.Kg;
+      long long idx;
+      if (a.simple) {
+        idx = (long long)(m + u) * g.C + c0;
+      } else {
+        int h = pp[u] * g.stride + r - g.pad, w = pq[u] * g.stride + s - g.pad;
+        ok = ok && h >= 0 && h < g.H && w >= 0 && w < g.W;
+        idx = (((long long)pn[u] * g.H + h) * g.W + w) * g.C + c0;
+        pq[u] += B_::BK;
+        while (pq[u] >= g.Q) {
+          pq[u] -= g.Q;
+          if (++pp[u] == g.P) { pp[u] = 0; ++pn[u]; }
+        }
+      }
+      this->v[u] = ok ? ldg16(x + idx) : zero16();
+    }
+    m += B_::BK;
+  }
+};
+
+// Element-wise fallback for channel counts that are not a multiple of the vector width
+// (first layers with 1 or 3 channels, 6- and 10-wide outputs).  Full index arithmetic per
+// element: slow, used only where the tensors are tiny or the layer is a stem.
+template <typename T, int PASS, int ROWS, bool IS_A> struct ScalarLoader {
+  static constexpr int BK = Cfg<T>::BK, STRIDE = BK + Cfg<T>::PAD;
+  static constexpr int E = ROWS * BK / NT;
+  static constexpr bool KFAST = IS_A ? (PASS != PASS_WGRAD) : (PASS == PASS_DGRAD);
+  T v[E];
+  int row0, kbase;
+  __device__ void init(const Args&, int row0_, int, int kt0) {
+    row0 = row0_;
+    kbase = kt0 * BK;
+  }
+  __device__ void load(const Args& a, int tid) {
+    const T* src = static_cast<const T*>(IS_A ? a.a : a.b);
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      int e = tid + i * NT;
+      int rl = KFAST ? e / BK : e % ROWS, kl = KFAST ? e % BK : e / ROWS;
+      int row = row0 + rl, kk = kbase + kl;
+      long long idx = -1;
+      if (row < (IS_A ? a.Mg : a.Ng) && kk < a.Kg)
+        idx = IS_A ? a_index<PASS>(a.g, row, kk) : b_index<PASS>(a.g, row, kk);
+      v[i] = idx >= 0 ? src[idx] : (T)0;
+    }
+    kbase += BK;
+  }
+  __device__ void store(T* tile, int tid) const {
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      int e = tid + i * NT;
+      int rl = KFAST ? e / BK : e % ROWS, kl = KFAST ? e % BK : e / ROWS;
+      tile[rl * STRIDE + kl] = v[i];
+    }
+  }
+};
+
+template <typename T, int PASS, int ROWS, bool VECMODE, bool IS_A> struct LoaderSel;
+template <typename T, int ROWS> struct LoaderSel<T, PASS_FWD, ROWS, true, true> { typedef FwdALoader<T, ROWS> type; };
+template <typename T, int ROWS> struct LoaderSel<T, PASS_FWD, ROWS, true, false> { typedef PlainRLoader<T, ROWS> type; };
+template <typename T, int ROWS> struct LoaderSel<T, PASS_DGRAD, ROWS, true, true> { typedef DgradALoader<T, ROWS> type; };
+template <typename T, int ROWS> struct LoaderSel<T, PASS_DGRAD, ROWS, true, false> { typedef DgradBLoader<T, ROWS> type; };
+template <typename T, int ROWS> struct LoaderSel<T, PASS_WGRAD, ROWS, true, true> { typedef WgradALoader<T, ROWS> type; };
+template <typename T, int ROWS> struct LoaderSel<T, PASS_WGRAD, ROWS, true, false> { typedef PlainRLoader<T, ROWS> type; };
+
+// ---- MFMA over one staged k-tile ----------------------------------------------------------------
+template <typename T, int FM, int FN, int STRIDE>
+__device__ inline void mma_tile(const T* As, const T* Bs, int arow, int brow, int lane, f32x16 (&acc)[FM][FN]) {
+  constexpr int BK = Cfg<T>::BK;
+  if constexpr (sizeof(T) == 2) {
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 af[FM], bf[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+        af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
+                    &As[(arow + i * 32 + (lane & 31)) * STRIDE + ks * 16 + 8 * (lane >> 5)]));
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        bf[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
+                    &Bs[(brow + j * 32 + (lane & 31)) * STRIDE + ks * 16 + 8 * (lane >> 5)]));
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < BK / 2; ++ks) {
+      float af[FM], bf[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i) af[i] = As[(arow + i * 32 + (lane & 31)) * STRIDE + ks * 2 + (lane >> 5)];
+#pragma unroll
+      for (int j = 0; j < FN; ++j) bf[j] = Bs[(brow + j * 32 + (lane & 31)) * STRIDE + ks * 2 + (lane >> 5)];
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+  }
+}
+
+// WM x WN wavefronts, each FM x FN MFMA blocks of 32x32
+template <typename T, int PASS, bool VECMODE, int WM, int WN, int FM, int FN>
+__global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
+  static_assert(WM * WN == 4, "four wavefronts");
+  constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
+  constexpr int BK = Cfg<T>::BK, STRIDE = BK + Cfg<T>::PAD;
+  constexpr int TILE = (BM + BN) * STRIDE;
+  __shared__ __attribute__((aligned(16))) T smem[2 * TILE];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // consecutive workgroup ids land on different XCDs; give each XCD a contiguous run of
+  // tiles so that tiles sharing an A row-block share that XCD's L2
+  const int logical = (blockIdx.x % NUM_XCD) * a.tiles_per_xcd + blockIdx.x / NUM_XCD;
+  if (blockIdx.x / NUM_XCD >= a.tiles_per_xcd || logical >= a.tiles_m * a.tiles_n) return;
+  const int m0 = (logical / a.tiles_n) * BM, n0 = (logical % a.tiles_n) * BN;
+  const int kt0 = blockIdx.y * a.nk_per_split;
+  const int kt1 = min(a.nk, kt0 + a.nk_per_split);
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int arow = (wave / WN) * FM * 32, brow = (wave % WN) * FN * 32;
+
+  if constexpr (VECMODE) {
+    typename LoaderSel<T, PASS, BM, true, true>::type la;
+    typename LoaderSel<T, PASS, BN, true, false>::type lb;
+    la.init(a, m0, tid, kt0);
+    lb.init(a, n0, tid, kt0);
+    la.load(a);
+    lb.load(a);
+    la.store(smem, tid);
+    lb.store(smem + BM * STRIDE, tid);
+    __syncthreads();
+    for (int kt = kt0; kt < kt1; ++kt) {
+      const int cur = (kt - kt0) & 1;
+      const bool more = kt + 1 < kt1;
+      if (more) {
+        la.load(a);
+        lb.load(a);
+      }
+      mma_tile<T, FM, FN, STRIDE>(smem + cur * TILE, smem + cur * TILE + BM * STRIDE, arow, brow, lane, acc);
+      if (more) {
+        la.store(smem + (cur ^ 1) * TILE, tid);
+        lb.store(smem + (cur ^ 1) * TILE + BM * STRIDE, tid);
+      }
+      __syncthreads();
+    }
+  } else {
+    ScalarLoader<T, PASS, BM, true> la;
+    ScalarLoader<T, PASS, BN, false> lb;
+    la.init(a, m0, tid, kt0);
+    lb.init(a, n0, tid, kt0);
+    la.load(a, tid);
+    lb.load(a, tid);
+    la.store(smem, tid);
+    lb.store(smem + BM * STRIDE, tid);
+    __syncthreads();
+    for (int kt = kt0; kt < kt1; ++kt) {
+      const int cur = (kt - kt0) & 1;
+      const bool more = kt + 1 < kt1;
+      if (more) {
+        la.load(a, tid);
+        lb.load(a, tid);
+      }
+      mma_tile<T, FM, FN, STRIDE>(smem + cur * TILE, smem + cur * TILE + BM * STRIDE, arow, brow, lane, acc);
+      if (more) {
+        la.store(smem + (cur ^ 1) * TILE, tid);
+        lb.store(smem + (cur ^ 1) * TILE + BM * STRIDE, tid);
+      }
+      __syncthreads();
+    }
+  }
+
+  // epilogue.  A 32x32 accumulator block: lane holds column (lane & 31) and, in register v,
+  // row 8*(v/4) + 4*(lane >> 5) + (v % 4).
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int col = n0 + brow + j * 32 + (lane & 31);
+      if (col >= a.Ng) continue;
+      const float bias = (PASS == PASS_FWD && a.bias) ? a.bias[col] : 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + arow + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+        if (row >= a.Mg) continue;
+        const long long o = (long long)row * a.Ng + col;
+        float val = acc[i][j][v];
+        if constexpr (PASS == PASS_FWD) {
+          T* y = static_cast<T*>(a.out);
+          y[o] = from_f32<T>(act_apply(val + bias, a.act));
+        } else if constexpr (PASS == PASS_DGRAD) {
+          T* dx = static_cast<T*>(a.out);
+          if (a.accumulate) val += to_f32<T>(dx[o]);
+          dx[o] = from_f32<T>(val);
+        } else {
+          float* dw = static_cast<float*>(a.out) + (long long)blockIdx.y * a.split_stride;
+          dw[o] = val;
+        }
+      }
+    }
+}
+
+__global__ void splitk_reduce_kernel(const float* __restrict__ part, float* __restrict__ out, long long n,
+                                     int splits) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int z = 0; z < splits; ++z) s += part[(long long)z * n + i];
+  out[i] = s;
+}
+
+template <typename T> bool vec_ok(const ConvGeom& g) {
+  return g.C % Cfg<T>::VEC == 0 && g.K % Cfg<T>::VEC == 0;
+}
+
+void fill_tiles(Args& a, int BM, int BN, int BK) {
+  a.tiles_m = (a.Mg + BM - 1) / BM;
+  a.tiles_n = (a.Ng + BN - 1) / BN;
+  a.nk = (a.Kg + BK - 1) / BK;
+  a.nk_per_split = a.nk;
+  a.split_stride = 0;
+  a.tiles_per_xcd = (a.tiles_m * a.tiles_n + NUM_XCD - 1) / NUM_XCD;
+}
+
+template <typename T, int PASS> int launch(Args& a, int splits, hipStream_t st) {
+  dim3 grid((unsigned)(a.tiles_per_xcd * NUM_XCD), (unsigned)splits);
+  if (vec_ok<T>(a.g))
+    hipLaunchKernelGGL((igemm_kernel<T, PASS, true, 2, 2, 2, 2>), grid, dim3(NT), 0, st, a);
+  else
+    hipLaunchKernelGGL((igemm_kernel<T, PASS, false, 2, 2, 2, 2>), grid, dim3(NT), 0, st, a);
+  return launch_status("igemm");
+}
+
+void wgrad_split(const ConvGeom& g, int dtype, int& splits, int& nk_per_split) {
+  const int BK = dtype == S4TF_BF16 ? Cfg<bf16_t>::BK : Cfg<float>::BK;
+  long long Mg = (long long)g.R * g.S * g.C, Kg = (long long)g.N * g.P * g.Q;
+  long long tiles = ((Mg + 127) / 128) * ((g.K + 127) / 128);
+  long long nk = (Kg + BK - 1) / BK;
+  long long want = (1024 + tiles - 1) / tiles;
+  if (want > nk) want = nk;
+  if (want < 1) want = 1;
+  nk_per_split = (int)((nk + want - 1) / want);
+  splits = (int)((nk + nk_per_split - 1) / nk_per_split);
+}
+
+}  // namespace
+
+int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, int act,
+              void* y, hipStream_t st) {
+  Args a = {};
+  a.g = g; a.a = x; a.b = w; a.out = y; a.bias = bias; a.act = act;
+  a.Mg = g.N * g.P * g.Q; a.Ng = g.K; a.Kg = g.R * g.S * g.C;
+  a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
+  ProfScope ps(PC_CONV_FWD, st);
+  if (dtype == S4TF_BF16) {
+    fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
+    return launch<bf16_t, PASS_FWD>(a, 1, st);
+  }
+  fill_tiles(a, 128, 128, Cfg<float>::BK);
+  return launch<float, PASS_FWD>(a, 1, st);
+}
+
+int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,
+                hipStream_t st) {
+  Args a = {};
+  a.g = g; a.a = dy; a.b = w; a.out = dx; a.accumulate = accumulate;
+  a.Mg = g.N * g.H * g.W; a.Ng = g.C; a.Kg = g.R * g.S * g.K;
+  a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
+  ProfScope ps(PC_CONV_DGRAD, st);
+  if (dtype == S4TF_BF16) {
+    fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
+    return launch<bf16_t, PASS_DGRAD>(a, 1, st);
+  }
+  fill_tiles(a, 128, 128, Cfg<float>::BK);
+  return launch<float, PASS_DGRAD>(a, 1, st);
+}
+
+size_t igemm_wgrad_workspace(const ConvGeom& g, int dtype) {
+  int splits, per;
+  wgrad_split(g, dtype, splits, per);
+  if (splits <= 1) return 0;
+  return (size_t)splits * g.R * g.S * g.C * g.K * sizeof(float);
+}
+
+int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, float* dw, void* ws,
+                size_t ws_bytes, hipStream_t st) {
+  Args a = {};
+  a.g = g; a.a = x; a.b = dy;
+  a.Mg = g.R * g.S * g.C; a.Ng = g.K; a.Kg = g.N * g.P * g.Q;
+  a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
+  int splits, per;
+  wgrad_split(g, dtype, splits, per);
+  const long long n = (long long)a.Mg * a.Ng;
+  if (splits > 1 && ws_bytes < (size_t)splits * n * sizeof(float))
+    return fail(S4TF_ERR_WORKSPACE, "wgrad needs %zu workspace bytes, got %zu", (size_t)splits * n * sizeof(float), ws_bytes);
+  fill_tiles(a, 128, 128, dtype == S4TF_BF16 ? Cfg<bf16_t>::BK : Cfg<float>::BK);
+  a.nk_per_split = per;
+  a.split_stride = n;
+  a.out = splits > 1 ? ws : (void*)dw;
+  int rc;
+  {
+    ProfScope ps(PC_CONV_WGRAD, st);
+    rc = dtype == S4TF_BF16 ? launch<bf16_t, PASS_WGRAD>(a, splits, st) : launch<float, PASS_WGRAD>(a, splits, st);
+  }
+  if (rc != S4TF_OK || splits == 1) return rc;
+  ProfScope ps(PC_WGRAD_REDUCE, st);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const float*>(ws), dw, n, splits);
+  return launch_status("splitk_reduce");
+}
+
+}  // namespace s4tf

@@ -1,0 +1,233 @@
+// Pooling forward / pullback, the activation pullback of conv/dense layers, column sums
+// (bias gradients) and the SGD-momentum update.  All bound by HBM bandwidth; threads map to
+// the channel-fastest NHWC index so wavefronts touch contiguous memory.
+#include "s4tf_internal.h"
+#include "pack.h"
+
+namespace s4tf {
+namespace {
+
+inline int blocks_for(long long total, int per_block = 256) {
+  long long b = (total + per_block - 1) / per_block;
+  if (b > 256 * 64) b = 256 * 64;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+
+// ---- 2x2 / 2 average pool (AvgPool2D of the paper's LeNet figure) -----------------------------
+template <typename T>
+__global__ void avgpool2_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int N, int H, int W, int C) {
+  const int P = H / 2, Q = W / 2;
+  const long long total = (long long)N * P * Q * C;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    int c = (int)(i % C);
+    long long t = i / C;
+    int q = (int)(t % Q);
+    t /= Q;
+    int p = (int)(t % P), n = (int)(t / P);
+    const T* b = x + (((long long)n * H + 2 * p) * W + 2 * q) * C + c;
+    float s = to_f32<T>(b[0]) + to_f32<T>(b[C]) + to_f32<T>(b[(long long)W * C]) + to_f32<T>(b[(long long)W * C + C]);
+    y[i] = from_f32<T>(s * 0.25f);
+  }
+}
+template <typename T>
+__global__ void avgpool2_vjp_kernel(const T* __restrict__ dy, T* __restrict__ dx, int N, int H, int W, int C, int accumulate) {
+  const int P = H / 2, Q = W / 2;
+  const long long total = (long long)N * H * W * C;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    int c = (int)(i % C);
+    long long t = i / C;
+    int w = (int)(t % W);
+    t /= W;
+    int h = (int)(t % H), n = (int)(t / H);
+    int p = h >> 1, q = w >> 1;
+    float v = 0.f;
+    if (p < P && q < Q) v = to_f32<T>(dy[(((long long)n * P + p) * Q + q) * C + c]) * 0.25f;
+    if (accumulate) v += to_f32<T>(dx[i]);
+    dx[i] = from_f32<T>(v);
+  }
+}
+
+// ---- 3x3 / 2 pad 1 max pool --------------------------------------------------------------------
+template <typename T>
+__global__ void maxpool3s2_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int N, int H, int W, int C) {
+  const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
+  const long long total = (long long)N * P * Q * C;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    int c = (int)(i % C);
+    long long t = i / C;
+    int q = (int)(t % Q);
+    t /= Q;
+    int p = (int)(t % P), n = (int)(t / P);
+    float best = -INFINITY;
+    for (int r = 0; r < 3; ++r) {
+      int h = 2 * p + r - 1;
+      if (h < 0 || h >= H) continue;
+      for (int s = 0; s < 3; ++s) {
+        int w = 2 * q + s - 1;
+        if (w < 0 || w >= W) continue;
+        float v = to_f32<T>(x[(((long long)n * H + h) * W + w) * C + c]);
+        if (v > best) best = v;
+      }
+    }
+    y[i] = from_f32<T>(best);
+  }
+}
+// gather form of the pullback: input (h,w) receives dy of every window in which it is the first
+// maximum in row-major window order (so the result does not depend on thread scheduling)
+template <typename T>
+__global__ void maxpool3s2_vjp_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int N,
+                                      int H, int W, int C, int accumulate) {
+  const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
+  const long long total = (long long)N * H * W * C;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    int c = (int)(i % C);
+    long long t = i / C;
+    int w = (int)(t % W);
+    t /= W;
+    int h = (int)(t % H), n = (int)(t / H);
+    const float mine = to_f32<T>(x[i]);
+    float g = 0.f;
+    // windows p with 2p-1 <= h <= 2p+1
+    for (int p = h / 2; p <= (h + 1) / 2; ++p) {
+      if (p >= P) continue;
+      for (int q = w / 2; q <= (w + 1) / 2; ++q) {
+        if (q >= Q) continue;
+        bool first = true;
+        for (int r = 0; r < 3 && first; ++r) {
+          int hh = 2 * p + r - 1;
+          if (hh < 0 || hh >= H) continue;
+          for (int s = 0; s < 3; ++s) {
+            int ww = 2 * q + s - 1;
+            if (ww < 0 || ww >= W) continue;
+            float v = to_f32<T>(x[(((long long)n * H + hh) * W + ww) * C + c]);
+            bool before = hh < h || (hh == h && ww < w);
+            // an earlier element that is >= mine, or a later one that is > mine, beats it
+            if ((before && v >= mine) || (!before && v > mine)) { first = false; break; }
+          }
+        }
+        if (first) g += to_f32<T>(dy[(((long long)n * P + p) * Q + q) * C + c]);
+      }
+    }
+    if (accumulate) g += to_f32<T>(dx[i]);
+    dx[i] = from_f32<T>(g);
+  }
+}
+
+// ---- dz = dy * act'(y) ---------------------------------------------------------------------------
+template <typename T>
+__global__ void act_vjp_kernel(const T* __restrict__ y, const T* dy, T* dz, long long n, int act) {  // dz may be dy
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+    dz[i] = from_f32<T>(to_f32<T>(dy[i]) * act_mask(to_f32<T>(y[i]), act));
+}
+
+// ---- out[c] = sum over rows of a[row][c]; one block per 64 columns, fixed summation order ------
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ a, long long rows, int cols, float* __restrict__ out) {
+  __shared__ float red[4][64];
+  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
+  float s = 0.f;
+  if (c < cols)
+    for (long long r = rl; r < rows; r += 4) s += to_f32<T>(a[r * cols + c]);
+  red[rl][cl] = s;
+  __syncthreads();
+  if (rl == 0 && c < cols) out[c] = red[0][cl] + red[1][cl] + red[2][cl] + red[3][cl];
+}
+
+// ---- SGD with momentum ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ param, float* __restrict__ vel,
+                                                  const float* __restrict__ grad, bf16_t* __restrict__ lowp,
+                                                  long long n4, long long n, float lr, float mu) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (; i < n4; i += stride) {
+    float4 p = reinterpret_cast<float4*>(param)[i], v = reinterpret_cast<float4*>(vel)[i];
+    const float4 g = reinterpret_cast<const float4*>(grad)[i];
+    v.x = mu * v.x + g.x; v.y = mu * v.y + g.y; v.z = mu * v.z + g.z; v.w = mu * v.w + g.w;
+    p.x -= lr * v.x; p.y -= lr * v.y; p.z -= lr * v.z; p.w -= lr * v.w;
+    reinterpret_cast<float4*>(vel)[i] = v;
+    reinterpret_cast<float4*>(param)[i] = p;
+    if (lowp) {
+      uint2 o;
+      o.x = (uint32_t)f32_to_bf16(p.x) | ((uint32_t)f32_to_bf16(p.y) << 16);
+      o.y = (uint32_t)f32_to_bf16(p.z) | ((uint32_t)f32_to_bf16(p.w) << 16);
+      reinterpret_cast<uint2*>(lowp)[i] = o;
+    }
+  }
+  // tail (count not a multiple of 4)
+  for (long long j = n4 * 4 + (long long)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += stride) {
+    float v = mu * vel[j] + grad[j];
+    float p = param[j] - lr * v;
+    vel[j] = v;
+    param[j] = p;
+    if (lowp) lowp[j] = f32_to_bf16(p);
+  }
+}
+
+}  // namespace
+
+int pool_fwd(const s4tf_pool_desc& d, const void* x, void* y, hipStream_t st) {
+  ProfScope ps(PC_POOL, st);
+  const bool avg = d.kind == S4TF_POOL_AVG2;
+  const int P = avg ? d.h / 2 : (d.h - 1) / 2 + 1, Q = avg ? d.w / 2 : (d.w - 1) / 2 + 1;
+  dim3 grid(blocks_for((long long)d.n * P * Q * d.c)), block(256);
+  if (d.dtype == S4TF_BF16) {
+    typedef bf16_t T;
+    if (avg) hipLaunchKernelGGL(avgpool2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+    else hipLaunchKernelGGL(maxpool3s2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+  } else {
+    typedef float T;
+    if (avg) hipLaunchKernelGGL(avgpool2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+    else hipLaunchKernelGGL(maxpool3s2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+  }
+  return launch_status("pool_fwd");
+}
+
+int pool_vjp(const s4tf_pool_desc& d, const void* x, const void* dy, void* dx, hipStream_t st) {
+  ProfScope ps(PC_POOL, st);
+  const bool avg = d.kind == S4TF_POOL_AVG2;
+  dim3 grid(blocks_for((long long)d.n * d.h * d.w * d.c)), block(256);
+  if (d.dtype == S4TF_BF16) {
+    typedef bf16_t T;
+    if (avg) hipLaunchKernelGGL(avgpool2_vjp_kernel<T>, grid, block, 0, st, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+    else hipLaunchKernelGGL(maxpool3s2_vjp_kernel<T>, grid, block, 0, st, (const T*)x, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+  } else {
+    typedef float T;
+    if (avg) hipLaunchKernelGGL(avgpool2_vjp_kernel<T>, grid, block, 0, st, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+    else hipLaunchKernelGGL(maxpool3s2_vjp_kernel<T>, grid, block, 0, st, (const T*)x, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+  }
+  return launch_status("pool_vjp");
+}
+
+int act_vjp(int dtype, int act, const void* y, const void* dy, void* dz, size_t count, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  dim3 grid(blocks_for((long long)count)), block(256);
+  if (dtype == S4TF_BF16)
+    hipLaunchKernelGGL(act_vjp_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)y, (const bf16_t*)dy, (bf16_t*)dz, (long long)count, act);
+  else
+    hipLaunchKernelGGL(act_vjp_kernel<float>, grid, block, 0, st, (const float*)y, (const float*)dy, (float*)dz, (long long)count, act);
+  return launch_status("act_vjp");
+}
+
+int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  dim3 grid((cols + 63) / 64), block(256);
+  if (dtype == S4TF_BF16)
+    hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)a, (long long)rows, cols, out);
+  else
+    hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, st, (const float*)a, (long long)rows, cols, out);
+  return launch_status("colsum");
+}
+
+int sgd(size_t count, float* param, float* vel, const float* grad, void* lowp, float lr, float mu,
+        hipStream_t st) {
+  if (count == 0) return S4TF_OK;
+  ProfScope ps(PC_SGD, st);
+  long long n4 = (long long)(count / 4);
+  dim3 grid(blocks_for(n4 > 0 ? n4 : 1)), block(256);
+  hipLaunchKernelGGL(sgd_kernel, grid, block, 0, st, param, vel, grad, (bf16_t*)lowp, n4, (long long)count, lr, mu);
+  return launch_status("sgd");
+}
+
+}  // namespace s4tf

@@ -1,0 +1,137 @@
+// Internal declarations shared by the HIP translation units of libs4tf.
+// Not part of the ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/s4tf.h"
+
+namespace s4tf {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+// ---- error reporting --------------------------------------------------------------------
+int fail(int status, const char* fmt, ...);
+void clear_error();
+
+// ---- bf16 <-> fp32 ----------------------------------------------------------------------
+__host__ __device__ inline float bf16_to_f32(bf16_t v) {
+  union { uint32_t u; float f; } x;
+  x.u = (uint32_t)v << 16;
+  return x.f;
+}
+// round to nearest, ties to even; NaN stays NaN
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+  union { uint32_t u; float f; } x;
+  x.f = f;
+  if ((x.u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((x.u >> 16) | 0x40u);
+  x.u += 0x7fffu + ((x.u >> 16) & 1u);
+  return (bf16_t)(x.u >> 16);
+}
+template <typename T> __device__ inline float to_f32(T v);
+template <> __device__ inline float to_f32<float>(float v) { return v; }
+template <> __device__ inline float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ inline T from_f32(float v);
+template <> __device__ inline float from_f32<float>(float v) { return v; }
+template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+__device__ inline float act_apply(float z, int act) {
+  if (act == S4TF_ACT_RELU) return z > 0.f ? z : 0.f;
+  if (act == S4TF_ACT_RELU6) return z < 0.f ? 0.f : (z > 6.f ? 6.f : z);
+  return z;
+}
+__device__ inline float act_mask(float y, int act) {
+  if (act == S4TF_ACT_RELU) return y > 0.f ? 1.f : 0.f;
+  if (act == S4TF_ACT_RELU6) return (y > 0.f && y < 6.f) ? 1.f : 0.f;
+  return 1.f;
+}
+
+// ---- per-kernel-class timing hook ---------------------------------------------------------
+enum ProfClass {
+  PC_CONV_FWD = 0, PC_CONV_DGRAD, PC_CONV_WGRAD, PC_WGRAD_REDUCE, PC_DWCONV_FWD, PC_DWCONV_DGRAD,
+  PC_DWCONV_WGRAD, PC_BN_STATS, PC_BN_APPLY, PC_BN_VJP_REDUCE, PC_BN_VJP_APPLY, PC_POOL, PC_HEAD,
+  PC_SGD, PC_ELEMENTWISE, PC_OTHER
+};
+struct ProfScope {
+  ProfScope(int cls, hipStream_t s);
+  ~ProfScope();
+  int cls;
+  hipStream_t stream;
+  void* rec;
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t dtype_size(int dtype) { return dtype == S4TF_BF16 ? 2 : 4; }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// ---- internal launchers (arguments already validated) ---------------------------------------
+struct ConvGeom {
+  int N, H, W, C, K, R, S, stride, pad, P, Q;
+};
+inline ConvGeom conv_geom(const s4tf_conv_desc& d) {
+  ConvGeom g;
+  g.N = d.n; g.H = d.h; g.W = d.w; g.C = d.c; g.K = d.k; g.R = d.r; g.S = d.s;
+  g.stride = d.stride; g.pad = d.pad;
+  g.P = (d.h + 2 * d.pad - d.r) / d.stride + 1;
+  g.Q = (d.w + 2 * d.pad - d.s) / d.stride + 1;
+  return g;
+}
+
+// dense (groups == 1) convolution as implicit GEMM on MFMA
+int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, int act,
+              void* y, hipStream_t st);
+int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,
+                hipStream_t st);
+size_t igemm_wgrad_workspace(const ConvGeom& g, int dtype);
+int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, float* dw, void* ws,
+                size_t ws_bytes, hipStream_t st);
+
+// depthwise (groups == C == K)
+int dwconv_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, int act,
+               void* y, hipStream_t st);
+int dwconv_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,
+                 hipStream_t st);
+size_t dwconv_wgrad_workspace(const ConvGeom& g);
+int dwconv_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, float* dw, void* ws,
+                 hipStream_t st);
+
+// elementwise / reductions
+int act_vjp(int dtype, int act, const void* y, const void* dy, void* dz, size_t count, hipStream_t st);
+int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStream_t st);
+
+// batch norm
+size_t bn_workspace(size_t M, int C);
+int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
+           void* y, float* mean, float* invstd, void* ws, hipStream_t st);
+int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* mean,
+           const float* invstd, const void* dy, void* dx, void* dres, float* dgamma, float* dbeta,
+           void* ws, hipStream_t st);
+
+// pools
+int pool_fwd(const s4tf_pool_desc& d, const void* x, void* y, hipStream_t st);
+int pool_vjp(const s4tf_pool_desc& d, const void* x, const void* dy, void* dx, hipStream_t st);
+
+// head
+size_t head_workspace(const s4tf_head_desc& d);
+int head_fwd_vjp(const s4tf_head_desc& d, const void* x, const float* W, const float* b,
+                 const int32_t* labels, float* loss, void* dx, float* dW, float* db, float* logits,
+                 void* ws, hipStream_t st);
+
+// optimizer
+int sgd(size_t count, float* param, float* vel, const float* grad, void* lowp, float lr, float mu,
+        hipStream_t st);
+
+// validation shared by the per-op entry points and the whole step
+int check_conv_desc(const s4tf_conv_desc* d);
+int check_bn_desc(const s4tf_bn_desc* d);
+int check_pool_desc(const s4tf_pool_desc* d);
+int check_head_desc(const s4tf_head_desc* d);
+
+inline int launch_status(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(S4TF_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+  return S4TF_OK;
+}
+
+}  // namespace s4tf

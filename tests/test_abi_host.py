@@ -1,0 +1,114 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, plans
+networks and rejects bad arguments before touching a device.  No GPU needed."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2102_13243_amd import binding as B
+from workloads import nets
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "s4tf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(s4tf_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = declared_symbols()
+    assert "s4tf_train_step" in names and "s4tf_conv2d_vjp" in names and len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_binding_has_the_same_names():
+    for n in declared_symbols():
+        if n in ("s4tf_last_error", "s4tf_profile_class_name"):
+            continue
+        assert hasattr(B, n), n
+
+
+@pytest.mark.parametrize("name,expect", [("tiny", 634), ("lenet5", 61706), ("resnet56", 855770),
+                                         ("resnet50", 25557032), ("mobilenetv2", 3504872)])
+def test_net_planning_matches_parameter_counts(name, expect):
+    net = nets.CONFIGS[name]()
+    desc, keep = B.make_net_desc(net)
+    off, size = B.s4tf_net_param_layout(desc)
+    assert sum(size) == expect
+    count = B.s4tf_net_param_count(desc)
+    assert count >= expect and count % 8 == 0
+    # tensors do not overlap, start at multiples of 8 elements, and are in op order
+    spans = sorted((o, s) for o, s in zip(off, size) if s)
+    for (o1, s1), (o2, _) in zip(spans, spans[1:]):
+        assert o1 % 8 == 0 and o1 + s1 <= o2
+    assert B.s4tf_train_step_workspace_bytes(desc) > 0
+
+
+def test_lenet_plan_follows_paper_shapes():
+    # fc1 has inputSize 400 in the paper's LeNet figure: the planner must derive 16*5*5
+    net = nets.lenet5()
+    desc, keep = B.make_net_desc(net)
+    _, size = B.s4tf_net_param_layout(desc)
+    assert size[2 * 5] == 400 * 120 and size[2 * 5 + 1] == 120
+    assert size[0] == 5 * 5 * 1 * 6 and size[2 * 2] == 5 * 5 * 6 * 16
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    L = B.lib()
+    d = B.ConvDesc(1, 8, 8, 4, 4, 3, 3, 1, 1, 1, B.S4TF_F32, 0, 0)
+    assert L.s4tf_conv2d_fwd(ctypes.byref(d), None, None, None, None, None, 0, None) == -1
+    assert "NULL" in B.last_error()
+    assert L.s4tf_conv2d_fwd(ctypes.byref(d), 8, 16, None, 16, None, 0, None) == -7      # misaligned x
+    bad = B.ConvDesc(1, 8, 8, 4, 4, 3, 3, 0, 1, 1, B.S4TF_F32, 0, 0)                    # stride 0
+    assert L.s4tf_conv2d_fwd(ctypes.byref(bad), 16, 16, None, 16, None, 0, None) == -2
+    bad = B.ConvDesc(1, 8, 8, 4, 4, 3, 3, 1, 1, 2, B.S4TF_F32, 0, 0)                    # 1 < groups < c
+    assert L.s4tf_conv2d_fwd(ctypes.byref(bad), 16, 16, None, 16, None, 0, None) == -4
+    bad = B.ConvDesc(1, 8, 8, 4, 4, 3, 3, 1, 1, 1, 7, 0, 0)                             # dtype
+    assert L.s4tf_conv2d_fwd(ctypes.byref(bad), 16, 16, None, 16, None, 0, None) == -3
+    bad = B.ConvDesc(1, 2, 2, 4, 4, 5, 5, 1, 0, 1, B.S4TF_F32, 0, 0)                    # filter > input
+    assert L.s4tf_conv2d_fwd(ctypes.byref(bad), 16, 16, None, 16, None, 0, None) == -2
+    # vjp with an activation needs y, and a workspace
+    da = B.ConvDesc(4, 8, 8, 4, 4, 3, 3, 1, 1, 1, B.S4TF_F32, 1, 0)
+    assert L.s4tf_conv2d_vjp(ctypes.byref(da), 16, 16, None, 16, None, 16, None, None, 0, None) == -1
+    need = B.s4tf_conv2d_vjp_workspace_bytes(da)
+    assert need > 0
+    assert L.s4tf_conv2d_vjp(ctypes.byref(da), 16, 16, 16, 16, None, 16, None, 16, need - 1, None) == -5
+    bn = B.BnDesc(2, 4, 4, 8, 1e-5, 1, B.S4TF_F32, 0)
+    assert L.s4tf_bn_relu_fwd(ctypes.byref(bn), 16, None, 16, 16, 16, 16, 16, None, 0, None) == -5
+    assert L.s4tf_sgd_momentum(0, None, None, None, None, 0.1, 0.9, None) == 0           # empty update is a no-op
+    assert L.s4tf_sgd_momentum(4, None, 16, 16, None, 0.1, 0.9, None) == -1
+
+
+def test_bad_networks_are_rejected():
+    net = nets.tiny_block()
+    # head not last
+    broken = dict(net, ops=net["ops"][::-1])
+    desc, keep = B.make_net_desc(broken)
+    assert B.s4tf_net_param_count(desc) == 0 and B.last_error()
+    # dangling tensor: a conv whose output nobody consumes
+    ops = list(net["ops"])
+    ops.insert(1, dict(ops[0], **{"in": 0}))
+    ops[2] = dict(ops[2], **{"in": 1})
+    ops[3] = dict(ops[3], **{"in": 3})
+    desc, keep = B.make_net_desc(dict(net, ops=ops))
+    assert B.s4tf_net_param_count(desc) == 0 and "consumer" in B.last_error()
+    # residual of a different shape
+    r = nets.resnet56(batch=2, blocks_per_stage=1, hw=8)
+    ops = [dict(o) for o in r["ops"]]
+    for o in ops:
+        if o["kind"] == "bn" and o["res"] >= 0:
+            o["res"] = 0
+            break
+    desc, keep = B.make_net_desc(dict(r, ops=ops))
+    assert B.s4tf_net_param_count(desc) == 0 and "residual" in B.last_error()
+    # params.count mismatch is caught before anything runs
+    desc, keep = B.make_net_desc(net)
+    p = B.Params(16, 16, 16, None, 3)
+    b = B.Batch(16, 16, 16, 16, 1 << 30, None)
+    assert B.lib().s4tf_train_step(ctypes.byref(desc), ctypes.byref(p), ctypes.byref(b), 0.1) == -2
