@@ -228,6 +228,15 @@ size_t s4tf_net_param_count(const s4tf_net_desc* net);
 int s4tf_net_param_layout(const s4tf_net_desc* net, int64_t* offsets, int64_t* sizes);
 size_t s4tf_train_step_workspace_bytes(const s4tf_net_desc* net);
 
+/* Where the step keeps its intermediates inside the workspace, for inspection and tests.
+ * All arguments after `net` are nullable host arrays.  For tensor t in 0..n_ops-1 (the head's
+ * output has no buffer): act_off[t] / grad_off[t] = byte offset of the activation / of its
+ * cotangent, -1 for the batch and reinterpretations of it; shape[4t..4t+3] = n,h,w,c.
+ * stat_off[i] (n_ops entries) = byte offset of BatchNorm op i's save_mean (c floats, followed
+ * by save_invstd), -1 for other ops.  After a step every buffer still holds its final value. */
+int s4tf_net_tensor_layout(const s4tf_net_desc* net, int64_t* act_off, int64_t* grad_off, int32_t* shape,
+                           int64_t* stat_off);
+
 /* One training step: forward, loss, pullbacks in reverse op order (cotangents of a tensor
  * with several consumers are summed in reverse consumer order), then one SGD-momentum
  * update of the whole arena.  Enqueues on batch->stream; never synchronises. */

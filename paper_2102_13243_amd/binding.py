@@ -95,6 +95,8 @@ def lib():
     L.s4tf_net_param_count.restype = c_sz
     L.s4tf_net_param_count.argtypes = [P(NetDesc)]
     L.s4tf_net_param_layout.argtypes = [P(NetDesc), P(ctypes.c_int64), P(ctypes.c_int64)]
+    L.s4tf_net_tensor_layout.argtypes = [P(NetDesc), P(ctypes.c_int64), P(ctypes.c_int64), P(c_i32), P(ctypes.c_int64)]
+    L.s4tf_net_tensor_layout.restype = ctypes.c_int
     L.s4tf_train_step_workspace_bytes.restype = c_sz
     L.s4tf_train_step_workspace_bytes.argtypes = [P(NetDesc)]
     L.s4tf_train_step.argtypes = [P(NetDesc), P(Params), P(Batch), c_f32]
@@ -211,6 +213,14 @@ def s4tf_net_param_layout(net_desc):
     return list(off), list(size)
 
 
+def s4tf_net_tensor_layout(net_desc):
+    n = net_desc.n_ops
+    act, grad, stat = (ctypes.c_int64 * n)(), (ctypes.c_int64 * n)(), (ctypes.c_int64 * n)()
+    shape = (c_i32 * (4 * n))()
+    _check(lib().s4tf_net_tensor_layout(ctypes.byref(net_desc), act, grad, shape, stat))
+    return list(act), list(grad), [tuple(shape[4 * t:4 * t + 4]) for t in range(n)], list(stat)
+
+
 def s4tf_train_step_workspace_bytes(net_desc):
     return int(lib().s4tf_train_step_workspace_bytes(ctypes.byref(net_desc)))
 
@@ -322,6 +332,33 @@ class TrainState:
         p = Params(_p(self.master), _p(self.velocity), _p(self.grad), _p(self.lowp), self.count)
         b = Batch(_p(x_dev), _p(labels_dev), _p(self.loss), _p(self.workspace), self.ws_bytes, _stream(stream))
         s4tf_train_step(self.desc, p, b, lr)
+
+    def _view(self, off, shape, dtype):
+        torch = self.torch
+        n = int(np.prod(shape))
+        es = 2 if dtype == torch.bfloat16 else 4
+        return self.workspace[off:off + n * es].view(dtype).view(*shape)
+
+    def tensor(self, t, cotangent=False):
+        """float64 host copy of the step's activation t (or of its cotangent) from the workspace."""
+        if not hasattr(self, "_layout"):
+            self._layout = s4tf_net_tensor_layout(self.desc)
+        act, grad, shape, _ = self._layout
+        off = (grad if cotangent else act)[t]
+        if off < 0:
+            raise ValueError("tensor %d has no buffer" % t)
+        dt = self.torch.bfloat16 if self.net["dtype"] == "bf16" else self.torch.float32
+        self.torch.cuda.synchronize()
+        return self._view(off, shape[t], dt).to(self.torch.float32).cpu().numpy().astype(np.float64)
+
+    def bn_stats(self, op):
+        if not hasattr(self, "_layout"):
+            self._layout = s4tf_net_tensor_layout(self.desc)
+        _, _, shape, stat = self._layout
+        c = shape[self.net["ops"][op]["in"]][3]
+        self.torch.cuda.synchronize()
+        v = self._view(stat[op], (2, c), self.torch.float32).cpu().numpy().astype(np.float64)
+        return v[0], v[1]
 
     def results(self):
         """Synchronise and download loss, gradients, parameters and velocities (nested lists)."""

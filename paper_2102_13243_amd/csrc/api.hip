@@ -418,6 +418,22 @@ int s4tf_net_param_layout(const s4tf_net_desc* net, int64_t* offsets, int64_t* s
   }
   return S4TF_OK;
 }
+int s4tf_net_tensor_layout(const s4tf_net_desc* net, int64_t* act_off, int64_t* grad_off, int32_t* shape,
+                           int64_t* stat_off) {
+  clear_error();
+  NetPlan pl;
+  CHECK(plan_net(net, pl));
+  for (int t = 0; t < net->n_ops; ++t) {
+    const TensorPlan& tp = pl.t[t];
+    const bool has = tp.root != 0;
+    if (act_off) act_off[t] = has ? (int64_t)tp.act_off : -1;
+    if (grad_off) grad_off[t] = has ? (int64_t)tp.grad_off : -1;
+    if (shape) { shape[4 * t] = tp.n; shape[4 * t + 1] = tp.h; shape[4 * t + 2] = tp.w; shape[4 * t + 3] = tp.c; }
+  }
+  if (stat_off)
+    for (int i = 0; i < net->n_ops; ++i) stat_off[i] = net->ops[i].kind == S4TF_OP_BN ? (int64_t)pl.stat_off[i] : -1;
+  return S4TF_OK;
+}
 size_t s4tf_train_step_workspace_bytes(const s4tf_net_desc* net) {
   clear_error();
   NetPlan pl;

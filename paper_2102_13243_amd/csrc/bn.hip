@@ -145,64 +145,69 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
   }
 }
 
+// dbeta and dgamma are sums of cotangents whose terms largely cancel (the cotangent reaching a
+// BatchNorm from a convolution that is itself followed by BatchNorm sums to almost zero), so the
+// per-thread and per-block partial sums are kept in double; the kernel stays bandwidth bound.
 template <typename T, int V>
 __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict__ x, const T* __restrict__ y,
                                                             const T* __restrict__ dy, const float* __restrict__ mean,
-                                                            const float* __restrict__ invstd, float* __restrict__ part,
+                                                            const float* __restrict__ invstd, double* __restrict__ part,
                                                             long long M, int C, int cvb, long long per, int act) {
-  extern __shared__ float red[];
+  extern __shared__ double redd[];
   const int CV = C / V, pl_count = blockDim.x / cvb;
   const int cvl = threadIdx.x % cvb, pl = threadIdx.x / cvb;
   const int cv = blockIdx.x * cvb + cvl;
   const bool live = cv < CV;
   const int c = live ? cv * V : 0;
-  float acc[2 * V], mu[V], is[V];
+  double acc[2 * V], mu[V], is[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) {
-    acc[e] = acc[V + e] = 0.f;
-    mu[e] = mean[c + e];
-    is[e] = invstd[c + e];
+    acc[e] = acc[V + e] = 0.0;
+    mu[e] = (double)mean[c + e];
+    is[e] = (double)invstd[c + e];
   }
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
   if (live)
     for (long long m = p0 + pl; m < p1; m += pl_count) {
       Pack<T, V> xv = ldp<T, V>(x + m * C + c), dv = ldp<T, V>(dy + m * C + c);
+      float dz[V];
       if (act != S4TF_ACT_NONE) {
         Pack<T, V> yv = ldp<T, V>(y + m * C + c);
 #pragma unroll
-        for (int e = 0; e < V; ++e) {
-          float dz = dv.get(e) * act_mask(yv.get(e), act);
-          acc[e] += dz;
-          acc[V + e] += dz * ((xv.get(e) - mu[e]) * is[e]);
-        }
+        for (int e = 0; e < V; ++e) dz[e] = dv.get(e) * act_mask(yv.get(e), act);
       } else {
 #pragma unroll
-        for (int e = 0; e < V; ++e) {
-          float dz = dv.get(e);
-          acc[e] += dz;
-          acc[V + e] += dz * ((xv.get(e) - mu[e]) * is[e]);
-        }
+        for (int e = 0; e < V; ++e) dz[e] = dv.get(e);
+      }
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        acc[e] += (double)dz[e];
+        acc[V + e] += (double)dz[e] * (((double)xv.get(e) - mu[e]) * is[e]);
       }
     }
-  block_lane_sum<2 * V>(acc, red, cvb, pl_count, cvl, pl);
-  if (pl == 0 && live) {
-    float* dst = part + (long long)blockIdx.y * 2 * C;
+  double* mine = redd + (size_t)(pl * cvb + cvl) * 2 * V;
 #pragma unroll
-    for (int e = 0; e < V; ++e) {
-      dst[c + e] = acc[e];
-      dst[C + c + e] = acc[V + e];
+  for (int e = 0; e < 2 * V; ++e) mine[e] = acc[e];
+  __syncthreads();
+  if (pl == 0 && live) {
+    double* dst = part + (long long)blockIdx.y * 2 * C;
+#pragma unroll
+    for (int e = 0; e < 2 * V; ++e) {
+      double sum = 0.0;
+      for (int l = 0; l < pl_count; ++l) sum += redd[(size_t)(l * cvb + cvl) * 2 * V + e];
+      if (e < V) dst[c + e] = sum; else dst[C + c + (e - V)] = sum;
     }
   }
 }
 
-__global__ void bn_vjp_finalize_kernel(const float* __restrict__ part, int chunks, int C, float* __restrict__ dgamma,
+__global__ void bn_vjp_finalize_kernel(const double* __restrict__ part, int chunks, int C, float* __restrict__ dgamma,
                                        float* __restrict__ dbeta) {
   int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= C) return;
   double s1 = 0.0, s2 = 0.0;
   for (int z = 0; z < chunks; ++z) {
-    s1 += (double)part[(long long)z * 2 * C + c];
-    s2 += (double)part[(long long)z * 2 * C + C + c];
+    s1 += part[(long long)z * 2 * C + c];
+    s2 += part[(long long)z * 2 * C + C + c];
   }
   dbeta[c] = (float)s1;
   dgamma[c] = (float)s2;
@@ -265,7 +270,7 @@ constexpr int MAX_CHUNKS = 2048;
 
 size_t bn_workspace(size_t M, int C) {
   (void)M;
-  return (size_t)MAX_CHUNKS * 2 * C * sizeof(float);
+  return (size_t)MAX_CHUNKS * 2 * C * sizeof(double);
 }
 
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
@@ -315,11 +320,11 @@ int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gam
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
   Plan p = make_plan((size_t)M, C, d.dtype);
-  float* part = static_cast<float*>(ws);
+  double* part = static_cast<double*>(ws);
   dim3 grid(p.cblocks, p.chunks), block(256);
   {
     ProfScope ps(PC_BN_VJP_REDUCE, st);
-    size_t shm = (size_t)256 * 2 * p.V * sizeof(float);
+    size_t shm = (size_t)256 * 2 * p.V * sizeof(double);
     if (d.dtype == S4TF_BF16) {
       typedef bf16_t T;
       if (p.V == 8) hipLaunchKernelGGL((bn_vjp_reduce_kernel<T, 8>), grid, block, shm, st, (const T*)x, (const T*)y, (const T*)dy, mean, invstd, part, M, C, p.cvb, p.per, d.act);

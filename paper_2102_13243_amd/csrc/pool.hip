@@ -124,15 +124,15 @@ __global__ void act_vjp_kernel(const T* __restrict__ y, const T* dy, T* dz, long
 // ---- out[c] = sum over rows of a[row][c]; one block per 64 columns, fixed summation order ------
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ a, long long rows, int cols, float* __restrict__ out) {
-  __shared__ float red[4][64];
+  __shared__ double red[4][64];
   const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
-  float s = 0.f;
+  double s = 0.0;  // bias cotangents cancel heavily: sum in double
   if (c < cols)
-    for (long long r = rl; r < rows; r += 4) s += to_f32<T>(a[r * cols + c]);
+    for (long long r = rl; r < rows; r += 4) s += (double)to_f32<T>(a[r * cols + c]);
   red[rl][cl] = s;
   __syncthreads();
-  if (rl == 0 && c < cols) out[c] = red[0][cl] + red[1][cl] + red[2][cl] + red[3][cl];
+  if (rl == 0 && c < cols) out[c] = (float)(red[0][cl] + red[1][cl] + red[2][cl] + red[3][cl]);
 }
 
 // ---- SGD with momentum ---------------------------------------------------------------------------
