@@ -1,0 +1,139 @@
+"""Benchmark of the whole training step (forward + pullbacks + SGD-momentum) on one MI355X.
+
+Workload: the ResNet-50-shaped bottleneck net, batch 64 of 3x224x224, bf16 activations and
+working weights with fp32 accumulation and fp32 master weights, synthetic N(0,1) inputs.
+One "step" is one call of s4tf_train_step over one resident batch.  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+METRIC = "train images/sec (fwd+VJP+SGD), ResNet-50 shape bs64 bf16; MFMA util %"
+PEAK = {"bf16": 2500.0, "f32": 157.3}   # dense MFMA TFLOP/s, MI355X
+
+
+def conv_flops(net, shapes):
+    """Algorithmic FLOPs of one step, per kernel class: 2*N*P*Q*K*R*S*C/groups per pass."""
+    out = {"conv_fwd_igemm": 0.0, "conv_dgrad_igemm": 0.0, "conv_wgrad_igemm": 0.0,
+           "dwconv_fwd": 0.0, "dwconv_dgrad": 0.0, "dwconv_wgrad": 0.0}
+    for i, op in enumerate(net["ops"]):
+        n, h, w, c = shapes[op["in"]]
+        if op["kind"] == "conv":
+            _, p, q, k = shapes[i + 1]
+            f = 2.0 * n * p * q * k * op["r"] * op["s"] * c / op["groups"]
+            pre = "dwconv_" if op["groups"] > 1 else "conv_"
+            suf = "" if op["groups"] > 1 else "_igemm"
+            out[pre + "fwd" + suf] += f
+            out[pre + "wgrad" + suf] += f
+            if op["in"] != 0:
+                out[pre + "dgrad" + suf] += f
+        elif op["kind"] == "head":   # its dense layer runs on the same kernels
+            f = 2.0 * n * c * op["classes"]
+            out["conv_fwd_igemm"] += f
+            out["conv_wgrad_igemm"] += f
+            out["conv_dgrad_igemm"] += f
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    from paper_2102_13243_amd import binding as B
+    from workloads import nets
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    kw = {"batch": args.batch} if args.batch else {}
+    net = nets.CONFIGS[args.workload](**kw)
+    wl = nets.make_workload(net)
+    st = B.TrainState(net, wl["params"], "cuda:0")
+    xd, ld = st.upload_batch(wl["x"], wl["labels"])
+    batch = net["input"][0]
+
+    for _ in range(args.warmup):
+        st.step(xd, ld)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.step(xd, ld)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    loss = float(st.loss[0].item())
+
+    # Per-kernel-class durations: the same steps again with every launch bracketed by HIP events on
+    # the launch stream (kept out of the timed region above so the events do not perturb it).
+    B.s4tf_profile_enable(True)
+    prof_steps = max(1, min(args.steps, 10))
+    for _ in range(prof_steps):
+        st.step(xd, ld)
+    torch.cuda.synchronize()
+    prof = B.s4tf_profile_collect()
+    B.s4tf_profile_enable(False)
+    shapes = nets.tensor_shapes(net)
+    flops = conv_flops(net, shapes)
+    classes = {}
+    for name, (ms, cnt) in prof.items():
+        classes[name] = {"ms_per_step": ms / prof_steps, "launches_per_step": cnt / prof_steps}
+        if flops.get(name):
+            classes[name]["tflops"] = flops[name] / (ms / prof_steps * 1e-3) / 1e12
+    dom = max(classes, key=lambda k: classes[k]["ms_per_step"])
+    dtype = net["dtype"]
+    roofline = None
+    if flops.get(dom) and dom.startswith("conv_"):
+        ach = classes[dom]["tflops"]
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": PEAK[dtype], "unit": "TFLOP/s",
+                    "frac": round(ach / PEAK[dtype], 4), "traffic": None,
+                    "launches_per_step": classes[dom]["launches_per_step"],
+                    "avg_launch_ms": classes[dom]["ms_per_step"] / classes[dom]["launches_per_step"],
+                    "flops_per_step": flops[dom]}
+    conv_ms = sum(classes[k]["ms_per_step"] for k in ("conv_fwd_igemm", "conv_dgrad_igemm", "conv_wgrad_igemm") if k in classes)
+    conv_fl = sum(flops[k] for k in ("conv_fwd_igemm", "conv_dgrad_igemm", "conv_wgrad_igemm"))
+    mfma_util = conv_fl / (conv_ms * 1e-3) / 1e12 / PEAK[dtype] if conv_ms else None
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        # a bounded sample of the same workload: same net and image size at a small batch, one step
+        sb = {"resnet50": 8, "mobilenetv2": 8, "resnet56": 64}.get(args.workload, batch)
+        sb = min(sb, batch)
+        snet = nets.CONFIGS[args.workload](batch=sb)
+        swl = nets.make_workload(snet)
+        t0 = time.perf_counter()
+        orc.train_step(snet, swl["x"], swl["labels"], swl["params"])
+        ct = time.perf_counter() - t0
+        cpu = {"value": round(sb / ct, 4), "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": "one oracle step of the same net and image size at batch %d (%.1f s)" % (sb, ct)}
+
+    out = {
+        "metric": METRIC, "value": round(batch / (ms_per_step * 1e-3), 1), "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": "%s-shaped net, batch %d of %dx%dx%d, %s storage, fp32 accumulate, SGD-momentum; one "
+                               "s4tf_train_step per step" % (net["name"], batch, net["input"][3], net["input"][1],
+                                                              net["input"][2], dtype),
+                   "params": nets.param_count(wl["params"]), "loss_after": round(loss, 5)},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "mfma_util_convs": None if mfma_util is None else round(mfma_util, 4),
+        "kernel_classes": {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in sorted(classes.items())},
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -2,12 +2,14 @@
 // Every kernel here is bound by HBM bandwidth.  All of them use the same decomposition:
 // grid = (channel blocks, pixel chunks); a thread = (channel vector of V adjacent channels,
 // pixel lane) keeps its per-channel constants in registers and walks its pixels with 16-byte
-// accesses, so a wavefront reads whole contiguous runs of the NHWC tensor.
+// accesses, four pixels in flight per thread, so a wavefront reads whole contiguous runs of
+// the NHWC tensor and enough loads are outstanding to cover the memory latency.
 //   forward   stats: per-channel sum and sum of squares of (x - pivot), pivot = x at pixel 0
-//             (keeps the one-pass variance free of cancellation); lanes are added in LDS in a
-//             fixed order, chunks are added in double by a finalize kernel -> mean, invstd
+//             (keeps the one-pass variance free of cancellation); the pixel lanes of a block are
+//             added with wavefront shuffles and LDS in a fixed order, the blocks' partial sums
+//             are added in double by a finalize kernel -> mean, invstd
 //             apply:  y = act(gamma*(x-mean)*invstd + beta (+ residual))
-//   pullback  reduce: dbeta = sum dz, dgamma = sum dz*xhat with dz = dy*act'(y)
+//   pullback  reduce: dbeta = sum dz, dgamma = sum dz*xhat with dz = dy*act'(y)   (in double)
 //             apply:  dx = gamma*invstd*(dz - dbeta/m - xhat*dgamma/m),  dresidual (+)= dz
 #include "s4tf_internal.h"
 #include "pack.h"
@@ -15,12 +17,15 @@
 namespace s4tf {
 namespace {
 
+constexpr int MAX_CHUNKS = 2048;
+constexpr int UNROLL = 4;
+
 struct Plan {
   int V, cvb, cblocks, pl, chunks;
   long long per;  // pixels per chunk
 };
 
-Plan make_plan(size_t M, int C, int dtype) {
+Plan make_plan(size_t M, int C, int dtype, int target_blocks, int min_pixels_per_lane) {
   Plan p;
   int V = dtype == S4TF_BF16 ? 8 : 4;
   if (C % V) V = 1;
@@ -31,30 +36,56 @@ Plan make_plan(size_t M, int C, int dtype) {
   p.cvb = cvb;
   p.cblocks = (CV + cvb - 1) / cvb;
   p.pl = 256 / cvb;
-  long long want = 2048 / p.cblocks;
+  long long want = target_blocks / p.cblocks;
   if (want < 1) want = 1;
+  if (want > MAX_CHUNKS) want = MAX_CHUNKS;
   long long per = ((long long)M + want - 1) / want;
-  long long minper = (long long)p.pl * 4;
+  long long minper = (long long)p.pl * min_pixels_per_lane;
   if (per < minper) per = minper;
   p.per = per;
   p.chunks = (int)(((long long)M + per - 1) / per);
   return p;
 }
 
-// add the pixel lanes of a block in a fixed order; result valid for pl == 0
-template <int NV>
-__device__ inline void block_lane_sum(float (&v)[NV], float* red, int cvb, int pl_count, int cvl, int pl) {
-  float* mine = red + (size_t)(pl * cvb + cvl) * NV;
+// Sum over the pixel lanes of a block; the result is valid in the threads with pl == 0.
+// Thread t has cvl = t % cvb with cvb a power of two <= 64, so inside a wavefront the lanes that
+// share a channel vector are the ones whose lane ids differ by multiples of cvb: a butterfly of
+// lane shuffles adds them, then the four wavefronts are added through LDS.  The order of the
+// additions is fixed, so the result does not depend on scheduling.
+template <typename A, int NV>
+__device__ inline void block_lane_sum(A (&v)[NV], A* red, int cvb, int cvl) {
+  for (int off = cvb; off < 64; off <<= 1) {
 #pragma unroll
-  for (int e = 0; e < NV; ++e) mine[e] = v[e];
+    for (int e = 0; e < NV; ++e) v[e] += __shfl_xor(v[e], off, 64);
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane < cvb) {
+#pragma unroll
+    for (int e = 0; e < NV; ++e) red[(size_t)(wave * cvb + cvl) * NV + e] = v[e];
+  }
   __syncthreads();
-  if (pl == 0) {
+  if (threadIdx.x < cvb) {
 #pragma unroll
-    for (int e = 0; e < NV; ++e) {
-      float s = 0.f;
-      for (int l = 0; l < pl_count; ++l) s += red[(size_t)(l * cvb + cvl) * NV + e];
-      v[e] = s;
-    }
+    for (int e = 0; e < NV; ++e)
+      v[e] = ((red[(size_t)cvl * NV + e] + red[(size_t)(cvb + cvl) * NV + e]) + red[(size_t)(2 * cvb + cvl) * NV + e]) +
+             red[(size_t)(3 * cvb + cvl) * NV + e];
+  }
+}
+
+// Walk the pixels first, first+step, ... < p1 of a chunk, UNROLL at a time: `load(m, slot)` issues
+// the loads of pixel m into slot, `use(m, slot)` consumes them.
+template <typename Load, typename Use>
+__device__ inline void walk_pixels(long long first, long long p1, long long step, Load load, Use use) {
+  long long m = first;
+  for (; m + (UNROLL - 1) * step < p1; m += UNROLL * step) {
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) load(m + u * step, u);
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) use(m + u * step, u);
+  }
+  for (; m < p1; m += step) {
+    load(m, 0);
+    use(m, 0);
   }
 }
 
@@ -70,19 +101,22 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ x, 
   float acc[2 * V];
 #pragma unroll
   for (int e = 0; e < 2 * V; ++e) acc[e] = 0.f;
-  Pack<T, V> pv = ldp<T, V>(x + c);
+  const Pack<T, V> pv = ldp<T, V>(x + c);
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
-  if (live)
-    for (long long m = p0 + pl; m < p1; m += pl_count) {
-      Pack<T, V> xv = ldp<T, V>(x + m * C + c);
+  if (live) {
+    Pack<T, V> xv[UNROLL];
+    walk_pixels(p0 + pl, p1, pl_count,
+                [&](long long m, int u) { xv[u] = ldp<T, V>(x + m * C + c); },
+                [&](long long, int u) {
 #pragma unroll
-      for (int e = 0; e < V; ++e) {
-        float d = xv.get(e) - pv.get(e);
-        acc[e] += d;
-        acc[V + e] += d * d;
-      }
-    }
-  block_lane_sum<2 * V>(acc, red, cvb, pl_count, cvl, pl);
+                  for (int e = 0; e < V; ++e) {
+                    float d = xv[u].get(e) - pv.get(e);
+                    acc[e] += d;
+                    acc[V + e] += d * d;
+                  }
+                });
+  }
+  block_lane_sum<float, 2 * V>(acc, red, cvb, cvl);
   if (pl == 0 && live) {
     float* dst = part + (long long)blockIdx.y * 2 * C;
 #pragma unroll
@@ -93,17 +127,37 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ x, 
   }
 }
 
+// Adds the chunks' partial sums [chunk][2][C] of 8 channels per block in double: 32 lanes per
+// channel stride over the chunks, then lane 0 adds the 32 lane totals in order.
+template <typename P>
+__device__ inline void sum_chunks(const P* __restrict__ part, int chunks, int C, int c, int zl, double (*sh)[2][8],
+                                  double& s1, double& s2) {
+  double a = 0.0, b = 0.0;
+  if (c < C)
+    for (int z = zl; z < chunks; z += 32) {
+      a += (double)part[(long long)z * 2 * C + c];
+      b += (double)part[(long long)z * 2 * C + C + c];
+    }
+  sh[zl][0][threadIdx.x & 7] = a;
+  sh[zl][1][threadIdx.x & 7] = b;
+  __syncthreads();
+  s1 = s2 = 0.0;
+  if (zl == 0)
+    for (int l = 0; l < 32; ++l) {
+      s1 += sh[l][0][threadIdx.x & 7];
+      s2 += sh[l][1][threadIdx.x & 7];
+    }
+}
+
 template <typename T>
-__global__ void bn_stats_finalize_kernel(const T* __restrict__ x, const float* __restrict__ part, int chunks,
-                                         long long M, int C, float eps, float* __restrict__ mean,
-                                         float* __restrict__ invstd) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= C) return;
-  double s1 = 0.0, s2 = 0.0;
-  for (int z = 0; z < chunks; ++z) {
-    s1 += (double)part[(long long)z * 2 * C + c];
-    s2 += (double)part[(long long)z * 2 * C + C + c];
-  }
+__global__ __launch_bounds__(256) void bn_stats_finalize_kernel(const T* __restrict__ x, const float* __restrict__ part,
+                                                                int chunks, long long M, int C, float eps,
+                                                                float* __restrict__ mean, float* __restrict__ invstd) {
+  __shared__ double sh[32][2][8];
+  const int c = blockIdx.x * 8 + (threadIdx.x & 7), zl = threadIdx.x >> 3;
+  double s1, s2;
+  sum_chunks<float>(part, chunks, C, c, zl, sh, s1, s2);
+  if (zl != 0 || c >= C) return;
   double pivot = (double)to_f32<T>(x[c]);
   double ms = s1 / (double)M;
   double var = s2 / (double)M - ms * ms;
@@ -131,18 +185,22 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
     be[e] = beta[c + e];
   }
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
-  for (long long m = p0 + pl; m < p1; m += pl_count) {
-    Pack<T, V> xv = ldp<T, V>(x + m * C + c), o;
-    if (res) {
-      Pack<T, V> rv = ldp<T, V>(res + m * C + c);
+  Pack<T, V> xv[UNROLL], rv[UNROLL];
+  walk_pixels(p0 + pl, p1, pl_count,
+              [&](long long m, int u) {
+                xv[u] = ldp<T, V>(x + m * C + c);
+                if (res) rv[u] = ldp<T, V>(res + m * C + c);
+              },
+              [&](long long m, int u) {
+                Pack<T, V> o;
 #pragma unroll
-      for (int e = 0; e < V; ++e) o.set(e, act_apply((xv.get(e) - mu[e]) * sc[e] + be[e] + rv.get(e), act));
-    } else {
-#pragma unroll
-      for (int e = 0; e < V; ++e) o.set(e, act_apply((xv.get(e) - mu[e]) * sc[e] + be[e], act));
-    }
-    stp<T, V>(y + m * C + c, o);
-  }
+                for (int e = 0; e < V; ++e) {
+                  float z = (xv[u].get(e) - mu[e]) * sc[e] + be[e];
+                  if (res) z += rv[u].get(e);
+                  o.set(e, act_apply(z, act));
+                }
+                stp<T, V>(y + m * C + c, o);
+              });
 }
 
 // dbeta and dgamma are sums of cotangents whose terms largely cancel (the cotangent reaching a
@@ -159,56 +217,51 @@ __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict_
   const int cv = blockIdx.x * cvb + cvl;
   const bool live = cv < CV;
   const int c = live ? cv * V : 0;
-  double acc[2 * V], mu[V], is[V];
+  double acc[2 * V];
+  float mu[V], is[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) {
     acc[e] = acc[V + e] = 0.0;
-    mu[e] = (double)mean[c + e];
-    is[e] = (double)invstd[c + e];
+    mu[e] = mean[c + e];
+    is[e] = invstd[c + e];
   }
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
-  if (live)
-    for (long long m = p0 + pl; m < p1; m += pl_count) {
-      Pack<T, V> xv = ldp<T, V>(x + m * C + c), dv = ldp<T, V>(dy + m * C + c);
-      float dz[V];
-      if (act != S4TF_ACT_NONE) {
-        Pack<T, V> yv = ldp<T, V>(y + m * C + c);
+  if (live) {
+    Pack<T, V> xv[UNROLL], dv[UNROLL], yv[UNROLL];
+    walk_pixels(p0 + pl, p1, pl_count,
+                [&](long long m, int u) {
+                  xv[u] = ldp<T, V>(x + m * C + c);
+                  dv[u] = ldp<T, V>(dy + m * C + c);
+                  if (act != S4TF_ACT_NONE) yv[u] = ldp<T, V>(y + m * C + c);
+                },
+                [&](long long, int u) {
 #pragma unroll
-        for (int e = 0; e < V; ++e) dz[e] = dv.get(e) * act_mask(yv.get(e), act);
-      } else {
-#pragma unroll
-        for (int e = 0; e < V; ++e) dz[e] = dv.get(e);
-      }
-#pragma unroll
-      for (int e = 0; e < V; ++e) {
-        acc[e] += (double)dz[e];
-        acc[V + e] += (double)dz[e] * (((double)xv.get(e) - mu[e]) * is[e]);
-      }
-    }
-  double* mine = redd + (size_t)(pl * cvb + cvl) * 2 * V;
-#pragma unroll
-  for (int e = 0; e < 2 * V; ++e) mine[e] = acc[e];
-  __syncthreads();
+                  for (int e = 0; e < V; ++e) {
+                    float dz = dv[u].get(e);
+                    if (act != S4TF_ACT_NONE) dz *= act_mask(yv[u].get(e), act);
+                    acc[e] += (double)dz;
+                    acc[V + e] += (double)dz * (((double)xv[u].get(e) - (double)mu[e]) * (double)is[e]);
+                  }
+                });
+  }
+  block_lane_sum<double, 2 * V>(acc, redd, cvb, cvl);
   if (pl == 0 && live) {
     double* dst = part + (long long)blockIdx.y * 2 * C;
 #pragma unroll
-    for (int e = 0; e < 2 * V; ++e) {
-      double sum = 0.0;
-      for (int l = 0; l < pl_count; ++l) sum += redd[(size_t)(l * cvb + cvl) * 2 * V + e];
-      if (e < V) dst[c + e] = sum; else dst[C + c + (e - V)] = sum;
+    for (int e = 0; e < V; ++e) {
+      dst[c + e] = acc[e];
+      dst[C + c + e] = acc[V + e];
     }
   }
 }
 
-__global__ void bn_vjp_finalize_kernel(const double* __restrict__ part, int chunks, int C, float* __restrict__ dgamma,
-                                       float* __restrict__ dbeta) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= C) return;
-  double s1 = 0.0, s2 = 0.0;
-  for (int z = 0; z < chunks; ++z) {
-    s1 += part[(long long)z * 2 * C + c];
-    s2 += part[(long long)z * 2 * C + C + c];
-  }
+__global__ __launch_bounds__(256) void bn_vjp_finalize_kernel(const double* __restrict__ part, int chunks, int C,
+                                                              float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  __shared__ double sh[32][2][8];
+  const int c = blockIdx.x * 8 + (threadIdx.x & 7), zl = threadIdx.x >> 3;
+  double s1, s2;
+  sum_chunks<double>(part, chunks, C, c, zl, sh, s1, s2);
+  if (zl != 0 || c >= C) return;
   dbeta[c] = (float)s1;
   dgamma[c] = (float)s2;
 }
@@ -218,8 +271,8 @@ __global__ __launch_bounds__(256) void bn_vjp_apply_kernel(const T* __restrict__
                                                            const T* __restrict__ dy, const float* __restrict__ gamma,
                                                            const float* __restrict__ mean, const float* __restrict__ invstd,
                                                            const float* __restrict__ dgamma, const float* __restrict__ dbeta,
-                                                           T* __restrict__ dx, T* __restrict__ dres, int acc_dres,
-                                                           long long M, int C, int cvb, long long per, int act) {
+                                                           T* __restrict__ dx, T* dres, int acc_dres, long long M, int C,
+                                                           int cvb, long long per, int act) {
   const int CV = C / V, pl_count = blockDim.x / cvb;
   const int cvl = threadIdx.x % cvb, pl = threadIdx.x / cvb;
   const int cv = blockIdx.x * cvb + cvl;
@@ -236,35 +289,27 @@ __global__ __launch_bounds__(256) void bn_vjp_apply_kernel(const T* __restrict__
     mg[e] = dgamma[c + e] * invM;
   }
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
-  for (long long m = p0 + pl; m < p1; m += pl_count) {
-    Pack<T, V> xv = ldp<T, V>(x + m * C + c), dv = ldp<T, V>(dy + m * C + c), o, r;
-    float dz[V];
-    if (act != S4TF_ACT_NONE) {
-      Pack<T, V> yv = ldp<T, V>(y + m * C + c);
+  Pack<T, V> xv[UNROLL], dv[UNROLL], yv[UNROLL], ov[UNROLL];
+  walk_pixels(p0 + pl, p1, pl_count,
+              [&](long long m, int u) {
+                xv[u] = ldp<T, V>(x + m * C + c);
+                dv[u] = ldp<T, V>(dy + m * C + c);
+                if (act != S4TF_ACT_NONE) yv[u] = ldp<T, V>(y + m * C + c);
+                if (dres && acc_dres) ov[u] = ldp<T, V>(dres + m * C + c);
+              },
+              [&](long long m, int u) {
+                Pack<T, V> o, r;
 #pragma unroll
-      for (int e = 0; e < V; ++e) dz[e] = dv.get(e) * act_mask(yv.get(e), act);
-    } else {
-#pragma unroll
-      for (int e = 0; e < V; ++e) dz[e] = dv.get(e);
-    }
-#pragma unroll
-    for (int e = 0; e < V; ++e) o.set(e, gs[e] * (dz[e] - mb[e] - (xv.get(e) - mu[e]) * is[e] * mg[e]));
-    stp<T, V>(dx + m * C + c, o);
-    if (dres) {
-      if (acc_dres) {
-        Pack<T, V> old = ldp<T, V>(dres + m * C + c);
-#pragma unroll
-        for (int e = 0; e < V; ++e) r.set(e, old.get(e) + dz[e]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < V; ++e) r.set(e, dz[e]);
-      }
-      stp<T, V>(dres + m * C + c, r);
-    }
-  }
+                for (int e = 0; e < V; ++e) {
+                  float dz = dv[u].get(e);
+                  if (act != S4TF_ACT_NONE) dz *= act_mask(yv[u].get(e), act);
+                  o.set(e, gs[e] * (dz - mb[e] - (xv[u].get(e) - mu[e]) * is[e] * mg[e]));
+                  if (dres) r.set(e, acc_dres ? ov[u].get(e) + dz : dz);
+                }
+                stp<T, V>(dx + m * C + c, o);
+                if (dres) stp<T, V>(dres + m * C + c, r);
+              });
 }
-
-constexpr int MAX_CHUNKS = 2048;
 
 }  // namespace
 
@@ -273,44 +318,41 @@ size_t bn_workspace(size_t M, int C) {
   return (size_t)MAX_CHUNKS * 2 * C * sizeof(double);
 }
 
+// KERNEL<T, V> for the descriptor's dtype and the plan's vector width
+#define BN_LAUNCH(KERNEL, plan, shm, ...)                                                                       \
+  do {                                                                                                          \
+    dim3 grid_((plan).cblocks, (plan).chunks), block_(256);                                                     \
+    if (d.dtype == S4TF_BF16) {                                                                                 \
+      typedef bf16_t T;                                                                                         \
+      if ((plan).V == 8) hipLaunchKernelGGL((KERNEL<T, 8>), grid_, block_, shm, st, __VA_ARGS__);               \
+      else hipLaunchKernelGGL((KERNEL<T, 1>), grid_, block_, shm, st, __VA_ARGS__);                             \
+    } else {                                                                                                    \
+      typedef float T;                                                                                          \
+      if ((plan).V == 4) hipLaunchKernelGGL((KERNEL<T, 4>), grid_, block_, shm, st, __VA_ARGS__);               \
+      else hipLaunchKernelGGL((KERNEL<T, 1>), grid_, block_, shm, st, __VA_ARGS__);                             \
+    }                                                                                                           \
+  } while (0)
+
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
            void* y, float* mean, float* invstd, void* ws, hipStream_t st) {
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
-  Plan p = make_plan((size_t)M, C, d.dtype);
+  const Plan pr = make_plan((size_t)M, C, d.dtype, 1024, 16);  // reduction: fewer, longer blocks
+  const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, 8);
   float* part = static_cast<float*>(ws);
-  dim3 grid(p.cblocks, p.chunks), block(256);
+  int rc;
   {
     ProfScope ps(PC_BN_STATS, st);
-    size_t shm = (size_t)256 * 2 * p.V * sizeof(float);
-#define XT(T) (const T*)x
-    if (d.dtype == S4TF_BF16) {
-      if (p.V == 8) hipLaunchKernelGGL((bn_stats_kernel<bf16_t, 8>), grid, block, shm, st, XT(bf16_t), part, M, C, p.cvb, p.per);
-      else hipLaunchKernelGGL((bn_stats_kernel<bf16_t, 1>), grid, block, shm, st, XT(bf16_t), part, M, C, p.cvb, p.per);
-    } else {
-      if (p.V == 4) hipLaunchKernelGGL((bn_stats_kernel<float, 4>), grid, block, shm, st, XT(float), part, M, C, p.cvb, p.per);
-      else hipLaunchKernelGGL((bn_stats_kernel<float, 1>), grid, block, shm, st, XT(float), part, M, C, p.cvb, p.per);
-    }
-    int rc = launch_status("bn_stats");
-    if (rc != S4TF_OK) return rc;
+    BN_LAUNCH(bn_stats_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(float), (const T*)x, part, M, C, pr.cvb, pr.per);
+    if ((rc = launch_status("bn_stats")) != S4TF_OK) return rc;
     if (d.dtype == S4TF_BF16)
-      hipLaunchKernelGGL((bn_stats_finalize_kernel<bf16_t>), dim3((C + 63) / 64), dim3(64), 0, st, XT(bf16_t), part, p.chunks, M, C, d.eps, mean, invstd);
+      hipLaunchKernelGGL((bn_stats_finalize_kernel<bf16_t>), dim3((C + 7) / 8), dim3(256), 0, st, (const bf16_t*)x, part, pr.chunks, M, C, d.eps, mean, invstd);
     else
-      hipLaunchKernelGGL((bn_stats_finalize_kernel<float>), dim3((C + 63) / 64), dim3(64), 0, st, XT(float), part, p.chunks, M, C, d.eps, mean, invstd);
-    rc = launch_status("bn_stats_finalize");
-    if (rc != S4TF_OK) return rc;
+      hipLaunchKernelGGL((bn_stats_finalize_kernel<float>), dim3((C + 7) / 8), dim3(256), 0, st, (const float*)x, part, pr.chunks, M, C, d.eps, mean, invstd);
+    if ((rc = launch_status("bn_stats_finalize")) != S4TF_OK) return rc;
   }
   ProfScope ps(PC_BN_APPLY, st);
-  size_t shm = 0;
-  if (d.dtype == S4TF_BF16) {
-    typedef bf16_t T;
-    if (p.V == 8) hipLaunchKernelGGL((bn_apply_kernel<T, 8>), grid, block, shm, st, (const T*)x, (const T*)res, gamma, beta, mean, invstd, (T*)y, M, C, p.cvb, p.per, d.act);
-    else hipLaunchKernelGGL((bn_apply_kernel<T, 1>), grid, block, shm, st, (const T*)x, (const T*)res, gamma, beta, mean, invstd, (T*)y, M, C, p.cvb, p.per, d.act);
-  } else {
-    typedef float T;
-    if (p.V == 4) hipLaunchKernelGGL((bn_apply_kernel<T, 4>), grid, block, shm, st, (const T*)x, (const T*)res, gamma, beta, mean, invstd, (T*)y, M, C, p.cvb, p.per, d.act);
-    else hipLaunchKernelGGL((bn_apply_kernel<T, 1>), grid, block, shm, st, (const T*)x, (const T*)res, gamma, beta, mean, invstd, (T*)y, M, C, p.cvb, p.per, d.act);
-  }
+  BN_LAUNCH(bn_apply_kernel, pa, 0, (const T*)x, (const T*)res, gamma, beta, mean, invstd, (T*)y, M, C, pa.cvb, pa.per, d.act);
   return launch_status("bn_apply");
 }
 
@@ -319,38 +361,21 @@ int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gam
            void* ws, hipStream_t st) {
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
-  Plan p = make_plan((size_t)M, C, d.dtype);
+  const Plan pr = make_plan((size_t)M, C, d.dtype, 1024, 16);
+  const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, 8);
   double* part = static_cast<double*>(ws);
-  dim3 grid(p.cblocks, p.chunks), block(256);
+  int rc;
   {
     ProfScope ps(PC_BN_VJP_REDUCE, st);
-    size_t shm = (size_t)256 * 2 * p.V * sizeof(double);
-    if (d.dtype == S4TF_BF16) {
-      typedef bf16_t T;
-      if (p.V == 8) hipLaunchKernelGGL((bn_vjp_reduce_kernel<T, 8>), grid, block, shm, st, (const T*)x, (const T*)y, (const T*)dy, mean, invstd, part, M, C, p.cvb, p.per, d.act);
-      else hipLaunchKernelGGL((bn_vjp_reduce_kernel<T, 1>), grid, block, shm, st, (const T*)x, (const T*)y, (const T*)dy, mean, invstd, part, M, C, p.cvb, p.per, d.act);
-    } else {
-      typedef float T;
-      if (p.V == 4) hipLaunchKernelGGL((bn_vjp_reduce_kernel<T, 4>), grid, block, shm, st, (const T*)x, (const T*)y, (const T*)dy, mean, invstd, part, M, C, p.cvb, p.per, d.act);
-      else hipLaunchKernelGGL((bn_vjp_reduce_kernel<T, 1>), grid, block, shm, st, (const T*)x, (const T*)y, (const T*)dy, mean, invstd, part, M, C, p.cvb, p.per, d.act);
-    }
-    int rc = launch_status("bn_vjp_reduce");
-    if (rc != S4TF_OK) return rc;
-    hipLaunchKernelGGL(bn_vjp_finalize_kernel, dim3((C + 63) / 64), dim3(64), 0, st, part, p.chunks, C, dgamma, dbeta);
-    rc = launch_status("bn_vjp_finalize");
-    if (rc != S4TF_OK) return rc;
+    BN_LAUNCH(bn_vjp_reduce_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(double), (const T*)x, (const T*)y, (const T*)dy,
+              mean, invstd, part, M, C, pr.cvb, pr.per, d.act);
+    if ((rc = launch_status("bn_vjp_reduce")) != S4TF_OK) return rc;
+    hipLaunchKernelGGL(bn_vjp_finalize_kernel, dim3((C + 7) / 8), dim3(256), 0, st, part, pr.chunks, C, dgamma, dbeta);
+    if ((rc = launch_status("bn_vjp_finalize")) != S4TF_OK) return rc;
   }
   ProfScope ps(PC_BN_VJP_APPLY, st);
-  size_t shm = 0;
-  if (d.dtype == S4TF_BF16) {
-    typedef bf16_t T;
-    if (p.V == 8) hipLaunchKernelGGL((bn_vjp_apply_kernel<T, 8>), grid, block, shm, st, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, dgamma, dbeta, (T*)dx, (T*)dres, d.accumulate_dres, M, C, p.cvb, p.per, d.act);
-    else hipLaunchKernelGGL((bn_vjp_apply_kernel<T, 1>), grid, block, shm, st, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, dgamma, dbeta, (T*)dx, (T*)dres, d.accumulate_dres, M, C, p.cvb, p.per, d.act);
-  } else {
-    typedef float T;
-    if (p.V == 4) hipLaunchKernelGGL((bn_vjp_apply_kernel<T, 4>), grid, block, shm, st, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, dgamma, dbeta, (T*)dx, (T*)dres, d.accumulate_dres, M, C, p.cvb, p.per, d.act);
-    else hipLaunchKernelGGL((bn_vjp_apply_kernel<T, 1>), grid, block, shm, st, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, dgamma, dbeta, (T*)dx, (T*)dres, d.accumulate_dres, M, C, p.cvb, p.per, d.act);
-  }
+  BN_LAUNCH(bn_vjp_apply_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, dgamma, dbeta, (T*)dx,
+            (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);
   return launch_status("bn_vjp_apply");
 }
 
