@@ -25,7 +25,7 @@ constexpr int NUM_XCD = 8;   // workgroup ids are dealt round-robin to the 8 XCD
 
 template <typename T> struct Cfg;
 template <> struct Cfg<float> { static constexpr int VEC = 4, BK = 16, PAD = 1; };
-template <> struct Cfg<bf16_t> { static constexpr int VEC = 8, BK = 32, PAD = 8; };
+template <> struct Cfg<bf16_t> { static constexpr int VEC = 8, BK = 64, PAD = 8; };
 
 struct Args {
   ConvGeom g;
@@ -511,6 +511,52 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
 
   // epilogue.  A 32x32 accumulator block: lane holds column (lane & 31) and, in register v,
   // row 8*(v/4) + 4*(lane >> 5) + (v % 4).
+  if constexpr (sizeof(T) == 2 && PASS != PASS_WGRAD && VECMODE) {
+    // 16-bit outputs with channel counts that are multiples of 8: stage the fp32 tile in LDS (the k-loop's buffers are free now) so that each
+    // lane then writes 8 adjacent outputs (16 bytes) and a wavefront writes whole rows of the tile
+    constexpr int CS = BN + 4;  // row stride in floats: rows 4 banks apart, conflict-free column writes
+    static_assert(BM * CS * 4 <= 2 * TILE * (int)sizeof(T), "C tile must fit in the staging buffers");
+    float* cs = reinterpret_cast<float*>(smem);
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int col = brow + j * 32 + (lane & 31);
+        const float bias = (PASS == PASS_FWD && a.bias && n0 + col < a.Ng) ? a.bias[n0 + col] : 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = arow + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+          float val = acc[i][j][v];
+          if constexpr (PASS == PASS_FWD) val = act_apply(val + bias, a.act);
+          cs[row * CS + col] = val;
+        }
+      }
+    __syncthreads();
+    T* out = static_cast<T*>(a.out);
+    constexpr int CPR = BN / 8;  // 16-byte chunks per tile row
+#pragma unroll
+    for (int it = 0; it < BM * CPR / NT; ++it) {
+      const int chunk = tid + it * NT;
+      const int row = chunk / CPR, col = (chunk % CPR) * 8;
+      if (m0 + row >= a.Mg || n0 + col >= a.Ng) continue;
+      const float4 lo = *reinterpret_cast<const float4*>(&cs[row * CS + col]);
+      const float4 hi = *reinterpret_cast<const float4*>(&cs[row * CS + col + 4]);
+      float v8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      T* dst = out + (long long)(m0 + row) * a.Ng + n0 + col;
+      if (PASS == PASS_DGRAD && a.accumulate) {
+        const uint4 old = *reinterpret_cast<const uint4*>(dst);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v8[e] += bf16_to_f32((bf16_t)half_of(old, e));
+      }
+      uint4 o;
+      o.x = (uint32_t)f32_to_bf16(v8[0]) | ((uint32_t)f32_to_bf16(v8[1]) << 16);
+      o.y = (uint32_t)f32_to_bf16(v8[2]) | ((uint32_t)f32_to_bf16(v8[3]) << 16);
+      o.z = (uint32_t)f32_to_bf16(v8[4]) | ((uint32_t)f32_to_bf16(v8[5]) << 16);
+      o.w = (uint32_t)f32_to_bf16(v8[6]) | ((uint32_t)f32_to_bf16(v8[7]) << 16);
+      *reinterpret_cast<uint4*>(dst) = o;
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -539,13 +585,24 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
     }
 }
 
-__global__ void splitk_reduce_kernel(const float* __restrict__ part, float* __restrict__ out, long long n,
-                                     int splits) {
-  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
+// out[i] = sum over splits of part[z][i], in a fixed order: 16 lanes stride over the splits of
+// 16 adjacent outputs, then lane 0 adds the 16 lane totals.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                            long long n, int splits) {
+  __shared__ float sh[16][17];
+  const int ol = threadIdx.x & 15, zl = threadIdx.x >> 4;
+  const long long i = (long long)blockIdx.x * 16 + ol;
   float s = 0.f;
-  for (int z = 0; z < splits; ++z) s += part[(long long)z * n + i];
-  out[i] = s;
+  if (i < n)
+    for (int z = zl; z < splits; z += 16) s += part[(long long)z * n + i];
+  sh[zl][ol] = s;
+  __syncthreads();
+  if (zl == 0 && i < n) {
+    float t = 0.f;
+#pragma unroll
+    for (int l = 0; l < 16; ++l) t += sh[l][ol];
+    out[i] = t;
+  }
 }
 
 template <typename T> bool vec_ok(const ConvGeom& g) {
@@ -643,7 +700,7 @@ int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, flo
   }
   if (rc != S4TF_OK || splits == 1) return rc;
   ProfScope ps(PC_WGRAD_REDUCE, st);
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, st,
                      static_cast<const float*>(ws), dw, n, splits);
   return launch_status("splitk_reduce");
 }
