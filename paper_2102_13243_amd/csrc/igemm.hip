@@ -12,6 +12,7 @@
 // Operands whose memory is contiguous along the GEMM row instead of along k (filters in the
 // forward pass, both operands of wgrad) are transposed in registers on their way into LDS.
 #include "s4tf_internal.h"
+#include "igemm_args.h"
 
 namespace s4tf {
 namespace {
@@ -19,26 +20,9 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-enum { PASS_FWD = 0, PASS_DGRAD = 1, PASS_WGRAD = 2 };
-constexpr int NT = 256;      // threads per block: 4 wavefronts
-constexpr int NUM_XCD = 8;   // workgroup ids are dealt round-robin to the 8 XCDs
-
 template <typename T> struct Cfg;
 template <> struct Cfg<float> { static constexpr int VEC = 4, BK = 16, PAD = 1; };
 template <> struct Cfg<bf16_t> { static constexpr int VEC = 8, BK = 64, PAD = 8; };
-
-struct Args {
-  ConvGeom g;
-  const void* a;
-  const void* b;
-  void* out;
-  const float* bias;
-  int Mg, Ng, Kg;
-  int act, accumulate, simple;
-  int nk, nk_per_split;
-  long long split_stride;
-  int tiles_m, tiles_n, tiles_per_xcd;
-};
 
 __device__ inline uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ inline uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
@@ -609,6 +593,27 @@ template <typename T> bool vec_ok(const ConvGeom& g) {
   return g.C % Cfg<T>::VEC == 0 && g.K % Cfg<T>::VEC == 0;
 }
 
+// x / d for 0 <= x < 2^31 as (mulhi(x, magic) >> shift); shift < 0 means d == 1
+void magic_div(int d, uint32_t& magic, int& shift) {
+  if (d <= 1) { magic = 0; shift = -1; return; }
+  int s = 0;
+  while ((1LL << s) < d) ++s;
+  magic = (uint32_t)(((1ULL << (31 + s)) + (unsigned long long)d - 1) / (unsigned long long)d);
+  shift = s - 1;
+}
+
+void fill_sizes(Args& a, int pass, int dtype) {
+  const ConvGeom& g = a.g;
+  const unsigned long long es = dtype_size(dtype);
+  const unsigned long long xs = (unsigned long long)g.N * g.H * g.W * g.C * es, ys = (unsigned long long)g.N * g.P * g.Q * g.K * es,
+                           ws = (unsigned long long)g.R * g.S * g.C * g.K * es;
+  auto clamp = [](unsigned long long v) { return (uint32_t)(v > 0xffffffffULL ? 0xffffffffULL : v); };
+  a.a_bytes = clamp(pass == PASS_DGRAD ? ys : xs);
+  a.b_bytes = clamp(pass == PASS_WGRAD ? ys : ws);
+  magic_div(g.Q, a.magicQ, a.shiftQ);
+  magic_div(g.P, a.magicP, a.shiftP);
+}
+
 void fill_tiles(Args& a, int BM, int BN, int BK) {
   a.tiles_m = (a.Mg + BM - 1) / BM;
   a.tiles_n = (a.Ng + BN - 1) / BN;
@@ -619,6 +624,7 @@ void fill_tiles(Args& a, int BM, int BN, int BK) {
 }
 
 template <typename T, int PASS> int launch(Args& a, int splits, hipStream_t st) {
+  if (sizeof(T) == 2 && igemm_dma_ok(PASS, a.g, a)) return igemm_dma_launch(PASS, a, splits, st);
   dim3 grid((unsigned)(a.tiles_per_xcd * NUM_XCD), (unsigned)splits);
   if (vec_ok<T>(a.g))
     hipLaunchKernelGGL((igemm_kernel<T, PASS, true, 2, 2, 2, 2>), grid, dim3(NT), 0, st, a);
@@ -647,6 +653,7 @@ int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const 
   a.g = g; a.a = x; a.b = w; a.out = y; a.bias = bias; a.act = act;
   a.Mg = g.N * g.P * g.Q; a.Ng = g.K; a.Kg = g.R * g.S * g.C;
   a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
+  fill_sizes(a, PASS_FWD, dtype);
   ProfScope ps(PC_CONV_FWD, st);
   if (dtype == S4TF_BF16) {
     fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
@@ -662,6 +669,7 @@ int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, voi
   a.g = g; a.a = dy; a.b = w; a.out = dx; a.accumulate = accumulate;
   a.Mg = g.N * g.H * g.W; a.Ng = g.C; a.Kg = g.R * g.S * g.K;
   a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
+  fill_sizes(a, PASS_DGRAD, dtype);
   ProfScope ps(PC_CONV_DGRAD, st);
   if (dtype == S4TF_BF16) {
     fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
@@ -684,6 +692,7 @@ int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, flo
   a.g = g; a.a = x; a.b = dy;
   a.Mg = g.R * g.S * g.C; a.Ng = g.K; a.Kg = g.N * g.P * g.Q;
   a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
+  fill_sizes(a, PASS_WGRAD, dtype);
   int splits, per;
   wgrad_split(g, dtype, splits, per);
   const long long n = (long long)a.Mg * a.Ng;

@@ -1,0 +1,501 @@
+// bf16 implicit-GEMM convolution, fast path for channel counts that are multiples of 8.
+//
+// Same GEMM view as igemm.hip (D[i][j] = sum_k A[i][k] B[j][k] for forward / dgrad / wgrad), but
+// the operand tiles go from global memory straight into LDS with 16-byte direct loads
+// (global_load_lds), so no VGPRs and no LDS-store instructions are spent on staging and several
+// k-tiles can be in flight: a ring of STAGES LDS buffers, one barrier per k-tile, vmcnt-based
+// waits.  A direct load writes 64 lanes x 16 bytes to one contiguous KiB of LDS, lane by lane; which
+// global chunk a lane fetches is free, and that freedom is the swizzle:
+//   * operands whose memory is contiguous along k (im2col rows of x or dy, filters in dgrad) are
+//     stored [row][k] with the 16-byte chunk index XOR-ed with (row >> 1) & 7, which makes the
+//     ds_read_b128 of an MFMA fragment (32 rows, one chunk each) conflict free;
+//   * operands whose memory is contiguous along the GEMM row (filters in the forward pass, x and
+//     dy in wgrad) are stored as they are, [k][row], and read with ds_read_b64_tr_b16, the LDS
+//     transpose load of gfx950, which hands each lane 4 consecutive k for its own row.
+// The loads are buffer loads: padding (image borders, ragged tiles, stride holes in dgrad) is an
+// out-of-range offset, which the hardware turns into zeros, so every lane always loads.  MFMA: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+#include "s4tf_internal.h"
+#include "igemm_args.h"
+
+namespace s4tf {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int BK = 64;        // k per stage: 128 bytes per row
+constexpr int ROWB = BK * 2;  // bytes per k-contiguous row
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t OOB = 0x80000000u;  // a byte offset past every tensor on this path: such a load returns zeros
+
+// Buffer resource over [base, base + bytes): a load whose offset is >= bytes writes zeros.
+__device__ inline i32x4 make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t p = (uint64_t)base;
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+  r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;
+  return r;
+}
+
+// One 16-byte chunk per lane: LDS[wave_base + lane*16 .. +16) = buffer[voff .. +16), zeros if out of range.
+// Issued as inline assembly on purpose: the compiler then does not count these loads, so it cannot
+// turn the hand-placed partial vmcnt waits of the k-loop into full ones (every LDS read after a
+// direct load it knows about gets a vmcnt(0)).  The loop orders LDS writes and reads itself: vmcnt
+// wait, then barrier.  The address work per load is a handful of VALU instructions (a fixed per-lane
+// offset plus a wavefront-uniform one, and a mask test): one MFMA lasts only 8 VALU issue slots.
+__device__ inline void dma16(uint32_t voff, i32x4 rsrc, char* wave_base) {
+  const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(wave_base));
+  asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" : : "v"(voff), "s"(rsrc), "s"(lds) : "memory");
+}
+template <int N> __device__ inline void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);  // vmcnt(N), other counters untouched
+}
+
+__device__ inline uint32_t half_of(const uint4& v, int e) {
+  uint32_t d = (e >> 1) == 0 ? v.x : (e >> 1) == 1 ? v.y : (e >> 1) == 2 ? v.z : v.w;
+  return (e & 1) ? (d >> 16) : (d & 0xffffu);
+}
+// x / d for 0 <= x < 2^31 with the host-computed (magic, shift) of Args (shift < 0: d == 1)
+__device__ inline int fast_div(int x, uint32_t magic, int shift) {
+  return shift < 0 ? x : (int)(__umulhi((uint32_t)x, magic) >> shift);
+}
+__device__ inline int log2_of(int v) { return 31 - __clz(v); }
+
+// ---- k-contiguous operands -----------------------------------------------------------------------
+// Tile-local row `row`, 16-byte chunk `kc` of its 128-byte k-run lives at byte
+//   (row*8 + (kc ^ ((row >> 1) & 7))) * 16.
+// Wave w fills the 1 KiB units u = w*UPW + i (8 rows each); lane l owns row 8u + l/8, slot l%8.
+template <int ROWS> struct KTile {
+  static constexpr int UPW = ROWS / 32;
+  __device__ static int row_of(int wave, int i, int lane) { return (wave * UPW + i) * 8 + (lane >> 3); }
+  __device__ static int kc_of(int wave, int i, int lane) { return (lane & 7) ^ ((row_of(wave, i, lane) >> 1) & 7); }
+  __device__ static int frag_off(int row, int kc) { return (row * 8 + (kc ^ ((row >> 1) & 7))) * 16; }
+};
+
+// Gathers of an image along k = (tap, channel): forward A reads x at (p*st + r - pad, q*st + s - pad),
+// dgrad A reads dy at ((h + pad - r)/st, (w + pad - s)/st).  Per row the byte offset splits into a
+// fixed per-lane part and a part that depends on the tap only, and whether a tap falls inside the
+// image is one bit of a per-row mask built once.  A k-tile of 64 lies inside one tap when the
+// channel count is a multiple of 64 (then the tap part is wavefront-uniform); channel counts 8, 16,
+// 32 put several taps in a k-tile and take the per-lane path.
+template <int ROWS, bool DGRAD> struct Gather {
+  typedef KTile<ROWS> TL;
+  i32x4 rsrc;
+  int loff[TL::UPW], kc[TL::UPW];
+  uint64_t mask[TL::UPW];
+  int r, s, tap, cb, kt;  // uniform: tap (r,s) and channel base of the next k-tile
+  int CH, WI, taps, S, invS, logC;
+  bool uniform_tap;
+  // tap part of the offset, in elements
+  __device__ int tap_off(int rr, int ss, const ConvGeom& g) const {
+    return DGRAD ? -((rr / g.stride) * g.Q + ss / g.stride) * g.K : (rr * g.W + ss) * g.C;
+  }
+  __device__ void init(const Args& a, int row0, int wave, int lane, int kt0) {
+    const ConvGeom& g = a.g;
+    rsrc = make_rsrc(a.a, a.a_bytes);
+    CH = DGRAD ? g.K : g.C;
+    S = g.S;
+    taps = g.R * g.S;
+    invS = (65536 + g.S - 1) / g.S;
+    uniform_tap = (CH % BK) == 0;
+    logC = log2_of(CH);
+#pragma unroll
+    for (int i = 0; i < TL::UPW; ++i) {
+      const int row = row0 + TL::row_of(wave, i, lane);
+      const bool rv = row < a.Mg;
+      kc[i] = TL::kc_of(wave, i, lane);
+      uint64_t m = 0;
+      if (!DGRAD) {
+        const int q = row % g.Q, t = row / g.Q, p = t % g.P, n = t / g.P;
+        const int h0 = p * g.stride - g.pad, w0 = q * g.stride - g.pad;
+        loff[i] = (((n * g.H + h0) * g.W + w0) * g.C + (uniform_tap ? kc[i] * 8 : 0)) * 2;
+        for (int rr = 0, t2 = 0; rr < g.R; ++rr)
+          for (int ss = 0; ss < g.S; ++ss, ++t2)
+            if (rv && h0 + rr >= 0 && h0 + rr < g.H && w0 + ss >= 0 && w0 + ss < g.W) m |= 1ull << t2;
+      } else {
+        const int w = row % g.W, t = row / g.W, h = t % g.H, n = t / g.H;
+        const int hp0 = h + g.pad, wp0 = w + g.pad;
+        loff[i] = (((n * g.P + hp0 / g.stride) * g.Q + wp0 / g.stride) * g.K + (uniform_tap ? kc[i] * 8 : 0)) * 2;
+        for (int rr = 0, t2 = 0; rr < g.R; ++rr)
+          for (int ss = 0; ss < g.S; ++ss, ++t2) {
+            const int hp = hp0 - rr, wp = wp0 - ss;
+            if (rv && hp >= 0 && wp >= 0 && hp % g.stride == 0 && wp % g.stride == 0 && hp / g.stride < g.P &&
+                wp / g.stride < g.Q)
+              m |= 1ull << t2;
+          }
+      }
+      mask[i] = m;
+    }
+    kt = kt0;
+    const int kk = kt0 * BK;
+    cb = kk % CH;
+    tap = kk / CH;
+    s = tap % g.S;
+    r = tap / g.S;
+  }
+  __device__ void issue(const Args& a, char* tile, int wave) {
+    const ConvGeom& g = a.g;
+    if (uniform_tap) {
+      const int uni = (tap_off(r, s, g) + cb) * 2;
+      const bool in = tap < taps;
+#pragma unroll
+      for (int i = 0; i < TL::UPW; ++i) {
+        const bool ok = in && ((mask[i] >> tap) & 1);
+        dma16(ok ? (uint32_t)(loff[i] + uni) : OOB, rsrc, tile + (wave * TL::UPW + i) * 1024);
+      }
+      cb += BK;
+      if (cb >= CH) {
+        cb = 0;
+        ++tap;
+        if (++s == g.S) { s = 0; ++r; }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < TL::UPW; ++i) {
+        const int kk = kt * BK + kc[i] * 8;
+        const int t = kk >> logC, c = kk & (CH - 1);
+        const int rr = (t * invS) >> 16, ss = t - rr * S;
+        const bool ok = t < taps && ((mask[i] >> t) & 1);
+        dma16(ok ? (uint32_t)(loff[i] + (tap_off(rr, ss, g) + c) * 2) : OOB, rsrc, tile + (wave * TL::UPW + i) * 1024);
+      }
+    }
+    ++kt;
+  }
+};
+
+// dgrad B: rows = input channels c, k = (r,s,ko); filters (R,S,C,K) are contiguous along ko.
+// k-tiles past R*S*K run off the end of the filter tensor and read as zeros.
+template <int ROWS> struct DgradB {
+  typedef KTile<ROWS> TL;
+  i32x4 rsrc;
+  uint32_t loff[TL::UPW];
+  int kc[TL::UPW], crow[TL::UPW];
+  int rs, kob, kt, logK;
+  bool uniform_tap;
+  __device__ void init(const Args& a, int row0, int wave, int lane, int kt0) {
+    const ConvGeom& g = a.g;
+    rsrc = make_rsrc(a.b, a.b_bytes);
+    uniform_tap = (g.K % BK) == 0;
+    logK = log2_of(g.K);
+#pragma unroll
+    for (int i = 0; i < TL::UPW; ++i) {
+      crow[i] = row0 + TL::row_of(wave, i, lane);
+      kc[i] = TL::kc_of(wave, i, lane);
+      loff[i] = crow[i] < a.Ng ? (uint32_t)((crow[i] * g.K + (uniform_tap ? kc[i] * 8 : 0)) * 2) : OOB;
+    }
+    kt = kt0;
+    const int kk = kt0 * BK;
+    kob = kk % g.K;
+    rs = kk / g.K;
+  }
+  __device__ void issue(const Args& a, char* tile, int wave) {
+    const ConvGeom& g = a.g;
+    if (uniform_tap) {
+      const uint32_t uni = (uint32_t)((rs * g.C * g.K + kob) * 2);
+#pragma unroll
+      for (int i = 0; i < TL::UPW; ++i) dma16(loff[i] + uni, rsrc, tile + (wave * TL::UPW + i) * 1024);
+      kob += BK;
+      if (kob >= g.K) { kob = 0; ++rs; }
+    } else {
+#pragma unroll
+      for (int i = 0; i < TL::UPW; ++i) {
+        const int kk = kt * BK + kc[i] * 8;
+        const int t = kk >> logK, ko = kk & (g.K - 1);
+        dma16(loff[i] + (uint32_t)((t * g.C * g.K + ko) * 2), rsrc, tile + (wave * TL::UPW + i) * 1024);
+      }
+    }
+    ++kt;
+  }
+};
+
+// ---- row-contiguous operands ---------------------------------------------------------------------
+// Stored as they lie in memory: LDS[(k*CPR + chunk)*16], k = 0..63, chunk = 8 adjacent rows.
+// Wave w fills units u = w*UPW + i; a unit is KPU k-rows; lane l owns k-row u*KPU + l/CPR, chunk l%CPR.
+template <int ROWS> struct RTile {
+  static constexpr int UPW = ROWS / 32;
+  static constexpr int CPR = ROWS / 8;   // chunks per k-row
+  static constexpr int KPU = 64 / CPR;   // k-rows per 1 KiB unit
+  __device__ static int k_of(int wave, int i, int lane) { return (wave * UPW + i) * KPU + lane / CPR; }
+  __device__ static int chunk_of(int lane) { return lane % CPR; }
+  // byte address a lane hands to ds_read_b64_tr_b16 to receive, for its own row nf + (lane & 31), the
+  // 4 k-values kb .. kb+3: lanes 16g..16g+15 together read k-rows kb..kb+3 x rows nf+16g .. nf+16g+15
+  __device__ static int tr_off(int kb, int nf, int lane) {
+    int j = lane & 15, g = (lane >> 4) & 1;
+    return ((kb + (j >> 2)) * ROWS + nf + 16 * g + 4 * (j & 3)) * 2;
+  }
+};
+
+// plain [k][ld] matrix: filters in the forward pass ([(r,s,c)][ko]), dy in wgrad ([(n,p,q)][ko]).
+// k-rows past the end of the tensor read as zeros.
+template <int ROWS> struct PlainR {
+  typedef RTile<ROWS> TL;
+  i32x4 rsrc;
+  uint32_t off[TL::UPW], step;
+  __device__ void init(const Args& a, int col0, int wave, int lane, int kt0) {
+    rsrc = make_rsrc(a.b, a.b_bytes);
+    const int col = col0 + TL::chunk_of(lane) * 8;
+    step = (uint32_t)(BK * a.g.K * 2);
+#pragma unroll
+    for (int i = 0; i < TL::UPW; ++i)
+      off[i] = col < a.Ng ? (uint32_t)(((kt0 * BK + TL::k_of(wave, i, lane)) * a.g.K + col) * 2) : OOB;
+  }
+  __device__ void issue(const Args&, char* tile, int wave) {
+#pragma unroll
+    for (int i = 0; i < TL::UPW; ++i) {
+      dma16(off[i], rsrc, tile + (wave * TL::UPW + i) * 1024);
+      off[i] += step;
+    }
+  }
+};
+
+// wgrad A: rows = (r,s,c) (contiguous along c), k = output pixel (n,p,q); gathers x
+template <int ROWS> struct WgradA {
+  typedef RTile<ROWS> TL;
+  i32x4 rsrc;
+  int coloff, dr, ds;  // fixed per lane: ((r-pad)*W + (s-pad))*C + c0, r - pad, s - pad
+  bool cv;
+  int m[TL::UPW];
+  uint32_t off[TL::UPW], step;
+  __device__ void init(const Args& a, int row0, int wave, int lane, int kt0) {
+    const ConvGeom& g = a.g;
+    rsrc = make_rsrc(a.a, a.a_bytes);
+    const int i0 = row0 + TL::chunk_of(lane) * 8;
+    cv = i0 < a.Mg;
+    const int c0 = i0 % g.C, t2 = i0 / g.C;
+    dr = t2 / g.S - g.pad;
+    ds = t2 % g.S - g.pad;
+    coloff = (dr * g.W + ds) * g.C + c0;
+    step = (uint32_t)(BK * g.C * 2);
+#pragma unroll
+    for (int i = 0; i < TL::UPW; ++i) {
+      m[i] = kt0 * BK + TL::k_of(wave, i, lane);
+      off[i] = cv ? (uint32_t)((m[i] * g.C + c0) * 2) : OOB;  // the 1x1 / stride 1 / no padding case
+    }
+  }
+  __device__ void issue(const Args& a, char* tile, int wave) {
+    const ConvGeom& g = a.g;
+#pragma unroll
+    for (int i = 0; i < TL::UPW; ++i) {
+      uint32_t v = off[i];
+      if (!a.simple) {
+        const int t = fast_div(m[i], a.magicQ, a.shiftQ), q = m[i] - t * g.Q;
+        const int n = fast_div(t, a.magicP, a.shiftP), p = t - n * g.P;
+        const int h = p * g.stride + dr, w = q * g.stride + ds;
+        const bool ok = cv && m[i] < a.Kg && h >= 0 && h < g.H && w >= 0 && w < g.W;
+        v = ok ? (uint32_t)((((n * g.H + p * g.stride) * g.W + q * g.stride) * g.C + coloff) * 2) : OOB;
+        m[i] += BK;
+      }
+      dma16(v, rsrc, tile + (wave * TL::UPW + i) * 1024);
+      off[i] += step;
+    }
+  }
+};
+
+template <int PASS, int ROWS, bool IS_A> struct Sel;
+template <int ROWS> struct Sel<PASS_FWD, ROWS, true> { typedef Gather<ROWS, false> type; static constexpr bool KC = true; };
+template <int ROWS> struct Sel<PASS_FWD, ROWS, false> { typedef PlainR<ROWS> type; static constexpr bool KC = false; };
+template <int ROWS> struct Sel<PASS_DGRAD, ROWS, true> { typedef Gather<ROWS, true> type; static constexpr bool KC = true; };
+template <int ROWS> struct Sel<PASS_DGRAD, ROWS, false> { typedef DgradB<ROWS> type; static constexpr bool KC = true; };
+template <int ROWS> struct Sel<PASS_WGRAD, ROWS, true> { typedef WgradA<ROWS> type; static constexpr bool KC = false; };
+template <int ROWS> struct Sel<PASS_WGRAD, ROWS, false> { typedef PlainR<ROWS> type; static constexpr bool KC = false; };
+
+// fragment of 32 rows x 16 k for the MFMA: 8 k-values per lane (k = 16*ks + 8*(lane>>5) + 0..7)
+template <bool KC, int ROWS> __device__ inline bf16x8 load_frag(const char* tile, int row0, int ks, int lane) {
+  if constexpr (KC) {
+    const int row = row0 + (lane & 31), kc = ks * 2 + (lane >> 5);
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + KTile<ROWS>::frag_off(row, kc)));
+  } else {
+    const int kb = ks * 16 + 8 * (lane >> 5);
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(tile + RTile<ROWS>::tr_off(kb, row0, lane)));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(tile + RTile<ROWS>::tr_off(kb + 4, row0, lane)));
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+template <int PASS, int STAGES, int WM, int WN, int FM, int FN>
+__global__ __launch_bounds__(NT, 2) void igemm_dma_kernel(const Args a) {
+  static_assert(WM * WN == 4, "four wavefronts");
+  constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
+  constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE_BYTES = A_BYTES + B_BYTES;
+  constexpr int LOADS = (BM + BN) / 32;  // direct loads per lane per stage
+  typedef Sel<PASS, BM, true> SA;
+  typedef Sel<PASS, BN, false> SB;
+  __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_BYTES];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int logical = (blockIdx.x % NUM_XCD) * a.tiles_per_xcd + blockIdx.x / NUM_XCD;
+  if (logical >= a.tiles_m * a.tiles_n) return;
+  const int m0 = (logical / a.tiles_n) * BM, n0 = (logical % a.tiles_n) * BN;
+  const int kt0 = blockIdx.y * a.nk_per_split;
+  const int kt1 = min(a.nk, kt0 + a.nk_per_split);
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  const int arow = (wave / WN) * FM * 32, brow = (wave % WN) * FN * 32;
+
+  typename SA::type la;
+  typename SB::type lb;
+  la.init(a, m0, wave, lane, kt0);
+  lb.init(a, n0, wave, lane, kt0);
+  // prologue: k-tiles kt0 .. kt0+STAGES-2 (tiles past the end fetch zeros: the counts stay uniform)
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s) {
+    la.issue(a, smem + s * STAGE_BYTES, wave);
+    lb.issue(a, smem + s * STAGE_BYTES + A_BYTES, wave);
+  }
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const int cur = (kt - kt0) % STAGES;
+    wait_vmcnt<(STAGES - 2) * LOADS>();  // this lane's direct loads of k-tile kt have landed
+    __syncthreads();                     // ... and everyone's; everyone is done reading tile kt-1
+    {
+      const int nxt = (kt - kt0 + STAGES - 1) % STAGES;  // the buffer tile kt-1 used
+      la.issue(a, smem + nxt * STAGE_BYTES, wave);
+      lb.issue(a, smem + nxt * STAGE_BYTES + A_BYTES, wave);
+    }
+    const char* As = smem + cur * STAGE_BYTES;
+    const char* Bs = As + A_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 af[FM], bf[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i) af[i] = load_frag<SA::KC, BM>(As, arow + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) bf[j] = load_frag<SB::KC, BN>(Bs, brow + j * 32, ks, lane);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  wait_vmcnt<0>();
+  __syncthreads();  // the ring is idle: reuse it for the output tile
+
+  // epilogue.  A 32x32 accumulator block: lane holds column (lane & 31) and, in register v,
+  // row 8*(v/4) + 4*(lane >> 5) + (v % 4).
+  if constexpr (PASS != PASS_WGRAD) {
+    // Each wavefront turns its own sub-tile around through a private LDS patch, 32 rows x (FN*32)
+    // columns of fp32 at a time, so that every lane then stores 8 adjacent bf16 outputs (16 bytes) and
+    // a store instruction covers whole 128-byte runs of output rows.  No block barrier is needed.
+    constexpr int WCOLS = FN * 32, CS = WCOLS + 4;  // row stride in floats: rows 4 banks apart
+    constexpr int PATCH = 32 * CS * 4;
+    static_assert(4 * PATCH <= STAGES * STAGE_BYTES, "staging patches must fit in the ring");
+    float* cs = reinterpret_cast<float*>(smem + wave * PATCH);
+    bf16_t* out = static_cast<bf16_t*>(a.out);
+    constexpr int CPRO = WCOLS / 8;  // 16-byte output chunks per patch row
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          cs[(8 * (v / 4) + 4 * (lane >> 5) + (v % 4)) * CS + j * 32 + (lane & 31)] = acc[i][j][v];
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int it = 0; it < 32 * CPRO / 64; ++it) {
+        const int chunk = lane + it * 64;
+        const int prow = chunk / CPRO, pcol = (chunk % CPRO) * 8;
+        const int row = m0 + arow + i * 32 + prow, col = n0 + brow + pcol;
+        if (row < a.Mg && col < a.Ng) {
+          const float4 lo = *reinterpret_cast<const float4*>(&cs[prow * CS + pcol]);
+          const float4 hi = *reinterpret_cast<const float4*>(&cs[prow * CS + pcol + 4]);
+          float v8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+          bf16_t* dst = out + (long long)row * a.Ng + col;
+          if constexpr (PASS == PASS_FWD) {
+            if (a.bias) {
+              const float4 b0 = *reinterpret_cast<const float4*>(a.bias + col);
+              const float4 b1 = *reinterpret_cast<const float4*>(a.bias + col + 4);
+              v8[0] += b0.x; v8[1] += b0.y; v8[2] += b0.z; v8[3] += b0.w;
+              v8[4] += b1.x; v8[5] += b1.y; v8[6] += b1.z; v8[7] += b1.w;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v8[e] = act_apply(v8[e], a.act);
+          }
+          if (PASS == PASS_DGRAD && a.accumulate) {
+            const uint4 old = *reinterpret_cast<const uint4*>(dst);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v8[e] += bf16_to_f32((bf16_t)half_of(old, e));
+          }
+          uint4 o;
+          o.x = (uint32_t)f32_to_bf16(v8[0]) | ((uint32_t)f32_to_bf16(v8[1]) << 16);
+          o.y = (uint32_t)f32_to_bf16(v8[2]) | ((uint32_t)f32_to_bf16(v8[3]) << 16);
+          o.z = (uint32_t)f32_to_bf16(v8[4]) | ((uint32_t)f32_to_bf16(v8[5]) << 16);
+          o.w = (uint32_t)f32_to_bf16(v8[6]) | ((uint32_t)f32_to_bf16(v8[7]) << 16);
+          *reinterpret_cast<uint4*>(dst) = o;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  } else {
+    float* dw = static_cast<float*>(a.out) + (long long)blockIdx.y * a.split_stride;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int col = n0 + brow + j * 32 + (lane & 31);
+        if (col >= a.Ng) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + arow + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+          if (row < a.Mg) dw[(long long)row * a.Ng + col] = acc[i][j][v];
+        }
+      }
+  }
+}
+
+}  // namespace
+
+bool igemm_dma_ok(int pass, const ConvGeom& g, const Args& a) {
+  auto chan_ok = [](int c) { return c % BK == 0 || c == 8 || c == 16 || c == 32; };
+  const long long lim = 1LL << 30;  // elements: keeps every byte offset below 2^31
+  if ((long long)g.N * g.H * g.W * g.C >= lim || (long long)g.N * g.P * g.Q * g.K >= lim ||
+      (long long)g.R * g.S * g.C * g.K >= lim || g.R * g.S > 64)
+    return false;
+  if (pass == PASS_FWD && !chan_ok(g.C)) return false;
+  if (pass == PASS_DGRAD && !chan_ok(g.K)) return false;
+  return g.C % 8 == 0 && g.K % 8 == 0 && aligned16(a.a) && aligned16(a.b) && aligned16(a.out);
+}
+
+template <int PASS, int FM>
+static void launch_tile(Args& a, int splits, hipStream_t st) {
+  constexpr int BM = 2 * FM * 32, BN = 128;
+  a.tiles_m = (a.Mg + BM - 1) / BM;
+  a.tiles_n = (a.Ng + BN - 1) / BN;
+  a.tiles_per_xcd = (a.tiles_m * a.tiles_n + NUM_XCD - 1) / NUM_XCD;
+  dim3 grid((unsigned)(a.tiles_per_xcd * NUM_XCD), (unsigned)splits);
+  hipLaunchKernelGGL((igemm_dma_kernel<PASS, 2, 2, 2, FM, 2>), grid, dim3(NT), 0, st, a);
+}
+
+// Tile choice: 128x128 when that already gives every SIMD of the chip (256 CUs x 4) two wavefronts
+// to interleave, else 64x128 (twice the workgroups; the small late-stage layers need them more than
+// they need the better LDS-bytes-per-MFMA ratio of the big tile).
+int igemm_dma_launch(int pass, Args& a, int splits, hipStream_t st) {
+  const long long big = (long long)((a.Mg + 127) / 128) * ((a.Ng + 127) / 128) * splits;
+  const bool small = big < 512;
+  if (pass == PASS_FWD) {
+    if (small) launch_tile<PASS_FWD, 1>(a, splits, st); else launch_tile<PASS_FWD, 2>(a, splits, st);
+  } else if (pass == PASS_DGRAD) {
+    if (small) launch_tile<PASS_DGRAD, 1>(a, splits, st); else launch_tile<PASS_DGRAD, 2>(a, splits, st);
+  } else {
+    if (small) launch_tile<PASS_WGRAD, 1>(a, splits, st); else launch_tile<PASS_WGRAD, 2>(a, splits, st);
+  }
+  return launch_status("igemm_dma");
+}
+
+}  // namespace s4tf
