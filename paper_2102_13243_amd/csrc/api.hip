@@ -161,6 +161,10 @@ struct NetPlan {
   std::vector<TensorPlan> t;
   std::vector<int64_t> poff, psize;  // 2 per op
   std::vector<size_t> stat_off;      // per op: save_mean/invstd (BN)
+  // a bf16 convolution on the batch itself whose channel count is not a multiple of 8 runs on
+  // zero-padded copies of the batch and of its filter (pad_c channels), see train step
+  std::vector<int> pad_c;
+  std::vector<size_t> xpad_off, wpad_off, dwpad_off;
   size_t param_count;
   size_t scratch_off, scratch_bytes, total_bytes;
 };
@@ -176,6 +180,10 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
   pl.poff.assign(2 * nops, 0);
   pl.psize.assign(2 * nops, 0);
   pl.stat_off.assign(nops, 0);
+  pl.pad_c.assign(nops, 0);
+  pl.xpad_off.assign(nops, 0);
+  pl.wpad_off.assign(nops, 0);
+  pl.dwpad_off.assign(nops, 0);
   pl.t[0] = TensorPlan{net->n, net->h, net->w, net->c, (size_t)net->n * net->h * net->w * net->c, 0, 0, 0, -1, 0};
   size_t pcount = 0, off = 0, scratch = 0;
   auto add_param = [&](int op, int slot, size_t n) {
@@ -199,6 +207,10 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
         out.h = g.P; out.w = g.Q; out.c = op.k;
         add_param(i, 0, (size_t)op.r * op.s * (in.c / op.groups) * op.k);
         if (op.has_bias) add_param(i, 1, (size_t)op.k);
+        if (net->dtype == S4TF_BF16 && in.root == 0 && op.groups == 1 && in.c % 8 != 0) {
+          pl.pad_c[i] = (int)align_up((size_t)in.c, 8);
+          g.C = pl.pad_c[i];
+        }
         size_t ws = op.groups == 1 ? igemm_wgrad_workspace(g, net->dtype) : dwconv_wgrad_workspace(g);
         if (ws > scratch) scratch = ws;
         break;
@@ -273,6 +285,14 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
     if (net->ops[i].kind == S4TF_OP_BN) {
       pl.stat_off[i] = off;
       off += align_up((size_t)2 * pl.t[net->ops[i].in].c * sizeof(float), 256);
+    }
+  for (int i = 0; i < nops; ++i)
+    if (pl.pad_c[i]) {
+      const s4tf_op& op = net->ops[i];
+      const TensorPlan& in = pl.t[op.in];
+      pl.xpad_off[i] = off; off += align_up((size_t)in.n * in.h * in.w * pl.pad_c[i] * es, 256);
+      pl.wpad_off[i] = off; off += align_up((size_t)op.r * op.s * pl.pad_c[i] * op.k * es, 256);
+      pl.dwpad_off[i] = off; off += align_up((size_t)op.r * op.s * pl.pad_c[i] * op.k * sizeof(float), 256);
     }
   pl.scratch_off = off;
   pl.scratch_bytes = align_up(scratch, 256);
@@ -482,6 +502,13 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
       case S4TF_OP_CONV: {
         s4tf_conv_desc d = conv_desc(i, 0);
         const float* bias = op.has_bias ? params->master + pl.poff[2 * i + 1] : nullptr;
+        if (pl.pad_c[i]) {  // zero-padded channels contribute nothing: same result, 16-byte loaders
+          CHECK(pad_channels(dt, act_ptr(op.in), ws + pl.xpad_off[i], (long long)in.n * in.h * in.w, in.c, pl.pad_c[i], 1, st));
+          CHECK(pad_channels(dt, conv_w(i), ws + pl.wpad_off[i], (long long)op.r * op.s, in.c, pl.pad_c[i], op.k, st));
+          d.c = pl.pad_c[i];
+          CHECK(conv_fwd_impl(d, ws + pl.xpad_off[i], ws + pl.wpad_off[i], bias, out_ptr(i + 1), st));
+          break;
+        }
         CHECK(conv_fwd_impl(d, act_ptr(op.in), conv_w(i), bias, out_ptr(i + 1), st));
         break;
       }
@@ -530,6 +557,14 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         s4tf_conv_desc d = conv_desc(i, written[src] ? 1 : 0);
         if (op.act != S4TF_ACT_NONE)  // in place: dy is not needed once dz exists
           CHECK(act_vjp(dt, op.act, out_ptr(i + 1), dy, dy, pl.t[i + 1].elems, st));
+        if (pl.pad_c[i]) {  // the batch has no cotangent; the filter gradient of the padded channels is dropped
+          d.c = pl.pad_c[i];
+          float* dwp = reinterpret_cast<float*>(ws + pl.dwpad_off[i]);
+          CHECK(conv_vjp_impl(d, ws + pl.xpad_off[i], ws + pl.wpad_off[i], dy, nullptr, dwp,
+                              op.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr, scratch, pl.scratch_bytes, st));
+          CHECK(unpad_channels_f32(dwp, params->grad + pl.poff[2 * i], (long long)op.r * op.s, in.c, pl.pad_c[i], op.k, st));
+          break;
+        }
         CHECK(conv_vjp_impl(d, act_ptr(src), conv_w(i), dy, want_dx ? grad_ptr(src) : nullptr,
                             params->grad + pl.poff[2 * i], op.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr,
                             scratch, pl.scratch_bytes, st));

@@ -135,6 +135,42 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ a, lo
   if (rl == 0 && c < cols) out[c] = (float)(red[0][cl] + red[1][cl] + red[2][cl] + red[3][cl]);
 }
 
+// ---- zero padding of one axis: dst[o][c][i] = c < C ? src[o][c][i] : 0 with Cp >= C channels -------
+// (a first layer with 1 or 3 input channels is run with 8, so that it can take the 16-byte loaders)
+template <typename T>
+__global__ void pad_axis_kernel(const T* __restrict__ src, T* __restrict__ dst, long long outer, int C, int Cp, int inner) {
+  const long long total = outer * Cp * inner;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int in = (int)(i % inner);
+    const long long t = i / inner;
+    const int c = (int)(t % Cp);
+    const long long o = t / Cp;
+    dst[i] = c < C ? src[(o * C + c) * inner + in] : (T)0;
+  }
+}
+// pixels of up to 8 bf16 channels -> 8 channels, one 16-byte store per pixel
+__global__ void pad_pixels8_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, long long pixels, int C) {
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < pixels; i += (long long)gridDim.x * blockDim.x) {
+    uint32_t v[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) v[c] = c < C ? (uint32_t)src[i * C + c] : 0u;
+    uint4 o;
+    o.x = v[0] | (v[1] << 16); o.y = v[2] | (v[3] << 16); o.z = v[4] | (v[5] << 16); o.w = v[6] | (v[7] << 16);
+    reinterpret_cast<uint4*>(dst)[i] = o;
+  }
+}
+// the reverse for gradients: dst[o][c][i] = src[o][c][i], c < C
+__global__ void unpad_axis_kernel(const float* __restrict__ src, float* __restrict__ dst, long long outer, int C, int Cp, int inner) {
+  const long long total = outer * C * inner;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int in = (int)(i % inner);
+    const long long t = i / inner;
+    const int c = (int)(t % C);
+    const long long o = t / C;
+    dst[i] = src[(o * Cp + c) * inner + in];
+  }
+}
+
 // ---- SGD with momentum ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ param, float* __restrict__ vel,
                                                   const float* __restrict__ grad, bf16_t* __restrict__ lowp,
@@ -218,6 +254,24 @@ int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStrea
   else
     hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, st, (const float*)a, (long long)rows, cols, out);
   return launch_status("colsum");
+}
+
+int pad_channels(int dtype, const void* src, void* dst, long long outer, int C, int Cp, int inner, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  if (dtype == S4TF_BF16 && inner == 1 && Cp == 8) {
+    hipLaunchKernelGGL(pad_pixels8_kernel, dim3(blocks_for(outer)), dim3(256), 0, st, (const bf16_t*)src, (bf16_t*)dst, outer, C);
+  } else if (dtype == S4TF_BF16) {
+    hipLaunchKernelGGL(pad_axis_kernel<bf16_t>, dim3(blocks_for(outer * Cp * inner)), dim3(256), 0, st, (const bf16_t*)src, (bf16_t*)dst, outer, C, Cp, inner);
+  } else {
+    hipLaunchKernelGGL(pad_axis_kernel<float>, dim3(blocks_for(outer * Cp * inner)), dim3(256), 0, st, (const float*)src, (float*)dst, outer, C, Cp, inner);
+  }
+  return launch_status("pad_channels");
+}
+
+int unpad_channels_f32(const float* src, float* dst, long long outer, int C, int Cp, int inner, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  hipLaunchKernelGGL(unpad_axis_kernel, dim3(blocks_for(outer * C * inner)), dim3(256), 0, st, src, dst, outer, C, Cp, inner);
+  return launch_status("unpad_channels");
 }
 
 int sgd(size_t count, float* param, float* vel, const float* grad, void* lowp, float lr, float mu,

@@ -100,6 +100,10 @@ int dwconv_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, fl
 int act_vjp(int dtype, int act, const void* y, const void* dy, void* dz, size_t count, hipStream_t st);
 int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStream_t st);
 
+// zero-pad / strip the channel axis of [outer][C][inner] tensors
+int pad_channels(int dtype, const void* src, void* dst, long long outer, int C, int Cp, int inner, hipStream_t st);
+int unpad_channels_f32(const float* src, float* dst, long long outer, int C, int Cp, int inner, hipStream_t st);
+
 // batch norm
 size_t bn_workspace(size_t M, int C);
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
