@@ -569,10 +569,53 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
     }
 }
 
-// out[i] = sum over splits of part[z][i], in a fixed order: 16 lanes stride over the splits of
-// 16 adjacent outputs, then lane 0 adds the 16 lane totals.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, float* __restrict__ out,
-                                                            long long n, int splits) {
+// out[i] = sum over splits of part[z][i], in a fixed order: ZL lanes stride over the splits of one
+// float4 of outputs (each with four running sums), then lane 0 adds the ZL lane totals.
+template <int ZL>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float4* __restrict__ part, float4* __restrict__ out,
+                                                            long long n4, int splits) {
+  constexpr int OL = 256 / ZL;
+  __shared__ float4 sh[ZL][OL];
+  const int ol = threadIdx.x % OL, zl = threadIdx.x / OL;
+  const long long i = (long long)blockIdx.x * OL + ol;
+  float4 s[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) s[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i < n4) {
+    int z = zl;
+    for (; z + 3 * ZL < splits; z += 4 * ZL) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float4 v = part[(long long)(z + u * ZL) * n4 + i];
+        s[u].x += v.x; s[u].y += v.y; s[u].z += v.z; s[u].w += v.w;
+      }
+    }
+    for (; z < splits; z += ZL) {
+      const float4 v = part[(long long)z * n4 + i];
+      s[0].x += v.x; s[0].y += v.y; s[0].z += v.z; s[0].w += v.w;
+    }
+  }
+  float4 t;
+  t.x = (s[0].x + s[1].x) + (s[2].x + s[3].x);
+  t.y = (s[0].y + s[1].y) + (s[2].y + s[3].y);
+  t.z = (s[0].z + s[1].z) + (s[2].z + s[3].z);
+  t.w = (s[0].w + s[1].w) + (s[2].w + s[3].w);
+  if (ZL > 1) {
+    sh[zl][ol] = t;
+    __syncthreads();
+    if (zl == 0) {
+#pragma unroll
+      for (int l = 1; l < ZL; ++l) {
+        const float4 v = sh[l][ol];
+        t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+      }
+    }
+  }
+  if (zl == 0 && i < n4) out[i] = t;
+}
+// the same for output counts that are not multiples of 4
+__global__ __launch_bounds__(256) void splitk_reduce_scalar_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                                   long long n, int splits) {
   __shared__ float sh[16][17];
   const int ol = threadIdx.x & 15, zl = threadIdx.x >> 4;
   const long long i = (long long)blockIdx.x * 16 + ol;
@@ -612,6 +655,8 @@ void fill_sizes(Args& a, int pass, int dtype) {
   a.b_bytes = clamp(pass == PASS_WGRAD ? ys : ws);
   magic_div(g.Q, a.magicQ, a.shiftQ);
   magic_div(g.P, a.magicP, a.shiftP);
+  magic_div(g.W, a.magicW, a.shiftW);
+  magic_div(g.H, a.magicH, a.shiftH);
 }
 
 void fill_tiles(Args& a, int BM, int BN, int BK) {
@@ -633,12 +678,24 @@ template <typename T, int PASS> int launch(Args& a, int splits, hipStream_t st) 
   return launch_status("igemm");
 }
 
+// Split of the wgrad reduction axis (output pixels) over blockIdx.y.  The fast bf16 kernel keeps two
+// workgroups per CU resident, so one full wave of 512 equally long workgroups is the target; each
+// extra split costs a tile of fp32 partials written and read again.
 void wgrad_split(const ConvGeom& g, int dtype, int& splits, int& nk_per_split) {
   const int BK = dtype == S4TF_BF16 ? Cfg<bf16_t>::BK : Cfg<float>::BK;
-  long long Mg = (long long)g.R * g.S * g.C, Kg = (long long)g.N * g.P * g.Q;
-  long long tiles = ((Mg + 127) / 128) * ((g.K + 127) / 128);
-  long long nk = (Kg + BK - 1) / BK;
-  long long want = (1024 + tiles - 1) / tiles;
+  const int Mg = g.R * g.S * g.C;
+  const long long Kg = (long long)g.N * g.P * g.Q;
+  const long long nk = (Kg + BK - 1) / BK;
+  long long want;
+  if (dtype == S4TF_BF16 && igemm_dma_geom_ok(PASS_WGRAD, g)) {
+    int BM, BN;
+    igemm_dma_tile(PASS_WGRAD, Mg, g.K, 1, BM, BN);
+    const long long tiles = (long long)((Mg + BM - 1) / BM) * ((g.K + BN - 1) / BN);
+    want = 512 / tiles;
+  } else {
+    const long long tiles = (long long)((Mg + 127) / 128) * ((g.K + 127) / 128);
+    want = (1024 + tiles - 1) / tiles;
+  }
   if (want > nk) want = nk;
   if (want < 1) want = 1;
   nk_per_split = (int)((nk + want - 1) / want);
@@ -709,8 +766,20 @@ int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, flo
   }
   if (rc != S4TF_OK || splits == 1) return rc;
   ProfScope ps(PC_WGRAD_REDUCE, st);
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, st,
-                     static_cast<const float*>(ws), dw, n, splits);
+  if (n % 4 == 0 && aligned16(ws) && aligned16(dw)) {
+    const long long n4 = n / 4;
+    const float4* part = static_cast<const float4*>(ws);
+    float4* out = reinterpret_cast<float4*>(dw);
+    if (splits >= 32)
+      hipLaunchKernelGGL(splitk_reduce_kernel<16>, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, st, part, out, n4, splits);
+    else if (splits >= 8)
+      hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)((n4 + 63) / 64)), dim3(256), 0, st, part, out, n4, splits);
+    else
+      hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part, out, n4, splits);
+  } else {
+    hipLaunchKernelGGL(splitk_reduce_scalar_kernel, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, st,
+                       static_cast<const float*>(ws), dw, n, splits);
+  }
   return launch_status("splitk_reduce");
 }
 

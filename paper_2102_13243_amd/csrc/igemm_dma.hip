@@ -94,9 +94,11 @@ template <int ROWS, bool DGRAD> struct Gather {
   int r, s, tap, cb, kt;  // uniform: tap (r,s) and channel base of the next k-tile
   int CH, WI, taps, S, invS, logC;
   bool uniform_tap;
+  // x / stride for x >= 0
+  __device__ static int sdiv(int x, int stride) { return stride == 1 ? x : stride == 2 ? (x >> 1) : x / stride; }
   // tap part of the offset, in elements
   __device__ int tap_off(int rr, int ss, const ConvGeom& g) const {
-    return DGRAD ? -((rr / g.stride) * g.Q + ss / g.stride) * g.K : (rr * g.W + ss) * g.C;
+    return DGRAD ? -(sdiv(rr, g.stride) * g.Q + sdiv(ss, g.stride)) * g.K : (rr * g.W + ss) * g.C;
   }
   __device__ void init(const Args& a, int row0, int wave, int lane, int kt0) {
     const ConvGeom& g = a.g;
@@ -112,24 +114,38 @@ template <int ROWS, bool DGRAD> struct Gather {
       const int row = row0 + TL::row_of(wave, i, lane);
       const bool rv = row < a.Mg;
       kc[i] = TL::kc_of(wave, i, lane);
+      const int kco = uniform_tap ? kc[i] * 8 : 0;
       uint64_t m = 0;
-      if (!DGRAD) {
-        const int q = row % g.Q, t = row / g.Q, p = t % g.P, n = t / g.P;
+      if (a.simple) {  // 1x1, stride 1, no padding: a plain row-major matrix
+        loff[i] = (row * CH + kco) * 2;
+        m = rv ? 1 : 0;
+      } else if (!DGRAD) {
+        const int t = fast_div(row, a.magicQ, a.shiftQ), q = row - t * g.Q;
+        const int n = fast_div(t, a.magicP, a.shiftP), p = t - n * g.P;
         const int h0 = p * g.stride - g.pad, w0 = q * g.stride - g.pad;
-        loff[i] = (((n * g.H + h0) * g.W + w0) * g.C + (uniform_tap ? kc[i] * 8 : 0)) * 2;
-        for (int rr = 0, t2 = 0; rr < g.R; ++rr)
-          for (int ss = 0; ss < g.S; ++ss, ++t2)
-            if (rv && h0 + rr >= 0 && h0 + rr < g.H && w0 + ss >= 0 && w0 + ss < g.W) m |= 1ull << t2;
+        loff[i] = (((n * g.H + h0) * g.W + w0) * g.C + kco) * 2;
+        // the taps inside the image form a rectangle: rows [rlo, rhi) x columns [slo, shi)
+        const int rlo = max(0, -h0), rhi = min(g.R, g.H - h0), slo = max(0, -w0), shi = min(g.S, g.W - w0);
+        if (rv && shi > slo) {
+          const uint64_t cols = ((1ull << shi) - 1) & ~((1ull << slo) - 1);
+          for (int rr = rlo; rr < rhi; ++rr) m |= cols << (rr * g.S);
+        }
       } else {
-        const int w = row % g.W, t = row / g.W, h = t % g.H, n = t / g.H;
+        const int t = fast_div(row, a.magicW, a.shiftW), w = row - t * g.W;
+        const int n = fast_div(t, a.magicH, a.shiftH), h = t - n * g.H;
         const int hp0 = h + g.pad, wp0 = w + g.pad;
-        loff[i] = (((n * g.P + hp0 / g.stride) * g.Q + wp0 / g.stride) * g.K + (uniform_tap ? kc[i] * 8 : 0)) * 2;
-        for (int rr = 0, t2 = 0; rr < g.R; ++rr)
-          for (int ss = 0; ss < g.S; ++ss, ++t2) {
-            const int hp = hp0 - rr, wp = wp0 - ss;
-            if (rv && hp >= 0 && wp >= 0 && hp % g.stride == 0 && wp % g.stride == 0 && hp / g.stride < g.P &&
-                wp / g.stride < g.Q)
-              m |= 1ull << t2;
+        loff[i] = (((n * g.P + sdiv(hp0, g.stride)) * g.Q + sdiv(wp0, g.stride)) * g.K + kco) * 2;
+        // tap (rr, ss) reads dy at ((hp0 - rr)/stride, (wp0 - ss)/stride) when both divide exactly and
+        // fall inside the output: the valid set is (valid rr) x (valid ss)
+        uint64_t cols = 0;
+        for (int ss = 0; ss < g.S; ++ss) {
+          const int wp = wp0 - ss, wq = sdiv(wp, g.stride);
+          if (wp >= 0 && wq * g.stride == wp && wq < g.Q) cols |= 1ull << ss;
+        }
+        if (rv)
+          for (int rr = 0; rr < g.R; ++rr) {
+            const int hp = hp0 - rr, hq = sdiv(hp, g.stride);
+            if (hp >= 0 && hq * g.stride == hp && hq < g.P) m |= cols << (rr * g.S);
           }
       }
       mask[i] = m;
@@ -461,40 +477,59 @@ __global__ __launch_bounds__(NT, 2) void igemm_dma_kernel(const Args a) {
 
 }  // namespace
 
-bool igemm_dma_ok(int pass, const ConvGeom& g, const Args& a) {
+bool igemm_dma_geom_ok(int pass, const ConvGeom& g) {
   auto chan_ok = [](int c) { return c % BK == 0 || c == 8 || c == 16 || c == 32; };
   const long long lim = 1LL << 30;  // elements: keeps every byte offset below 2^31
   if ((long long)g.N * g.H * g.W * g.C >= lim || (long long)g.N * g.P * g.Q * g.K >= lim ||
-      (long long)g.R * g.S * g.C * g.K >= lim || g.R * g.S > 64)
+      (long long)g.R * g.S * g.C * g.K >= lim || g.R * g.S > 64 || g.S > 32)
     return false;
   if (pass == PASS_FWD && !chan_ok(g.C)) return false;
   if (pass == PASS_DGRAD && !chan_ok(g.K)) return false;
-  return g.C % 8 == 0 && g.K % 8 == 0 && aligned16(a.a) && aligned16(a.b) && aligned16(a.out);
+  return g.C % 8 == 0 && g.K % 8 == 0;
 }
 
-template <int PASS, int FM>
+bool igemm_dma_ok(int pass, const ConvGeom& g, const Args& a) {
+  return igemm_dma_geom_ok(pass, g) && aligned16(a.a) && aligned16(a.b) && aligned16(a.out);
+}
+
+// Tile choice.  GEMMs at most 64 columns wide take 128x64 tiles (a 128-wide tile would spend half
+// its MFMAs on padding).  Otherwise 128x128 when that already gives every SIMD of the chip
+// (256 CUs x 4) two wavefronts to interleave, else 64x128: twice the workgroups, which the small
+// late-stage layers need more than they need the better LDS-bytes-per-MFMA ratio of the big tile.
+// wgrad picks by the matrix shape alone (its workgroup count is set by the split of the reduction).
+void igemm_dma_tile(int pass, int Mg, int Ng, int splits, int& BM, int& BN) {
+  BM = 128;
+  BN = Ng <= 64 ? 64 : 128;
+  if (BN == 64) return;
+  if (pass == PASS_WGRAD) {
+    if (Mg <= 64) BM = 64;
+  } else if ((long long)((Mg + 127) / 128) * ((Ng + 127) / 128) * splits < 512) {
+    BM = 64;
+  }
+}
+
+template <int PASS, int FM, int FN>
 static void launch_tile(Args& a, int splits, hipStream_t st) {
-  constexpr int BM = 2 * FM * 32, BN = 128;
+  constexpr int BM = 2 * FM * 32, BN = 2 * FN * 32;
   a.tiles_m = (a.Mg + BM - 1) / BM;
   a.tiles_n = (a.Ng + BN - 1) / BN;
   a.tiles_per_xcd = (a.tiles_m * a.tiles_n + NUM_XCD - 1) / NUM_XCD;
   dim3 grid((unsigned)(a.tiles_per_xcd * NUM_XCD), (unsigned)splits);
-  hipLaunchKernelGGL((igemm_dma_kernel<PASS, 2, 2, 2, FM, 2>), grid, dim3(NT), 0, st, a);
+  hipLaunchKernelGGL((igemm_dma_kernel<PASS, 2, 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
 }
 
-// Tile choice: 128x128 when that already gives every SIMD of the chip (256 CUs x 4) two wavefronts
-// to interleave, else 64x128 (twice the workgroups; the small late-stage layers need them more than
-// they need the better LDS-bytes-per-MFMA ratio of the big tile).
+template <int PASS> static void launch_pass(Args& a, int splits, hipStream_t st) {
+  int BM, BN;
+  igemm_dma_tile(PASS, a.Mg, a.Ng, splits, BM, BN);
+  if (BN == 64) launch_tile<PASS, 2, 1>(a, splits, st);
+  else if (BM == 64) launch_tile<PASS, 1, 2>(a, splits, st);
+  else launch_tile<PASS, 2, 2>(a, splits, st);
+}
+
 int igemm_dma_launch(int pass, Args& a, int splits, hipStream_t st) {
-  const long long big = (long long)((a.Mg + 127) / 128) * ((a.Ng + 127) / 128) * splits;
-  const bool small = big < 512;
-  if (pass == PASS_FWD) {
-    if (small) launch_tile<PASS_FWD, 1>(a, splits, st); else launch_tile<PASS_FWD, 2>(a, splits, st);
-  } else if (pass == PASS_DGRAD) {
-    if (small) launch_tile<PASS_DGRAD, 1>(a, splits, st); else launch_tile<PASS_DGRAD, 2>(a, splits, st);
-  } else {
-    if (small) launch_tile<PASS_WGRAD, 1>(a, splits, st); else launch_tile<PASS_WGRAD, 2>(a, splits, st);
-  }
+  if (pass == PASS_FWD) launch_pass<PASS_FWD>(a, splits, st);
+  else if (pass == PASS_DGRAD) launch_pass<PASS_DGRAD>(a, splits, st);
+  else launch_pass<PASS_WGRAD>(a, splits, st);
   return launch_status("igemm_dma");
 }
 

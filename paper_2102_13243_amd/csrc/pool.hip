@@ -49,68 +49,97 @@ __global__ void avgpool2_vjp_kernel(const T* __restrict__ dy, T* __restrict__ dx
 }
 
 // ---- 3x3 / 2 pad 1 max pool --------------------------------------------------------------------
-template <typename T>
+// one thread per V channels of one output pixel
+template <typename T, int V>
 __global__ void maxpool3s2_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int N, int H, int W, int C) {
-  const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
-  const long long total = (long long)N * P * Q * C;
+  const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1, CV = C / V;
+  const long long total = (long long)N * P * Q * CV;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-    int c = (int)(i % C);
-    long long t = i / C;
+    int c = (int)(i % CV) * V;
+    long long t = i / CV;
     int q = (int)(t % Q);
     t /= Q;
     int p = (int)(t % P), n = (int)(t / P);
-    float best = -INFINITY;
+    float best[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) best[v] = -INFINITY;
+#pragma unroll
     for (int r = 0; r < 3; ++r) {
       int h = 2 * p + r - 1;
       if (h < 0 || h >= H) continue;
+#pragma unroll
       for (int s = 0; s < 3; ++s) {
         int w = 2 * q + s - 1;
         if (w < 0 || w >= W) continue;
-        float v = to_f32<T>(x[(((long long)n * H + h) * W + w) * C + c]);
-        if (v > best) best = v;
+        Pack<T, V> xv = ldp<T, V>(x + (((long long)n * H + h) * W + w) * C + c);
+#pragma unroll
+        for (int v = 0; v < V; ++v) best[v] = fmaxf(best[v], xv.get(v));
       }
     }
-    y[i] = from_f32<T>(best);
+    Pack<T, V> o;
+#pragma unroll
+    for (int v = 0; v < V; ++v) o.set(v, best[v]);
+    stp<T, V>(y + i * V, o);
   }
 }
 // gather form of the pullback: input (h,w) receives dy of every window in which it is the first
-// maximum in row-major window order (so the result does not depend on thread scheduling)
-template <typename T>
+// maximum in row-major window order (so the result does not depend on thread scheduling).
+// One thread per V channels of one input pixel; each of its (up to four) windows is scanned in
+// window order with a strict '>' so that the first maximum keeps the title.
+template <typename T, int V>
 __global__ void maxpool3s2_vjp_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int N,
                                       int H, int W, int C, int accumulate) {
-  const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
-  const long long total = (long long)N * H * W * C;
+  const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1, CV = C / V;
+  const long long total = (long long)N * H * W * CV;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-    int c = (int)(i % C);
-    long long t = i / C;
+    int c = (int)(i % CV) * V;
+    long long t = i / CV;
     int w = (int)(t % W);
     t /= W;
     int h = (int)(t % H), n = (int)(t / H);
-    const float mine = to_f32<T>(x[i]);
-    float g = 0.f;
+    float g[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) g[v] = 0.f;
     // windows p with 2p-1 <= h <= 2p+1
     for (int p = h / 2; p <= (h + 1) / 2; ++p) {
       if (p >= P) continue;
       for (int q = w / 2; q <= (w + 1) / 2; ++q) {
         if (q >= Q) continue;
-        bool first = true;
-        for (int r = 0; r < 3 && first; ++r) {
+        float best[V];
+        bool mine[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) { best[v] = -INFINITY; mine[v] = false; }
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
           int hh = 2 * p + r - 1;
           if (hh < 0 || hh >= H) continue;
+#pragma unroll
           for (int s = 0; s < 3; ++s) {
             int ww = 2 * q + s - 1;
             if (ww < 0 || ww >= W) continue;
-            float v = to_f32<T>(x[(((long long)n * H + hh) * W + ww) * C + c]);
-            bool before = hh < h || (hh == h && ww < w);
-            // an earlier element that is >= mine, or a later one that is > mine, beats it
-            if ((before && v >= mine) || (!before && v > mine)) { first = false; break; }
+            Pack<T, V> xv = ldp<T, V>(x + (((long long)n * H + hh) * W + ww) * C + c);
+            const bool me = hh == h && ww == w;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+              float e = xv.get(v);
+              if (e > best[v]) { best[v] = e; mine[v] = me; }
+            }
           }
         }
-        if (first) g += to_f32<T>(dy[(((long long)n * P + p) * Q + q) * C + c]);
+        Pack<T, V> dv = ldp<T, V>(dy + (((long long)n * P + p) * Q + q) * C + c);
+#pragma unroll
+        for (int v = 0; v < V; ++v) if (mine[v]) g[v] += dv.get(v);
       }
     }
-    if (accumulate) g += to_f32<T>(dx[i]);
-    dx[i] = from_f32<T>(g);
+    Pack<T, V> o;
+    if (accumulate) {
+      Pack<T, V> old = ldp<T, V>(dx + i * V);
+#pragma unroll
+      for (int v = 0; v < V; ++v) g[v] += old.get(v);
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) o.set(v, g[v]);
+    stp<T, V>(dx + i * V, o);
   }
 }
 
@@ -208,14 +237,19 @@ int pool_fwd(const s4tf_pool_desc& d, const void* x, void* y, hipStream_t st) {
   const bool avg = d.kind == S4TF_POOL_AVG2;
   const int P = avg ? d.h / 2 : (d.h - 1) / 2 + 1, Q = avg ? d.w / 2 : (d.w - 1) / 2 + 1;
   dim3 grid(blocks_for((long long)d.n * P * Q * d.c)), block(256);
+  const int V = d.dtype == S4TF_BF16 ? 8 : 4;
+  const bool vec = d.c % V == 0 && aligned16(x) && aligned16(y);
+  dim3 vgrid(blocks_for((long long)d.n * P * Q * d.c / V));
   if (d.dtype == S4TF_BF16) {
     typedef bf16_t T;
     if (avg) hipLaunchKernelGGL(avgpool2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
-    else hipLaunchKernelGGL(maxpool3s2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+    else if (vec) hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 8>), vgrid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+    else hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 1>), grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
   } else {
     typedef float T;
     if (avg) hipLaunchKernelGGL(avgpool2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
-    else hipLaunchKernelGGL(maxpool3s2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+    else if (vec) hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 4>), vgrid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+    else hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 1>), grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
   }
   return launch_status("pool_fwd");
 }
@@ -224,14 +258,19 @@ int pool_vjp(const s4tf_pool_desc& d, const void* x, const void* dy, void* dx, h
   ProfScope ps(PC_POOL, st);
   const bool avg = d.kind == S4TF_POOL_AVG2;
   dim3 grid(blocks_for((long long)d.n * d.h * d.w * d.c)), block(256);
+  const int V = d.dtype == S4TF_BF16 ? 8 : 4;
+  const bool vec = d.c % V == 0 && aligned16(x) && aligned16(dy) && aligned16(dx);
+  dim3 vgrid(blocks_for((long long)d.n * d.h * d.w * d.c / V));
   if (d.dtype == S4TF_BF16) {
     typedef bf16_t T;
     if (avg) hipLaunchKernelGGL(avgpool2_vjp_kernel<T>, grid, block, 0, st, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
-    else hipLaunchKernelGGL(maxpool3s2_vjp_kernel<T>, grid, block, 0, st, (const T*)x, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+    else if (vec) hipLaunchKernelGGL((maxpool3s2_vjp_kernel<T, 8>), vgrid, block, 0, st, (const T*)x, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+    else hipLaunchKernelGGL((maxpool3s2_vjp_kernel<T, 1>), grid, block, 0, st, (const T*)x, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
   } else {
     typedef float T;
     if (avg) hipLaunchKernelGGL(avgpool2_vjp_kernel<T>, grid, block, 0, st, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
-    else hipLaunchKernelGGL(maxpool3s2_vjp_kernel<T>, grid, block, 0, st, (const T*)x, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+    else if (vec) hipLaunchKernelGGL((maxpool3s2_vjp_kernel<T, 4>), vgrid, block, 0, st, (const T*)x, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+    else hipLaunchKernelGGL((maxpool3s2_vjp_kernel<T, 1>), grid, block, 0, st, (const T*)x, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
   }
   return launch_status("pool_vjp");
 }
