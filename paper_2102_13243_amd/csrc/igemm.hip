@@ -728,6 +728,15 @@ int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, voi
   a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
   fill_sizes(a, PASS_DGRAD, dtype);
   ProfScope ps(PC_CONV_DGRAD, st);
+  if (dtype == S4TF_BF16 && g.R == 1 && g.S == 1 && g.pad == 0 && g.stride == 2 && igemm_dma_ok(PASS_DGRAD, g, a)) {
+    // only pixels (2p, 2q) of dx receive anything: a plain GEMM over the pixels of dy whose rows the
+    // epilogue scatters (and, unless it accumulates, surrounds with zeros)
+    a.Mg = g.N * g.P * g.Q;
+    a.simple = 1;
+    a.scatter2 = 1;
+    fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
+    return igemm_dma_launch(PASS_DGRAD, a, 1, st);
+  }
   if (dtype == S4TF_BF16) {
     fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
     return launch<bf16_t, PASS_DGRAD>(a, 1, st);

@@ -16,6 +16,7 @@ struct Args {
   const float* bias;
   int Mg, Ng, Kg;
   int act, accumulate, simple;
+  int scatter2;                     // dgrad of a 1x1 / stride 2 / no padding layer run over the pixels of dy
   int nk, nk_per_split;
   long long split_stride;
   int tiles_m, tiles_n, tiles_per_xcd;

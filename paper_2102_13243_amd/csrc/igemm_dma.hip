@@ -339,15 +339,26 @@ template <bool KC, int ROWS> __device__ inline bf16x8 load_frag(const char* tile
   }
 }
 
+// Staging patch of the bf16 epilogue: per wavefront 32 rows x (FN*32) columns of fp32, rows 4 banks apart
+template <int FN> struct Patch {
+  static constexpr int WCOLS = FN * 32, CS = WCOLS + 4, BYTES = 32 * CS * 4;
+};
+
+// STAGES >= 2: ring of LDS stages, the loads of k-tile kt+STAGES-1 fly while kt is multiplied; two
+// workgroups per CU.  STAGES == 1: load, wait, multiply; half the LDS, four workgroups per CU, whose
+// phases interleave: the better trade for GEMMs with only one or two k-tiles, where a ring has
+// nothing to overlap and the run time is load latency plus epilogue.
 template <int PASS, int STAGES, int WM, int WN, int FM, int FN>
-__global__ __launch_bounds__(NT, 2) void igemm_dma_kernel(const Args a) {
+__global__ __launch_bounds__(NT, STAGES == 1 ? 4 : 2) void igemm_dma_kernel(const Args a) {
   static_assert(WM * WN == 4, "four wavefronts");
   constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
   constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int LOADS = (BM + BN) / 32;  // direct loads per lane per stage
+  constexpr int RING = STAGES * STAGE_BYTES;
+  constexpr int SMEM = (PASS != PASS_WGRAD && 4 * Patch<FN>::BYTES > RING) ? 4 * Patch<FN>::BYTES : RING;
   typedef Sel<PASS, BM, true> SA;
   typedef Sel<PASS, BN, false> SB;
-  __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char smem[SMEM];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int logical = (blockIdx.x % NUM_XCD) * a.tiles_per_xcd + blockIdx.x / NUM_XCD;
@@ -369,22 +380,8 @@ __global__ __launch_bounds__(NT, 2) void igemm_dma_kernel(const Args a) {
   typename SB::type lb;
   la.init(a, m0, wave, lane, kt0);
   lb.init(a, n0, wave, lane, kt0);
-  // prologue: k-tiles kt0 .. kt0+STAGES-2 (tiles past the end fetch zeros: the counts stay uniform)
-#pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) {
-    la.issue(a, smem + s * STAGE_BYTES, wave);
-    lb.issue(a, smem + s * STAGE_BYTES + A_BYTES, wave);
-  }
-  for (int kt = kt0; kt < kt1; ++kt) {
-    const int cur = (kt - kt0) % STAGES;
-    wait_vmcnt<(STAGES - 2) * LOADS>();  // this lane's direct loads of k-tile kt have landed
-    __syncthreads();                     // ... and everyone's; everyone is done reading tile kt-1
-    {
-      const int nxt = (kt - kt0 + STAGES - 1) % STAGES;  // the buffer tile kt-1 used
-      la.issue(a, smem + nxt * STAGE_BYTES, wave);
-      lb.issue(a, smem + nxt * STAGE_BYTES + A_BYTES, wave);
-    }
-    const char* As = smem + cur * STAGE_BYTES;
+
+  auto multiply = [&](const char* As) {
     const char* Bs = As + A_BYTES;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
@@ -399,9 +396,38 @@ __global__ __launch_bounds__(NT, 2) void igemm_dma_kernel(const Args a) {
         for (int j = 0; j < FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
     }
+  };
+
+  if constexpr (STAGES == 1) {
+    for (int kt = kt0; kt < kt1; ++kt) {
+      if (kt > kt0) __syncthreads();  // everyone is done reading the previous k-tile
+      la.issue(a, smem, wave);
+      lb.issue(a, smem + A_BYTES, wave);
+      wait_vmcnt<0>();
+      __syncthreads();
+      multiply(smem);
+    }
+  } else {
+    // prologue: k-tiles kt0 .. kt0+STAGES-2 (tiles past the end fetch zeros: the counts stay uniform)
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) {
+      la.issue(a, smem + s * STAGE_BYTES, wave);
+      lb.issue(a, smem + s * STAGE_BYTES + A_BYTES, wave);
+    }
+    for (int kt = kt0; kt < kt1; ++kt) {
+      const int cur = (kt - kt0) % STAGES;
+      wait_vmcnt<(STAGES - 2) * LOADS>();  // this lane's direct loads of k-tile kt have landed
+      __syncthreads();                     // ... and everyone's; everyone is done reading tile kt-1
+      {
+        const int nxt = (kt - kt0 + STAGES - 1) % STAGES;  // the buffer tile kt-1 used
+        la.issue(a, smem + nxt * STAGE_BYTES, wave);
+        lb.issue(a, smem + nxt * STAGE_BYTES + A_BYTES, wave);
+      }
+      multiply(smem + cur * STAGE_BYTES);
+    }
   }
   wait_vmcnt<0>();
-  __syncthreads();  // the ring is idle: reuse it for the output tile
+  __syncthreads();  // the LDS tiles are idle: reuse them for the output tile
 
   // epilogue.  A 32x32 accumulator block: lane holds column (lane & 31) and, in register v,
   // row 8*(v/4) + 4*(lane >> 5) + (v % 4).
@@ -409,14 +435,35 @@ __global__ __launch_bounds__(NT, 2) void igemm_dma_kernel(const Args a) {
     // Each wavefront turns its own sub-tile around through a private LDS patch, 32 rows x (FN*32)
     // columns of fp32 at a time, so that every lane then stores 8 adjacent bf16 outputs (16 bytes) and
     // a store instruction covers whole 128-byte runs of output rows.  No block barrier is needed.
-    constexpr int WCOLS = FN * 32, CS = WCOLS + 4;  // row stride in floats: rows 4 banks apart
-    constexpr int PATCH = 32 * CS * 4;
-    static_assert(4 * PATCH <= STAGES * STAGE_BYTES, "staging patches must fit in the ring");
-    float* cs = reinterpret_cast<float*>(smem + wave * PATCH);
+    constexpr int WCOLS = Patch<FN>::WCOLS, CS = Patch<FN>::CS;
+    float* cs = reinterpret_cast<float*>(smem + wave * Patch<FN>::BYTES);
     bf16_t* out = static_cast<bf16_t*>(a.out);
     constexpr int CPRO = WCOLS / 8;  // 16-byte output chunks per patch row
+    constexpr int ITERS = 32 * CPRO / 64;
+    const bool scatter = PASS == PASS_DGRAD && a.scatter2;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
+      // where this lane's chunks go (-1: outside the matrix); a 1x1 / stride-2 dgrad runs over the
+      // pixels of dy and scatters row (n,p,q) to pixel (n,2p,2q) of dx
+      long long dsto[ITERS];
+      uint4 old[ITERS];
+#pragma unroll
+      for (int it = 0; it < ITERS; ++it) {
+        const int chunk = lane + it * 64;
+        const int prow = chunk / CPRO, pcol = (chunk % CPRO) * 8;
+        const int row = m0 + arow + i * 32 + prow, col = n0 + brow + pcol;
+        dsto[it] = -1;
+        if (row < a.Mg && col < a.Ng) {
+          long long orow = row;
+          if (scatter) {
+            const int t = fast_div(row, a.magicQ, a.shiftQ), q = row - t * a.g.Q;
+            const int n = fast_div(t, a.magicP, a.shiftP), p = t - n * a.g.P;
+            orow = ((long long)n * a.g.H + 2 * p) * a.g.W + 2 * q;
+          }
+          dsto[it] = orow * a.Ng + col;
+          if (PASS == PASS_DGRAD && a.accumulate) old[it] = *reinterpret_cast<const uint4*>(out + dsto[it]);
+        }
+      }
 #pragma unroll
       for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -424,15 +471,15 @@ __global__ __launch_bounds__(NT, 2) void igemm_dma_kernel(const Args a) {
           cs[(8 * (v / 4) + 4 * (lane >> 5) + (v % 4)) * CS + j * 32 + (lane & 31)] = acc[i][j][v];
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int it = 0; it < 32 * CPRO / 64; ++it) {
+      for (int it = 0; it < ITERS; ++it) {
         const int chunk = lane + it * 64;
         const int prow = chunk / CPRO, pcol = (chunk % CPRO) * 8;
-        const int row = m0 + arow + i * 32 + prow, col = n0 + brow + pcol;
-        if (row < a.Mg && col < a.Ng) {
+        const int col = n0 + brow + pcol;
+        if (dsto[it] >= 0) {
           const float4 lo = *reinterpret_cast<const float4*>(&cs[prow * CS + pcol]);
           const float4 hi = *reinterpret_cast<const float4*>(&cs[prow * CS + pcol + 4]);
           float v8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-          bf16_t* dst = out + (long long)row * a.Ng + col;
+          bf16_t* dst = out + dsto[it];
           if constexpr (PASS == PASS_FWD) {
             if (a.bias) {
               const float4 b0 = *reinterpret_cast<const float4*>(a.bias + col);
@@ -444,9 +491,8 @@ __global__ __launch_bounds__(NT, 2) void igemm_dma_kernel(const Args a) {
             for (int e = 0; e < 8; ++e) v8[e] = act_apply(v8[e], a.act);
           }
           if (PASS == PASS_DGRAD && a.accumulate) {
-            const uint4 old = *reinterpret_cast<const uint4*>(dst);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v8[e] += bf16_to_f32((bf16_t)half_of(old, e));
+            for (int e = 0; e < 8; ++e) v8[e] += bf16_to_f32((bf16_t)half_of(old[it], e));
           }
           uint4 o;
           o.x = (uint32_t)f32_to_bf16(v8[0]) | ((uint32_t)f32_to_bf16(v8[1]) << 16);
@@ -454,6 +500,17 @@ __global__ __launch_bounds__(NT, 2) void igemm_dma_kernel(const Args a) {
           o.z = (uint32_t)f32_to_bf16(v8[4]) | ((uint32_t)f32_to_bf16(v8[5]) << 16);
           o.w = (uint32_t)f32_to_bf16(v8[6]) | ((uint32_t)f32_to_bf16(v8[7]) << 16);
           *reinterpret_cast<uint4*>(dst) = o;
+          if (scatter && !a.accumulate) {
+            // the three pixels of the 2x2 cell that no output pixel reads get a zero cotangent
+            const int row = m0 + arow + i * 32 + prow;
+            const int t = fast_div(row, a.magicQ, a.shiftQ), q = row - t * a.g.Q;
+            const int p = t - fast_div(t, a.magicP, a.shiftP) * a.g.P;
+            const uint4 z = make_uint4(0, 0, 0, 0);
+            const bool wr = 2 * q + 1 < a.g.W, hd = 2 * p + 1 < a.g.H;
+            if (wr) *reinterpret_cast<uint4*>(dst + a.Ng) = z;
+            if (hd) *reinterpret_cast<uint4*>(dst + (long long)a.g.W * a.Ng) = z;
+            if (wr && hd) *reinterpret_cast<uint4*>(dst + (long long)(a.g.W + 1) * a.Ng) = z;
+          }
         }
       }
       __builtin_amdgcn_wave_barrier();
@@ -508,6 +565,8 @@ void igemm_dma_tile(int pass, int Mg, int Ng, int splits, int& BM, int& BN) {
   }
 }
 
+constexpr int SHORT_NK = 2;
+
 template <int PASS, int FM, int FN>
 static void launch_tile(Args& a, int splits, hipStream_t st) {
   constexpr int BM = 2 * FM * 32, BN = 2 * FN * 32;
@@ -515,7 +574,11 @@ static void launch_tile(Args& a, int splits, hipStream_t st) {
   a.tiles_n = (a.Ng + BN - 1) / BN;
   a.tiles_per_xcd = (a.tiles_m * a.tiles_n + NUM_XCD - 1) / NUM_XCD;
   dim3 grid((unsigned)(a.tiles_per_xcd * NUM_XCD), (unsigned)splits);
-  hipLaunchKernelGGL((igemm_dma_kernel<PASS, 2, 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
+  // GEMMs with at most SHORT_NK k-tiles: no ring, twice the workgroups per CU
+  if (PASS != PASS_WGRAD && a.nk <= SHORT_NK)
+    hipLaunchKernelGGL((igemm_dma_kernel<PASS, (PASS == PASS_WGRAD ? 2 : 1), 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
+  else
+    hipLaunchKernelGGL((igemm_dma_kernel<PASS, 2, 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
 }
 
 template <int PASS> static void launch_pass(Args& a, int splits, hipStream_t st) {

@@ -77,6 +77,11 @@ CONV_SHAPES = [
     (1, 35, 35, 8, 8, 7, 2, 3),       # 7x7 stride 2 (stem-like), N = 1
     (2, 8, 8, 128, 256, 3, 1, 1),     # deep K loop (1152), two N tiles
     (2, 6, 6, 16, 16, 3, 1, 2),       # pad wider than "same"
+    (2, 15, 15, 64, 128, 1, 2, 0),    # strided 1x1, odd extent, fast path: dgrad scatters rows and zero-fills
+    (2, 16, 16, 128, 64, 1, 2, 0),    # strided 1x1, even extent, 64-wide output
+    (3, 20, 20, 64, 64, 3, 1, 1),     # 64-wide GEMMs in all three passes, several ragged row tiles
+    (2, 30, 30, 64, 256, 1, 1, 0),    # one k-tile forward (no ring), two in dgrad
+    (2, 9, 9, 256, 64, 1, 1, 0),      # four k-tiles forward, one in dgrad
 ]
 
 
@@ -104,6 +109,7 @@ def test_conv2d_fwd_and_vjp(shape, bf16):
     dz_ref, _ = orc.bias_act_vjp(y_ref, dy, "relu", need_db=False)
     dx_ref, dw_ref, db_ref = orc.conv2d_vjp(x, wt, dz_ref, stride, pad, need_dx=True, need_db=True)
     dx = empty((n, h, w, c), bf16)
+    dx.fill_(float("nan"))   # every element must be written, also those no output pixel reads
     dw, db = empty((r, r, c, k)), empty((k,))
     wsp = ws(B.s4tf_conv2d_vjp_workspace_bytes(d))
     B.s4tf_conv2d_vjp(d, xd, wd, to_dev(y_ref, bf16), to_dev(dy, bf16), dx, dw, db, wsp)
