@@ -205,7 +205,10 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
 
 // dbeta and dgamma are sums of cotangents whose terms largely cancel (the cotangent reaching a
 // BatchNorm from a convolution that is itself followed by BatchNorm sums to almost zero), so the
-// per-thread and per-block partial sums are kept in double; the kernel stays bandwidth bound.
+// per-thread and per-block partial sums are kept in double.  The terms themselves, and the sum of
+// one group of UNROLL pixels, are fp32 (their rounding errors are independent and average out; what
+// must not happen is a long running sum in fp32), which keeps the double work to two additions per
+// channel and group.
 template <typename T, int V>
 __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict__ x, const T* __restrict__ y,
                                                             const T* __restrict__ dy, const float* __restrict__ mean,
@@ -218,10 +221,11 @@ __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict_
   const bool live = cv < CV;
   const int c = live ? cv * V : 0;
   double acc[2 * V];
-  float mu[V], is[V];
+  float grp[2 * V], mu[V], is[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) {
     acc[e] = acc[V + e] = 0.0;
+    grp[e] = grp[V + e] = 0.f;
     mu[e] = mean[c + e];
     is[e] = invstd[c + e];
   }
@@ -237,12 +241,19 @@ __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict_
                 [&](long long, int u) {
 #pragma unroll
                   for (int e = 0; e < V; ++e) {
+                    if (u == 0) {  // a new group of (at most UNROLL) pixels: bank the previous group's sums
+                      acc[e] += (double)grp[e];
+                      acc[V + e] += (double)grp[V + e];
+                      grp[e] = grp[V + e] = 0.f;
+                    }
                     float dz = dv[u].get(e);
                     if (act != S4TF_ACT_NONE) dz *= act_mask(yv[u].get(e), act);
-                    acc[e] += (double)dz;
-                    acc[V + e] += (double)dz * (((double)xv[u].get(e) - (double)mu[e]) * (double)is[e]);
+                    grp[e] += dz;
+                    grp[V + e] += dz * ((xv[u].get(e) - mu[e]) * is[e]);
                   }
                 });
+#pragma unroll
+    for (int e = 0; e < 2 * V; ++e) acc[e] += (double)grp[e];
   }
   block_lane_sum<double, 2 * V>(acc, redd, cvb, cvl);
   if (pl == 0 && live) {

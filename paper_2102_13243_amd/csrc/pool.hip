@@ -84,62 +84,91 @@ __global__ void maxpool3s2_fwd_kernel(const T* __restrict__ x, T* __restrict__ y
 }
 // gather form of the pullback: input (h,w) receives dy of every window in which it is the first
 // maximum in row-major window order (so the result does not depend on thread scheduling).
-// One thread per V channels of one input pixel; each of its (up to four) windows is scanned in
-// window order with a strict '>' so that the first maximum keeps the title.
+// One thread per V channels of one 2x2 cell of input pixels (2a..2a+1, 2b..2b+1): the cell lies in
+// the four windows (a..a+1, b..b+1) and in no other; each window is scanned once in window order with
+// a strict '>' (the first maximum keeps the title) and hands its dy to the cell pixel that won, if any.
 template <typename T, int V>
 __global__ void maxpool3s2_vjp_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int N,
                                       int H, int W, int C, int accumulate) {
   const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1, CV = C / V;
-  const long long total = (long long)N * H * W * CV;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-    int c = (int)(i % CV) * V;
-    long long t = i / CV;
-    int w = (int)(t % W);
-    t /= W;
-    int h = (int)(t % H), n = (int)(t / H);
-    float g[V];
+  const int HA = (H + 1) / 2, WB = (W + 1) / 2;
+  const long long total = (long long)N * HA * WB * CV;
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long long)gridDim.x * blockDim.x) {
+    int c = (int)(idx % CV) * V;
+    long long t = idx / CV;
+    int b = (int)(t % WB);
+    t /= WB;
+    int a = (int)(t % HA), n = (int)(t / HA);
+    float g[2][2][V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) g[v] = 0.f;
-    // windows p with 2p-1 <= h <= 2p+1
-    for (int p = h / 2; p <= (h + 1) / 2; ++p) {
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int v = 0; v < V; ++v) g[u >> 1][u & 1][v] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int p = a + i;
       if (p >= P) continue;
-      for (int q = w / 2; q <= (w + 1) / 2; ++q) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int q = b + j;
         if (q >= Q) continue;
         float best[V];
-        bool mine[V];
+        int bi[V];
 #pragma unroll
-        for (int v = 0; v < V; ++v) { best[v] = -INFINITY; mine[v] = false; }
+        for (int v = 0; v < V; ++v) { best[v] = -INFINITY; bi[v] = -1; }
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
-          int hh = 2 * p + r - 1;
+          const int hh = 2 * p + r - 1;
           if (hh < 0 || hh >= H) continue;
 #pragma unroll
           for (int s = 0; s < 3; ++s) {
-            int ww = 2 * q + s - 1;
+            const int ww = 2 * q + s - 1;
             if (ww < 0 || ww >= W) continue;
-            Pack<T, V> xv = ldp<T, V>(x + (((long long)n * H + hh) * W + ww) * C + c);
-            const bool me = hh == h && ww == w;
+            const Pack<T, V> xv = ldp<T, V>(x + (((long long)n * H + hh) * W + ww) * C + c);
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-              float e = xv.get(v);
-              if (e > best[v]) { best[v] = e; mine[v] = me; }
+              const float e = xv.get(v);
+              if (e > best[v]) { best[v] = e; bi[v] = r * 3 + s; }
             }
           }
         }
-        Pack<T, V> dv = ldp<T, V>(dy + (((long long)n * P + p) * Q + q) * C + c);
+        const Pack<T, V> dv = ldp<T, V>(dy + (((long long)n * P + p) * Q + q) * C + c);
+        // cell pixel (dh, dw) sits at window position (dh + 1 - 2i, dw + 1 - 2j)
 #pragma unroll
-        for (int v = 0; v < V; ++v) if (mine[v]) g[v] += dv.get(v);
+        for (int dh = 0; dh < 2; ++dh) {
+          const int r = dh + 1 - 2 * i;
+          if (r < 0) continue;
+#pragma unroll
+          for (int dw = 0; dw < 2; ++dw) {
+            const int s2 = dw + 1 - 2 * j;
+            if (s2 < 0) continue;
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+              if (bi[v] == r * 3 + s2) g[dh][dw][v] += dv.get(v);
+          }
+        }
       }
     }
-    Pack<T, V> o;
-    if (accumulate) {
-      Pack<T, V> old = ldp<T, V>(dx + i * V);
 #pragma unroll
-      for (int v = 0; v < V; ++v) g[v] += old.get(v);
+    for (int dh = 0; dh < 2; ++dh) {
+      const int h = 2 * a + dh;
+      if (h >= H) continue;
+#pragma unroll
+      for (int dw = 0; dw < 2; ++dw) {
+        const int w = 2 * b + dw;
+        if (w >= W) continue;
+        T* dst = dx + (((long long)n * H + h) * W + w) * C + c;
+        Pack<T, V> o;
+        if (accumulate) {
+          const Pack<T, V> old = ldp<T, V>(dst);
+#pragma unroll
+          for (int v = 0; v < V; ++v) g[dh][dw][v] += old.get(v);
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) o.set(v, g[dh][dw][v]);
+        stp<T, V>(dst, o);
+      }
     }
-#pragma unroll
-    for (int v = 0; v < V; ++v) o.set(v, g[v]);
-    stp<T, V>(dx + i * V, o);
   }
 }
 
@@ -261,6 +290,11 @@ int pool_vjp(const s4tf_pool_desc& d, const void* x, const void* dy, void* dx, h
   const int V = d.dtype == S4TF_BF16 ? 8 : 4;
   const bool vec = d.c % V == 0 && aligned16(x) && aligned16(dy) && aligned16(dx);
   dim3 vgrid(blocks_for((long long)d.n * d.h * d.w * d.c / V));
+  const long long cells = (long long)d.n * ((d.h + 1) / 2) * ((d.w + 1) / 2);  // max pool: a thread per 2x2 cell
+  if (!avg) {
+    grid = dim3(blocks_for(cells * d.c));
+    vgrid = dim3(blocks_for(cells * d.c / V));
+  }
   if (d.dtype == S4TF_BF16) {
     typedef bf16_t T;
     if (avg) hipLaunchKernelGGL(avgpool2_vjp_kernel<T>, grid, block, 0, st, (const T*)dy, (T*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
