@@ -349,7 +349,7 @@ int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* g
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
   const Plan pr = make_plan((size_t)M, C, d.dtype, 1024, 16);  // reduction: fewer, longer blocks
-  const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, 8);
+  const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, UNROLL);
   float* part = static_cast<float*>(ws);
   int rc;
   {
@@ -373,7 +373,7 @@ int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gam
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
   const Plan pr = make_plan((size_t)M, C, d.dtype, 1024, 16);
-  const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, 8);
+  const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, UNROLL);
   double* part = static_cast<double*>(ws);
   int rc;
   {

@@ -427,10 +427,10 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // consecutive workgroup ids land on different XCDs; give each XCD a contiguous run of
   // tiles so that tiles sharing an A row-block share that XCD's L2
-  const int logical = (blockIdx.x % NUM_XCD) * a.tiles_per_xcd + blockIdx.x / NUM_XCD;
-  if (blockIdx.x / NUM_XCD >= a.tiles_per_xcd || logical >= a.tiles_m * a.tiles_n) return;
+  int logical, split;
+  if (!block_to_tile(a, logical, split)) return;
   const int m0 = (logical / a.tiles_n) * BM, n0 = (logical % a.tiles_n) * BN;
-  const int kt0 = blockIdx.y * a.nk_per_split;
+  const int kt0 = split * a.nk_per_split;
   const int kt1 = min(a.nk, kt0 + a.nk_per_split);
 
   f32x16 acc[FM][FN];
@@ -562,7 +562,7 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
           if (a.accumulate) val += to_f32<T>(dx[o]);
           dx[o] = from_f32<T>(val);
         } else {
-          float* dw = static_cast<float*>(a.out) + (long long)blockIdx.y * a.split_stride;
+          float* dw = static_cast<float*>(a.out) + (long long)split * a.split_stride;
           dw[o] = val;
         }
       }
@@ -636,13 +636,17 @@ template <typename T> bool vec_ok(const ConvGeom& g) {
   return g.C % Cfg<T>::VEC == 0 && g.K % Cfg<T>::VEC == 0;
 }
 
-// x / d for 0 <= x < 2^31 as (mulhi(x, magic) >> shift); shift < 0 means d == 1
+// x / d for 0 <= x < 2^31 and d >= 1 as (mulhi(x, magic) + x) >> shift, with shift = ceil(log2 d) and
+// magic = ceil(2^(32+shift) / d) - 2^32: the round-up error of the 33-bit multiplier is below d <= 2^shift,
+// which makes the quotient exact for every 32-bit x; d == 1 gives magic 0, shift 0, and no special case.
 void magic_div(int d, uint32_t& magic, int& shift) {
-  if (d <= 1) { magic = 0; shift = -1; return; }
+  if (d < 1) d = 1;
   int s = 0;
   while ((1LL << s) < d) ++s;
-  magic = (uint32_t)(((1ULL << (31 + s)) + (unsigned long long)d - 1) / (unsigned long long)d);
-  shift = s - 1;
+  const unsigned __int128 one = 1;
+  const unsigned __int128 m = ((one << (32 + s)) + (unsigned)d - 1) / (unsigned)d;
+  magic = (uint32_t)(m - (one << 32));
+  shift = s;
 }
 
 void fill_sizes(Args& a, int pass, int dtype) {
@@ -665,12 +669,12 @@ void fill_tiles(Args& a, int BM, int BN, int BK) {
   a.nk = (a.Kg + BK - 1) / BK;
   a.nk_per_split = a.nk;
   a.split_stride = 0;
-  a.tiles_per_xcd = (a.tiles_m * a.tiles_n + NUM_XCD - 1) / NUM_XCD;
 }
 
 template <typename T, int PASS> int launch(Args& a, int splits, hipStream_t st) {
   if (sizeof(T) == 2 && igemm_dma_ok(PASS, a.g, a)) return igemm_dma_launch(PASS, a, splits, st);
-  dim3 grid((unsigned)(a.tiles_per_xcd * NUM_XCD), (unsigned)splits);
+  a.splits = splits;
+  dim3 grid(grid_blocks(a));
   if (vec_ok<T>(a.g))
     hipLaunchKernelGGL((igemm_kernel<T, PASS, true, 2, 2, 2, 2>), grid, dim3(NT), 0, st, a);
   else
@@ -678,7 +682,7 @@ template <typename T, int PASS> int launch(Args& a, int splits, hipStream_t st) 
   return launch_status("igemm");
 }
 
-// Split of the wgrad reduction axis (output pixels) over blockIdx.y.  The fast bf16 kernel keeps two
+// Split of the wgrad reduction axis (output pixels) over workgroups.  The fast bf16 kernel keeps two
 // workgroups per CU resident, so one full wave of 512 equally long workgroups is the target; each
 // extra split costs a tile of fp32 partials written and read again.
 void wgrad_split(const ConvGeom& g, int dtype, int& splits, int& nk_per_split) {

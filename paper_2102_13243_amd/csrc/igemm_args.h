@@ -17,9 +17,9 @@ struct Args {
   int Mg, Ng, Kg;
   int act, accumulate, simple;
   int scatter2;                     // dgrad of a 1x1 / stride 2 / no padding layer run over the pixels of dy
-  int nk, nk_per_split;
+  int nk, nk_per_split, splits;
   long long split_stride;
-  int tiles_m, tiles_n, tiles_per_xcd;
+  int tiles_m, tiles_n;
   uint32_t a_bytes, b_bytes;        // sizes of the tensors behind a and b
   uint32_t magicQ, magicP;          // x / Q and x / P by multiply-high (output pixel index -> n,p,q)
   int shiftQ, shiftP;
@@ -27,6 +27,32 @@ struct Args {
   int shiftW, shiftH;
 };
 
+
+// Workgroup -> (output tile, split of the reduction axis).  Workgroup ids are dealt round-robin to the
+// XCDs, each with an L2 of its own.  The (split, tile) pairs, split-major, are cut into one contiguous
+// run per XCD: neighbours in a run share an operand row-block or, across tiles of one split, the same
+// slice of both operands.  With at least as many splits as XCDs, whole splits are dealt round-robin
+// instead (all tiles of a split on one XCD).  Either way every XCD gets work even when there are fewer
+// tiles than XCDs.  False: this workgroup has nothing to do.
+__device__ inline bool block_to_tile(const Args& a, int& logical, int& split) {
+  const int x = blockIdx.x % NUM_XCD, j = blockIdx.x / NUM_XCD;
+  const int tiles = a.tiles_m * a.tiles_n;
+  if (a.splits >= NUM_XCD) {
+    split = (j / tiles) * NUM_XCD + x;
+    logical = j % tiles;
+    return split < a.splits;
+  }
+  const int units = tiles * a.splits, per_xcd = (units + NUM_XCD - 1) / NUM_XCD;
+  const int u = x * per_xcd + j;
+  split = u / tiles;
+  logical = u - split * tiles;
+  return j < per_xcd && u < units;
+}
+inline unsigned grid_blocks(const Args& a) {
+  const int tiles = a.tiles_m * a.tiles_n;
+  if (a.splits >= NUM_XCD) return (unsigned)(NUM_XCD * ((a.splits + NUM_XCD - 1) / NUM_XCD) * tiles);
+  return (unsigned)(NUM_XCD * ((tiles * a.splits + NUM_XCD - 1) / NUM_XCD));
+}
 
 // bf16 fast path: operands go from global memory straight into LDS (igemm_dma.hip)
 bool igemm_dma_geom_ok(int pass, const ConvGeom& g);                     // shape only

@@ -63,9 +63,9 @@ __device__ inline uint32_t half_of(const uint4& v, int e) {
   uint32_t d = (e >> 1) == 0 ? v.x : (e >> 1) == 1 ? v.y : (e >> 1) == 2 ? v.z : v.w;
   return (e & 1) ? (d >> 16) : (d & 0xffffu);
 }
-// x / d for 0 <= x < 2^31 with the host-computed (magic, shift) of Args (shift < 0: d == 1)
+// x / d for 0 <= x < 2^31 with the host-computed (magic, shift) of Args
 __device__ inline int fast_div(int x, uint32_t magic, int shift) {
-  return shift < 0 ? x : (int)(__umulhi((uint32_t)x, magic) >> shift);
+  return (int)((__umulhi((uint32_t)x, magic) + (uint32_t)x) >> shift);
 }
 __device__ inline int log2_of(int v) { return 31 - __clz(v); }
 
@@ -91,7 +91,7 @@ template <int ROWS, bool DGRAD> struct Gather {
   i32x4 rsrc;
   int loff[TL::UPW], kc[TL::UPW];
   uint64_t mask[TL::UPW];
-  int r, s, tap, cb, kt;  // uniform: tap (r,s) and channel base of the next k-tile
+  int r, s, tap, cb, kt, toff;  // uniform: tap (r,s), its offset, and the channel base of the next k-tile
   int CH, WI, taps, S, invS, logC;
   bool uniform_tap;
   // x / stride for x >= 0
@@ -156,11 +156,12 @@ template <int ROWS, bool DGRAD> struct Gather {
     tap = kk / CH;
     s = tap % g.S;
     r = tap / g.S;
+    toff = tap_off(r, s, g);
   }
   __device__ void issue(const Args& a, char* tile, int wave) {
     const ConvGeom& g = a.g;
     if (uniform_tap) {
-      const int uni = (tap_off(r, s, g) + cb) * 2;
+      const int uni = (toff + cb) * 2;
       const bool in = tap < taps;
 #pragma unroll
       for (int i = 0; i < TL::UPW; ++i) {
@@ -168,10 +169,11 @@ template <int ROWS, bool DGRAD> struct Gather {
         dma16(ok ? (uint32_t)(loff[i] + uni) : OOB, rsrc, tile + (wave * TL::UPW + i) * 1024);
       }
       cb += BK;
-      if (cb >= CH) {
+      if (cb >= CH) {  // next tap: the only place that pays for its offset
         cb = 0;
         ++tap;
         if (++s == g.S) { s = 0; ++r; }
+        toff = tap_off(r, s, g);
       }
     } else {
 #pragma unroll
@@ -298,19 +300,23 @@ template <int ROWS> struct WgradA {
   }
   __device__ void issue(const Args& a, char* tile, int wave) {
     const ConvGeom& g = a.g;
+    if (a.simple) {
+#pragma unroll
+      for (int i = 0; i < TL::UPW; ++i) {
+        dma16(off[i], rsrc, tile + (wave * TL::UPW + i) * 1024);
+        off[i] += step;
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < TL::UPW; ++i) {
-      uint32_t v = off[i];
-      if (!a.simple) {
-        const int t = fast_div(m[i], a.magicQ, a.shiftQ), q = m[i] - t * g.Q;
-        const int n = fast_div(t, a.magicP, a.shiftP), p = t - n * g.P;
-        const int h = p * g.stride + dr, w = q * g.stride + ds;
-        const bool ok = cv && m[i] < a.Kg && h >= 0 && h < g.H && w >= 0 && w < g.W;
-        v = ok ? (uint32_t)((((n * g.H + p * g.stride) * g.W + q * g.stride) * g.C + coloff) * 2) : OOB;
-        m[i] += BK;
-      }
+      const int t = fast_div(m[i], a.magicQ, a.shiftQ), q = m[i] - t * g.Q;
+      const int n = fast_div(t, a.magicP, a.shiftP), p = t - n * g.P;
+      const int h = p * g.stride + dr, w = q * g.stride + ds;
+      const bool ok = cv && m[i] < a.Kg && h >= 0 && h < g.H && w >= 0 && w < g.W;
+      const uint32_t v = ok ? (uint32_t)((((n * g.H + p * g.stride) * g.W + q * g.stride) * g.C + coloff) * 2) : OOB;
+      m[i] += BK;
       dma16(v, rsrc, tile + (wave * TL::UPW + i) * 1024);
-      off[i] += step;
     }
   }
 };
@@ -349,7 +355,7 @@ template <int FN> struct Patch {
 // phases interleave: the better trade for GEMMs with only one or two k-tiles, where a ring has
 // nothing to overlap and the run time is load latency plus epilogue.
 template <int PASS, int STAGES, int WM, int WN, int FM, int FN>
-__global__ __launch_bounds__(NT, STAGES == 1 ? 4 : 2) void igemm_dma_kernel(const Args a) {
+__global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void igemm_dma_kernel(const Args a) {
   static_assert(WM * WN == 4, "four wavefronts");
   constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
   constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE_BYTES = A_BYTES + B_BYTES;
@@ -361,10 +367,10 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : 2) void igemm_dma_kernel(cons
   __shared__ __attribute__((aligned(1024))) char smem[SMEM];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int logical = (blockIdx.x % NUM_XCD) * a.tiles_per_xcd + blockIdx.x / NUM_XCD;
-  if (logical >= a.tiles_m * a.tiles_n) return;
+  int logical, split;
+  if (!block_to_tile(a, logical, split)) return;
   const int m0 = (logical / a.tiles_n) * BM, n0 = (logical % a.tiles_n) * BN;
-  const int kt0 = blockIdx.y * a.nk_per_split;
+  const int kt0 = split * a.nk_per_split;
   const int kt1 = min(a.nk, kt0 + a.nk_per_split);
 
   f32x16 acc[FM][FN];
@@ -516,7 +522,7 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : 2) void igemm_dma_kernel(cons
       __builtin_amdgcn_wave_barrier();
     }
   } else {
-    float* dw = static_cast<float*>(a.out) + (long long)blockIdx.y * a.split_stride;
+    float* dw = static_cast<float*>(a.out) + (long long)split * a.split_stride;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -572,11 +578,22 @@ static void launch_tile(Args& a, int splits, hipStream_t st) {
   constexpr int BM = 2 * FM * 32, BN = 2 * FN * 32;
   a.tiles_m = (a.Mg + BM - 1) / BM;
   a.tiles_n = (a.Ng + BN - 1) / BN;
-  a.tiles_per_xcd = (a.tiles_m * a.tiles_n + NUM_XCD - 1) / NUM_XCD;
-  dim3 grid((unsigned)(a.tiles_per_xcd * NUM_XCD), (unsigned)splits);
+  a.splits = splits;
+  dim3 grid(grid_blocks(a));
   // GEMMs with at most SHORT_NK k-tiles: no ring, twice the workgroups per CU
-  if (PASS != PASS_WGRAD && a.nk <= SHORT_NK)
+  // Ring depth.  LDS decides how many workgroups share a CU (160 KiB); a grid with more workgroups than
+  // that keeps the CUs busiest with many short rings, a grid that cannot fill them anyway is better
+  // off with the deeper ring its LDS share allows: fewer exposed load latencies per workgroup.
+  constexpr int STAGE = (BM + BN) * ROWB;
+  constexpr int DEEP2 = 2 * 3 * STAGE <= 160 * 1024 ? 3 : 2;  // two workgroups per CU
+  constexpr int DEEP1 = 5 * STAGE <= 160 * 1024 ? 5 : 4;      // one workgroup per CU
+  const long long blocks = (long long)a.tiles_m * a.tiles_n * splits;
+  if (PASS != PASS_WGRAD && a.nk <= SHORT_NK)  // no ring, four workgroups per CU
     hipLaunchKernelGGL((igemm_dma_kernel<PASS, (PASS == PASS_WGRAD ? 2 : 1), 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
+  else if (blocks <= 256 && a.nk_per_split >= 8)
+    hipLaunchKernelGGL((igemm_dma_kernel<PASS, DEEP1, 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
+  else if (blocks <= 512 && DEEP2 == 3)
+    hipLaunchKernelGGL((igemm_dma_kernel<PASS, DEEP2, 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
   else
     hipLaunchKernelGGL((igemm_dma_kernel<PASS, 2, 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
 }
