@@ -51,9 +51,12 @@ __device__ inline i32x4 make_rsrc(const void* base, uint32_t bytes) {
 // direct load it knows about gets a vmcnt(0)).  The loop orders LDS writes and reads itself: vmcnt
 // wait, then barrier.  The address work per load is a handful of VALU instructions (a fixed per-lane
 // offset plus a wavefront-uniform one, and a mask test): one MFMA lasts only 8 VALU issue slots.
-__device__ inline void dma16(uint32_t voff, i32x4 rsrc, char* wave_base) {
-  const uint32_t lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(wave_base));
+__device__ inline void dma16(uint32_t voff, i32x4 rsrc, uint32_t lds) {  // lds: wavefront-uniform LDS byte address
   asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds" : : "v"(voff), "s"(rsrc), "s"(lds) : "memory");
+}
+// LDS byte address of a __shared__ object, as a wavefront-uniform 32-bit value
+__device__ inline uint32_t lds_addr(const void* p) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(p));
 }
 template <int N> __device__ inline void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);  // vmcnt(N), other counters untouched
@@ -158,7 +161,7 @@ template <int ROWS, bool DGRAD> struct Gather {
     r = tap / g.S;
     toff = tap_off(r, s, g);
   }
-  __device__ void issue(const Args& a, char* tile, int wave) {
+  __device__ void issue(const Args& a, uint32_t tile, int wave) {
     const ConvGeom& g = a.g;
     if (uniform_tap) {
       const int uni = (toff + cb) * 2;
@@ -166,7 +169,7 @@ template <int ROWS, bool DGRAD> struct Gather {
 #pragma unroll
       for (int i = 0; i < TL::UPW; ++i) {
         const bool ok = in && ((mask[i] >> tap) & 1);
-        dma16(ok ? (uint32_t)(loff[i] + uni) : OOB, rsrc, tile + (wave * TL::UPW + i) * 1024);
+        dma16(ok ? (uint32_t)(loff[i] + uni) : OOB, rsrc, tile + (uint32_t)((wave * TL::UPW + i) * 1024));
       }
       cb += BK;
       if (cb >= CH) {  // next tap: the only place that pays for its offset
@@ -214,7 +217,7 @@ template <int ROWS> struct DgradB {
     kob = kk % g.K;
     rs = kk / g.K;
   }
-  __device__ void issue(const Args& a, char* tile, int wave) {
+  __device__ void issue(const Args& a, uint32_t tile, int wave) {
     const ConvGeom& g = a.g;
     if (uniform_tap) {
       const uint32_t uni = (uint32_t)((rs * g.C * g.K + kob) * 2);
@@ -235,19 +238,27 @@ template <int ROWS> struct DgradB {
 };
 
 // ---- row-contiguous operands ---------------------------------------------------------------------
-// Stored as they lie in memory: LDS[(k*CPR + chunk)*16], k = 0..63, chunk = 8 adjacent rows.
-// Wave w fills units u = w*UPW + i; a unit is KPU k-rows; lane l owns k-row u*KPU + l/CPR, chunk l%CPR.
+// Stored [k][row] as they lie in memory, a k-row being CPR 16-byte chunks of 8 adjacent rows, except that
+// chunk c of k-row k sits at chunk position c ^ 2*(k & 3): a transpose read fetches, per group of 16
+// lanes, 32 bytes from each of four consecutive k-rows, and k-rows are a whole number of bank sweeps
+// apart, so unswizzled those four pieces would collide on the same 8 banks.
+// Wave w fills units u = w*UPW + i; a unit is KPU k-rows; lane l fills position l%CPR of k-row
+// u*KPU + l/CPR (KPU is a multiple of 4, so the swizzle depends on the lane only).
 template <int ROWS> struct RTile {
   static constexpr int UPW = ROWS / 32;
   static constexpr int CPR = ROWS / 8;   // chunks per k-row
   static constexpr int KPU = 64 / CPR;   // k-rows per 1 KiB unit
+  static_assert(KPU % 4 == 0 && CPR >= 8, "swizzle assumes whole groups of four k-rows per unit");
   __device__ static int k_of(int wave, int i, int lane) { return (wave * UPW + i) * KPU + lane / CPR; }
-  __device__ static int chunk_of(int lane) { return lane % CPR; }
+  // the chunk of its k-row (8 adjacent rows of the tile) that a lane fetches
+  __device__ static int chunk_of(int lane) { return (lane % CPR) ^ (((lane / CPR) & 3) << 1); }
   // byte address a lane hands to ds_read_b64_tr_b16 to receive, for its own row nf + (lane & 31), the
-  // 4 k-values kb .. kb+3: lanes 16g..16g+15 together read k-rows kb..kb+3 x rows nf+16g .. nf+16g+15
+  // 4 k-values kb .. kb+3 (kb a multiple of 4): lanes 16g..16g+15 together read k-rows kb..kb+3 x rows
+  // nf+16g .. nf+16g+15
   __device__ static int tr_off(int kb, int nf, int lane) {
-    int j = lane & 15, g = (lane >> 4) & 1;
-    return ((kb + (j >> 2)) * ROWS + nf + 16 * g + 4 * (j & 3)) * 2;
+    const int j = lane & 15, g = (lane >> 4) & 1;
+    const int k = kb + (j >> 2), n = nf + 16 * g + 4 * (j & 3);
+    return k * ROWS * 2 + (((n >> 3) ^ ((k & 3) << 1)) << 4) + (n & 7) * 2;
   }
 };
 
@@ -265,7 +276,7 @@ template <int ROWS> struct PlainR {
     for (int i = 0; i < TL::UPW; ++i)
       off[i] = col < a.Ng ? (uint32_t)(((kt0 * BK + TL::k_of(wave, i, lane)) * a.g.K + col) * 2) : OOB;
   }
-  __device__ void issue(const Args&, char* tile, int wave) {
+  __device__ void issue(const Args&, uint32_t tile, int wave) {
 #pragma unroll
     for (int i = 0; i < TL::UPW; ++i) {
       dma16(off[i], rsrc, tile + (wave * TL::UPW + i) * 1024);
@@ -298,7 +309,7 @@ template <int ROWS> struct WgradA {
       off[i] = cv ? (uint32_t)((m[i] * g.C + c0) * 2) : OOB;  // the 1x1 / stride 1 / no padding case
     }
   }
-  __device__ void issue(const Args& a, char* tile, int wave) {
+  __device__ void issue(const Args& a, uint32_t tile, int wave) {
     const ConvGeom& g = a.g;
     if (a.simple) {
 #pragma unroll
@@ -366,7 +377,8 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
   typedef Sel<PASS, BN, false> SB;
   __shared__ __attribute__((aligned(1024))) char smem[SMEM];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t ring = lds_addr(smem);
   int logical, split;
   if (!block_to_tile(a, logical, split)) return;
   const int m0 = (logical / a.tiles_n) * BM, n0 = (logical % a.tiles_n) * BN;
@@ -387,7 +399,10 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
   la.init(a, m0, wave, lane, kt0);
   lb.init(a, n0, wave, lane, kt0);
 
-  auto multiply = [&](const char* As) {
+  // one k-tile: four k-steps of 16; `between(ks)` runs after the MFMAs of step ks are issued, which
+  // is where the loop puts the address work and the issue of the next direct loads, so that they
+  // overlap the matrix pipeline instead of delaying the first LDS reads after the barrier
+  auto multiply = [&](const char* As, auto between) {
     const char* Bs = As + A_BYTES;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
@@ -401,35 +416,36 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
 #pragma unroll
         for (int j = 0; j < FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+      between(ks);
     }
   };
 
   if constexpr (STAGES == 1) {
     for (int kt = kt0; kt < kt1; ++kt) {
       if (kt > kt0) __syncthreads();  // everyone is done reading the previous k-tile
-      la.issue(a, smem, wave);
-      lb.issue(a, smem + A_BYTES, wave);
+      la.issue(a, ring, wave);
+      lb.issue(a, ring + A_BYTES, wave);
       wait_vmcnt<0>();
       __syncthreads();
-      multiply(smem);
+      multiply(smem, [](int) {});
     }
   } else {
     // prologue: k-tiles kt0 .. kt0+STAGES-2 (tiles past the end fetch zeros: the counts stay uniform)
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) {
-      la.issue(a, smem + s * STAGE_BYTES, wave);
-      lb.issue(a, smem + s * STAGE_BYTES + A_BYTES, wave);
+      la.issue(a, ring + s * STAGE_BYTES, wave);
+      lb.issue(a, ring + s * STAGE_BYTES + A_BYTES, wave);
     }
+    int cur = 0, nxt = STAGES - 1;  // ring slots of k-tile kt and of k-tile kt+STAGES-1 (the one kt-1 used)
     for (int kt = kt0; kt < kt1; ++kt) {
-      const int cur = (kt - kt0) % STAGES;
       wait_vmcnt<(STAGES - 2) * LOADS>();  // this lane's direct loads of k-tile kt have landed
       __syncthreads();                     // ... and everyone's; everyone is done reading tile kt-1
-      {
-        const int nxt = (kt - kt0 + STAGES - 1) % STAGES;  // the buffer tile kt-1 used
-        la.issue(a, smem + nxt * STAGE_BYTES, wave);
-        lb.issue(a, smem + nxt * STAGE_BYTES + A_BYTES, wave);
-      }
-      multiply(smem + cur * STAGE_BYTES);
+      multiply(smem + cur * STAGE_BYTES, [&](int ks) {
+        if (ks == 0) la.issue(a, ring + nxt * STAGE_BYTES, wave);
+        if (ks == 1) lb.issue(a, ring + nxt * STAGE_BYTES + A_BYTES, wave);
+      });
+      cur = cur + 1 == STAGES ? 0 : cur + 1;
+      nxt = nxt + 1 == STAGES ? 0 : nxt + 1;
     }
   }
   wait_vmcnt<0>();
