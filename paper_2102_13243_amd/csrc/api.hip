@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "s4tf_internal.h"
@@ -130,22 +131,61 @@ static size_t conv_vjp_ws_parts(const s4tf_conv_desc& d, size_t* dz_bytes) {
   return dz + align_up(wg, 256);
 }
 
-static int conv_fwd_impl(const s4tf_conv_desc& d, const void* x, const void* w, const float* bias, void* y, hipStream_t st) {
+static int conv_fwd_impl(const s4tf_conv_desc& d, const void* x, const void* w, const float* bias, void* y, hipStream_t st,
+                         float* stats_part = nullptr, int* stats_rows = nullptr) {
   ConvGeom g = conv_geom(d);
-  if (d.groups == 1) return igemm_fwd(g, d.dtype, x, w, bias, d.act, y, st);
+  if (stats_rows) *stats_rows = 0;
+  if (d.groups == 1) return igemm_fwd(g, d.dtype, x, w, bias, d.act, y, st, stats_part, stats_rows);
   return dwconv_fwd(g, d.dtype, x, w, bias, d.act, y, st);
 }
 // dz: cotangent after the activation pullback
-static int conv_vjp_impl(const s4tf_conv_desc& d, const void* x, const void* w, const void* dz, void* dx, float* dw,
-                         float* dbias, void* wg_ws, size_t wg_bytes, hipStream_t st) {
+// The pullback's two halves are independent given dz: the input cotangent, and the parameter gradients.
+static int conv_dgrad_impl(const s4tf_conv_desc& d, const void* w, const void* dz, void* dx, hipStream_t st) {
+  ConvGeom g = conv_geom(d);
+  if (d.groups == 1) return igemm_dgrad(g, d.dtype, dz, w, dx, d.accumulate_dx, st);
+  return dwconv_dgrad(g, d.dtype, dz, w, dx, d.accumulate_dx, st);
+}
+static int conv_param_grads_impl(const s4tf_conv_desc& d, const void* x, const void* dz, float* dw, float* dbias,
+                                 void* wg_ws, size_t wg_bytes, hipStream_t st) {
   ConvGeom g = conv_geom(d);
   if (dbias) CHECK(colsum(d.dtype, dz, (size_t)g.N * g.P * g.Q, g.K, dbias, st));
-  if (d.groups == 1) {
-    if (dx) CHECK(igemm_dgrad(g, d.dtype, dz, w, dx, d.accumulate_dx, st));
-    return igemm_wgrad(g, d.dtype, x, dz, dw, wg_ws, wg_bytes, st);
-  }
-  if (dx) CHECK(dwconv_dgrad(g, d.dtype, dz, w, dx, d.accumulate_dx, st));
+  if (d.groups == 1) return igemm_wgrad(g, d.dtype, x, dz, dw, wg_ws, wg_bytes, st);
   return dwconv_wgrad(g, d.dtype, x, dz, dw, wg_ws, st);
+}
+static int conv_vjp_impl(const s4tf_conv_desc& d, const void* x, const void* w, const void* dz, void* dx, float* dw,
+                         float* dbias, void* wg_ws, size_t wg_bytes, hipStream_t st) {
+  if (dx) CHECK(conv_dgrad_impl(d, w, dz, dx, st));
+  return conv_param_grads_impl(d, x, dz, dw, dbias, wg_ws, wg_bytes, st);
+}
+
+// ---- second stream of the train step -------------------------------------------------------------------
+// Parameter gradients of the convolutions are needed only by the optimizer at the end of the step, while
+// the chain of input cotangents (dgrad, BatchNorm pullback) is latency and bandwidth bound and leaves
+// the matrix cores idle: the step forks the filter-gradient kernels onto a stream of the library's own
+// (default priority) and joins it before the optimizer.  One stream and two events per device, created
+// on first use and kept for the life of the process.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+static std::mutex g_side_mutex;
+static SideStream g_side[64];
+static int side_stream(SideStream** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return fail(S4TF_ERR_DEVICE, "cannot tell the current device");
+  std::lock_guard<std::mutex> lock(g_side_mutex);
+  SideStream& s = g_side[dev];
+  if (!s.stream) {
+    hipStream_t st = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&e0, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&e1, hipEventDisableTiming) != hipSuccess)
+      return fail(S4TF_ERR_DEVICE, "cannot create the second stream of the train step: %s", hipGetErrorString(hipGetLastError()));
+    s.stream = st; s.fork = e0; s.join = e1;
+  }
+  *out = &s;
+  return S4TF_OK;
 }
 
 // ---- whole-step planning -------------------------------------------------------------------------------
@@ -167,6 +207,7 @@ struct NetPlan {
   std::vector<size_t> xpad_off, wpad_off, dwpad_off;
   size_t param_count;
   size_t scratch_off, scratch_bytes, total_bytes;
+  size_t wscratch_off, wscratch_bytes;  // scratch of the filter-gradient kernels, which run on a stream of their own
 };
 
 static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
@@ -185,7 +226,7 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
   pl.wpad_off.assign(nops, 0);
   pl.dwpad_off.assign(nops, 0);
   pl.t[0] = TensorPlan{net->n, net->h, net->w, net->c, (size_t)net->n * net->h * net->w * net->c, 0, 0, 0, -1, 0};
-  size_t pcount = 0, off = 0, scratch = 0;
+  size_t pcount = 0, off = 0, scratch = 0, wscratch = 0;
   auto add_param = [&](int op, int slot, size_t n) {
     pl.poff[2 * op + slot] = (int64_t)pcount;
     pl.psize[2 * op + slot] = (int64_t)n;
@@ -212,7 +253,12 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
           g.C = pl.pad_c[i];
         }
         size_t ws = op.groups == 1 ? igemm_wgrad_workspace(g, net->dtype) : dwconv_wgrad_workspace(g);
-        if (ws > scratch) scratch = ws;
+        if (ws > wscratch) wscratch = ws;
+        // a BatchNorm right behind takes its statistics from partial sums the convolution leaves in scratch
+        if (i + 1 < nops && net->ops[i + 1].kind == S4TF_OP_BN && net->ops[i + 1].in == i + 1 && op.groups == 1) {
+          ws = igemm_fwd_stats_bytes(g);
+          if (ws > scratch) scratch = ws;
+        }
         break;
       }
       case S4TF_OP_BN: {
@@ -296,7 +342,9 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
     }
   pl.scratch_off = off;
   pl.scratch_bytes = align_up(scratch, 256);
-  pl.total_bytes = off + pl.scratch_bytes;
+  pl.wscratch_off = pl.scratch_off + pl.scratch_bytes;
+  pl.wscratch_bytes = align_up(wscratch, 256);
+  pl.total_bytes = pl.wscratch_off + pl.wscratch_bytes;
   pl.param_count = pcount;
   return S4TF_OK;
 }
@@ -480,6 +528,29 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   const int nops = net->n_ops;
   const int dt = net->dtype;
   void* scratch = ws + pl.scratch_off;
+  void* wscratch = ws + pl.wscratch_off;
+  SideStream* side = nullptr;
+  CHECK(side_stream(&side));
+  // Whatever way this function returns, `st` ends up waiting for what the side stream was given, so
+  // that in stream order on `st` the step is over (and its workspace free) when its last kernel is.
+  struct Join {
+    SideStream* s; hipStream_t st; bool forked = false;
+    int now() {
+      if (!forked) return S4TF_OK;
+      forked = false;
+      if (hipEventRecord(s->join, s->stream) != hipSuccess || hipStreamWaitEvent(st, s->join, 0) != hipSuccess)
+        return fail(S4TF_ERR_DEVICE, "train step: stream join failed");
+      return S4TF_OK;
+    }
+    ~Join() { (void)now(); }
+  } join{side, st};
+  // everything `st` has queued so far (the previous step's optimizer included) precedes the side stream's work
+  auto fork = [&]() -> int {
+    join.forked = true;
+    if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+      return fail(S4TF_ERR_DEVICE, "train step: stream fork failed");
+    return S4TF_OK;
+  };
   auto act_ptr = [&](int t) -> const void* { return pl.t[t].root == 0 ? batch->x : (const void*)(ws + pl.t[t].act_off); };
   auto out_ptr = [&](int t) -> void* { return ws + pl.t[t].act_off; };
   auto grad_ptr = [&](int t) -> void* { return ws + pl.t[t].grad_off; };
@@ -495,28 +566,35 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   };
 
   // ---- forward ----
+  int stats_rows = 0;  // > 0: the previous op, a convolution, left partial statistics of its output in scratch
   for (int i = 0; i < nops - 1; ++i) {
     const s4tf_op& op = net->ops[i];
     const TensorPlan& in = pl.t[op.in];
+    const int prev_stats_rows = stats_rows;
+    stats_rows = 0;
     switch (op.kind) {
       case S4TF_OP_CONV: {
         s4tf_conv_desc d = conv_desc(i, 0);
         const float* bias = op.has_bias ? params->master + pl.poff[2 * i + 1] : nullptr;
+        const bool bn_next = net->ops[i + 1].kind == S4TF_OP_BN && net->ops[i + 1].in == i + 1 && op.groups == 1;
+        float* sp = bn_next ? static_cast<float*>(scratch) : nullptr;
+        int* sr = bn_next ? &stats_rows : nullptr;
         if (pl.pad_c[i]) {  // zero-padded channels contribute nothing: same result, 16-byte loaders
           CHECK(pad_channels(dt, act_ptr(op.in), ws + pl.xpad_off[i], (long long)in.n * in.h * in.w, in.c, pl.pad_c[i], 1, st));
           CHECK(pad_channels(dt, conv_w(i), ws + pl.wpad_off[i], (long long)op.r * op.s, in.c, pl.pad_c[i], op.k, st));
           d.c = pl.pad_c[i];
-          CHECK(conv_fwd_impl(d, ws + pl.xpad_off[i], ws + pl.wpad_off[i], bias, out_ptr(i + 1), st));
+          CHECK(conv_fwd_impl(d, ws + pl.xpad_off[i], ws + pl.wpad_off[i], bias, out_ptr(i + 1), st, sp, sr));
           break;
         }
-        CHECK(conv_fwd_impl(d, act_ptr(op.in), conv_w(i), bias, out_ptr(i + 1), st));
+        CHECK(conv_fwd_impl(d, act_ptr(op.in), conv_w(i), bias, out_ptr(i + 1), st, sp, sr));
         break;
       }
       case S4TF_OP_BN: {
         s4tf_bn_desc d = {in.n, in.h, in.w, in.c, op.eps, op.act, dt, 0};
         float* stats = reinterpret_cast<float*>(ws + pl.stat_off[i]);
         CHECK(bn_fwd(d, act_ptr(op.in), op.res >= 0 ? act_ptr(op.res) : nullptr, params->master + pl.poff[2 * i],
-                     params->master + pl.poff[2 * i + 1], out_ptr(i + 1), stats, stats + in.c, scratch, st));
+                     params->master + pl.poff[2 * i + 1], out_ptr(i + 1), stats, stats + in.c, scratch, st,
+                     prev_stats_rows > 0 ? static_cast<const float*>(scratch) : nullptr, prev_stats_rows));
         break;
       }
       case S4TF_OP_AVGPOOL2:
@@ -557,18 +635,22 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         s4tf_conv_desc d = conv_desc(i, written[src] ? 1 : 0);
         if (op.act != S4TF_ACT_NONE)  // in place: dy is not needed once dz exists
           CHECK(act_vjp(dt, op.act, out_ptr(i + 1), dy, dy, pl.t[i + 1].elems, st));
+        // dz is final: the parameter gradients go to the side stream, the input cotangent stays here
+        CHECK(fork());
+        float* dbias = op.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr;
         if (pl.pad_c[i]) {  // the batch has no cotangent; the filter gradient of the padded channels is dropped
           d.c = pl.pad_c[i];
           float* dwp = reinterpret_cast<float*>(ws + pl.dwpad_off[i]);
-          CHECK(conv_vjp_impl(d, ws + pl.xpad_off[i], ws + pl.wpad_off[i], dy, nullptr, dwp,
-                              op.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr, scratch, pl.scratch_bytes, st));
-          CHECK(unpad_channels_f32(dwp, params->grad + pl.poff[2 * i], (long long)op.r * op.s, in.c, pl.pad_c[i], op.k, st));
+          CHECK(conv_param_grads_impl(d, ws + pl.xpad_off[i], dy, dwp, dbias, wscratch, pl.wscratch_bytes, side->stream));
+          CHECK(unpad_channels_f32(dwp, params->grad + pl.poff[2 * i], (long long)op.r * op.s, in.c, pl.pad_c[i], op.k, side->stream));
           break;
         }
-        CHECK(conv_vjp_impl(d, act_ptr(src), conv_w(i), dy, want_dx ? grad_ptr(src) : nullptr,
-                            params->grad + pl.poff[2 * i], op.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr,
-                            scratch, pl.scratch_bytes, st));
-        written[src] = 1;
+        CHECK(conv_param_grads_impl(d, act_ptr(src), dy, params->grad + pl.poff[2 * i], dbias, wscratch, pl.wscratch_bytes,
+                                    side->stream));
+        if (want_dx) {
+          CHECK(conv_dgrad_impl(d, conv_w(i), dy, grad_ptr(src), st));
+          written[src] = 1;
+        }
         break;
       }
       case S4TF_OP_BN: {
@@ -596,7 +678,8 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         break;
     }
   }
-  // ---- optimizer: one launch over the whole arena ----
+  // ---- optimizer: one launch over the whole arena, once the side stream's gradients are in ----
+  CHECK(join.now());
   return sgd(params->count, params->master, params->velocity, params->grad, bf16 ? params->lowp : nullptr, lr,
              net->momentum, st);
 }

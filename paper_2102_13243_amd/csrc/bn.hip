@@ -166,6 +166,51 @@ __global__ __launch_bounds__(256) void bn_stats_finalize_kernel(const T* __restr
   invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
 }
 
+// Statistics from the partial sums a convolution left behind: run i covers rows [i*rows, min(M, (i+1)*rows))
+// and holds per channel s_i = sum x and q_i = sum (x - s_i/n_i)^2.  With S = sum s_i:
+//   mean = S/M,   M*var = sum q_i + sum s_i^2/n_i - S^2/M      (all in double)
+// There are thousands of runs and few channels, so a block takes only CPB channels and spreads the runs
+// over 1024/CPB lanes; lanes are added by a shuffle butterfly, the 16 wavefronts through LDS, in a
+// fixed order.
+template <int CPB>
+__global__ __launch_bounds__(1024) void bn_stats_from_runs_kernel(const float* __restrict__ part, int runs, int rows,
+                                                                  long long M, int C, float eps, float* __restrict__ mean,
+                                                                  float* __restrict__ invstd) {
+  constexpr int ZL = 1024 / CPB;
+  __shared__ double sh[16][3][CPB];
+  const int cl = threadIdx.x % CPB, c = blockIdx.x * CPB + cl, zl = threadIdx.x / CPB;
+  const double inv_rows = 1.0 / (double)rows;
+  const double inv_last = 1.0 / (double)(M - (long long)(runs - 1) * rows);
+  double v[3] = {0.0, 0.0, 0.0};
+  if (c < C) {
+#pragma unroll 4
+    for (int i = zl; i < runs; i += ZL) {
+      const double s = (double)part[((long long)i * 2) * C + c];
+      const double q = (double)part[((long long)i * 2 + 1) * C + c];
+      v[0] += s;
+      v[1] += q;
+      v[2] += s * s * (i == runs - 1 ? inv_last : inv_rows);
+    }
+  }
+  for (int off = CPB; off < 64; off <<= 1) {
+#pragma unroll
+    for (int e = 0; e < 3; ++e) v[e] += __shfl_xor(v[e], off, 64);
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane < CPB) {
+#pragma unroll
+    for (int e = 0; e < 3; ++e) sh[wave][e][cl] = v[e];
+  }
+  __syncthreads();
+  if (threadIdx.x >= CPB || c >= C) return;
+  double S = 0.0, Q = 0.0, W = 0.0;
+  for (int w = 0; w < 16; ++w) { S += sh[w][0][cl]; Q += sh[w][1][cl]; W += sh[w][2][cl]; }
+  double var = (Q + W - S * S / (double)M) / (double)M;
+  if (var < 0.0) var = 0.0;
+  mean[c] = (float)(S / (double)M);
+  invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
+}
+
 template <typename T, int V>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
@@ -345,14 +390,24 @@ size_t bn_workspace(size_t M, int C) {
   } while (0)
 
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
-           void* y, float* mean, float* invstd, void* ws, hipStream_t st) {
+           void* y, float* mean, float* invstd, void* ws, hipStream_t st, const float* stats_part, int stats_rows) {
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
   const Plan pr = make_plan((size_t)M, C, d.dtype, 1024, 16);  // reduction: fewer, longer blocks
   const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, UNROLL);
   float* part = static_cast<float*>(ws);
   int rc;
-  {
+  if (stats_part && stats_rows > 0) {
+    ProfScope ps(PC_BN_STATS, st);
+    const int runs = (int)((M + stats_rows - 1) / stats_rows);
+    if (C >= 256)
+      hipLaunchKernelGGL(bn_stats_from_runs_kernel<8>, dim3((C + 7) / 8), dim3(1024), 0, st, stats_part, runs, stats_rows, M, C,
+                         d.eps, mean, invstd);
+    else
+      hipLaunchKernelGGL(bn_stats_from_runs_kernel<2>, dim3((C + 1) / 2), dim3(1024), 0, st, stats_part, runs, stats_rows, M, C,
+                         d.eps, mean, invstd);
+    if ((rc = launch_status("bn_stats_from_runs")) != S4TF_OK) return rc;
+  } else {
     ProfScope ps(PC_BN_STATS, st);
     BN_LAUNCH(bn_stats_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(float), (const T*)x, part, M, C, pr.cvb, pr.per);
     if ((rc = launch_status("bn_stats")) != S4TF_OK) return rc;

@@ -709,19 +709,31 @@ void wgrad_split(const ConvGeom& g, int dtype, int& splits, int& nk_per_split) {
 }  // namespace
 
 int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, int act,
-              void* y, hipStream_t st) {
+              void* y, hipStream_t st, float* stats_part, int* stats_rows) {
   Args a = {};
   a.g = g; a.a = x; a.b = w; a.out = y; a.bias = bias; a.act = act;
   a.Mg = g.N * g.P * g.Q; a.Ng = g.K; a.Kg = g.R * g.S * g.C;
   a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
   fill_sizes(a, PASS_FWD, dtype);
+  if (stats_rows) *stats_rows = 0;
   ProfScope ps(PC_CONV_FWD, st);
   if (dtype == S4TF_BF16) {
     fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
+    if (stats_part && stats_rows && !bias && act == S4TF_ACT_NONE && igemm_dma_ok(PASS_FWD, g, a)) {
+      a.stats = stats_part;
+      const int rc = igemm_dma_launch(PASS_FWD, a, 1, st);
+      *stats_rows = a.stats_rows;
+      return rc;
+    }
     return launch<bf16_t, PASS_FWD>(a, 1, st);
   }
   fill_tiles(a, 128, 128, Cfg<float>::BK);
   return launch<float, PASS_FWD>(a, 1, st);
+}
+
+size_t igemm_fwd_stats_bytes(const ConvGeom& g) {  // the finest runs any tile uses are 32 rows
+  const size_t M = (size_t)g.N * g.P * g.Q;
+  return (M + 31) / 32 * 2 * g.K * sizeof(float);
 }
 
 int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,

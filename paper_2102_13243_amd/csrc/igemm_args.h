@@ -14,6 +14,8 @@ struct Args {
   const void* b;
   void* out;
   const float* bias;
+  float* stats;       // forward only, optional: per-column partial sums of the stored outputs, see igemm_fwd
+  int stats_rows;     // set by the launcher: output rows per partial sum
   int Mg, Ng, Kg;
   int act, accumulate, simple;
   int scatter2;                     // dgrad of a 1x1 / stride 2 / no padding layer run over the pixels of dy

@@ -448,6 +448,46 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
       nxt = nxt + 1 == STAGES ? 0 : nxt + 1;
     }
   }
+  if constexpr (PASS == PASS_FWD) {
+    // Optional by-product for a BatchNorm that follows: per channel (column), over this wavefront's
+    // FM*32 output rows, the sum of the values as stored (rounded to bf16) and the sum of their squared
+    // deviations from that run's own mean.  Lanes l and l^32 hold the two halves of a column.
+    if (a.stats) {
+      const int rbase = m0 + arow;
+      const int cnt = min(max(a.Mg - rbase, 0), FM * 32);
+      float* part = a.stats + (long long)(rbase / (FM * 32)) * 2 * a.Ng;
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        float r[FM][16];
+        float s1 = 0.f;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = rbase + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+            r[i][v] = row < a.Mg ? bf16_to_f32(f32_to_bf16(acc[i][j][v])) : 0.f;
+            s1 += r[i][v];
+          }
+        s1 += __shfl_xor(s1, 32, 64);
+        const float mean = cnt > 0 ? s1 / (float)cnt : 0.f;
+        float m2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = rbase + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+            const float dlt = r[i][v] - mean;
+            if (row < a.Mg) m2 += dlt * dlt;
+          }
+        m2 += __shfl_xor(m2, 32, 64);
+        const int col = n0 + brow + j * 32 + (lane & 31);
+        if (lane < 32 && col < a.Ng && cnt > 0) {  // a run with no valid row has no slot
+          part[col] = s1;
+          part[a.Ng + col] = m2;
+        }
+      }
+    }
+  }
   wait_vmcnt<0>();
   __syncthreads();  // the LDS tiles are idle: reuse them for the output tile
 
@@ -595,6 +635,7 @@ static void launch_tile(Args& a, int splits, hipStream_t st) {
   a.tiles_m = (a.Mg + BM - 1) / BM;
   a.tiles_n = (a.Ng + BN - 1) / BN;
   a.splits = splits;
+  a.stats_rows = FM * 32;
   dim3 grid(grid_blocks(a));
   // GEMMs with at most SHORT_NK k-tiles: no ring, twice the workgroups per CU
   // Ring depth.  LDS decides how many workgroups share a CU (160 KiB); a grid with more workgroups than

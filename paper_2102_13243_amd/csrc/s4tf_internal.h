@@ -21,13 +21,18 @@ __host__ __device__ inline float bf16_to_f32(bf16_t v) {
   x.u = (uint32_t)v << 16;
   return x.f;
 }
-// round to nearest, ties to even; NaN stays NaN
+// round to nearest, ties to even; NaN stays NaN.  Device code takes the hardware conversion of gfx950
+// (v_cvt_pk_bf16_f32, two values per instruction when the compiler can pair them).
 __host__ __device__ inline bf16_t f32_to_bf16(float f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_bit_cast(bf16_t, (__bf16)f);
+#else
   union { uint32_t u; float f; } x;
   x.f = f;
   if ((x.u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((x.u >> 16) | 0x40u);
   x.u += 0x7fffu + ((x.u >> 16) & 1u);
   return (bf16_t)(x.u >> 16);
+#endif
 }
 template <typename T> __device__ inline float to_f32(T v);
 template <> __device__ inline float to_f32<float>(float v) { return v; }
@@ -79,8 +84,13 @@ inline ConvGeom conv_geom(const s4tf_conv_desc& d) {
 }
 
 // dense (groups == 1) convolution as implicit GEMM on MFMA
+// stats_part (optional, with bias == NULL and act == none): the kernel also writes, for every run of
+// *stats_rows consecutive output rows (pixels) r and every channel, the sum of the stored outputs and the
+// sum of their squared deviations from that run's own mean: stats_part[(r*2 + 0)*K + k], [(r*2 + 1)*K + k];
+// ceil(N*P*Q / *stats_rows) runs.  *stats_rows comes back 0 when the kernel that ran does not do this.
 int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, int act,
-              void* y, hipStream_t st);
+              void* y, hipStream_t st, float* stats_part = nullptr, int* stats_rows = nullptr);
+size_t igemm_fwd_stats_bytes(const ConvGeom& g);  // upper bound on the size of stats_part
 int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,
                 hipStream_t st);
 size_t igemm_wgrad_workspace(const ConvGeom& g, int dtype);
@@ -106,8 +116,11 @@ int unpad_channels_f32(const float* src, float* dst, long long outer, int C, int
 
 // batch norm
 size_t bn_workspace(size_t M, int C);
+// stats_part / stats_rows: per-channel partial sums that the producing convolution left (see igemm_fwd);
+// NULL / 0: the statistics are computed here from x
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
-           void* y, float* mean, float* invstd, void* ws, hipStream_t st);
+           void* y, float* mean, float* invstd, void* ws, hipStream_t st, const float* stats_part = nullptr,
+           int stats_rows = 0);
 int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* mean,
            const float* invstd, const void* dy, void* dx, void* dres, float* dgamma, float* dbeta,
            void* ws, hipStream_t st);
