@@ -127,37 +127,48 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ x, 
   }
 }
 
-// Adds the chunks' partial sums [chunk][2][C] of 8 channels per block in double: 32 lanes per
-// channel stride over the chunks, then lane 0 adds the 32 lane totals in order.
+// Adds the chunks' partial sums [chunk][2][C] of 8 channels per block of 1024 threads in double: 128
+// lanes per channel stride over the chunks (several loads in flight each), a shuffle butterfly adds
+// the lanes of a wavefront, thread c adds the 16 wavefront totals in order.  Result in threads 0..7.
+constexpr int FIN_THREADS = 1024;
 template <typename P>
-__device__ inline void sum_chunks(const P* __restrict__ part, int chunks, int C, int c, int zl, double (*sh)[2][8],
-                                  double& s1, double& s2) {
+__device__ inline void sum_chunks(const P* __restrict__ part, int chunks, int C, int c, double (*sh)[2][8], double& s1,
+                                  double& s2) {
+  const int zl = threadIdx.x >> 3, cl = threadIdx.x & 7;
   double a = 0.0, b = 0.0;
-  if (c < C)
-    for (int z = zl; z < chunks; z += 32) {
+  if (c < C) {
+#pragma unroll 4
+    for (int z = zl; z < chunks; z += FIN_THREADS / 8) {
       a += (double)part[(long long)z * 2 * C + c];
       b += (double)part[(long long)z * 2 * C + C + c];
     }
-  sh[zl][0][threadIdx.x & 7] = a;
-  sh[zl][1][threadIdx.x & 7] = b;
+  }
+  for (int off = 8; off < 64; off <<= 1) {
+    a += __shfl_xor(a, off, 64);
+    b += __shfl_xor(b, off, 64);
+  }
+  if ((threadIdx.x & 63) < 8) {
+    sh[threadIdx.x >> 6][0][cl] = a;
+    sh[threadIdx.x >> 6][1][cl] = b;
+  }
   __syncthreads();
   s1 = s2 = 0.0;
-  if (zl == 0)
-    for (int l = 0; l < 32; ++l) {
-      s1 += sh[l][0][threadIdx.x & 7];
-      s2 += sh[l][1][threadIdx.x & 7];
+  if (threadIdx.x < 8)
+    for (int w = 0; w < FIN_THREADS / 64; ++w) {
+      s1 += sh[w][0][cl];
+      s2 += sh[w][1][cl];
     }
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void bn_stats_finalize_kernel(const T* __restrict__ x, const float* __restrict__ part,
-                                                                int chunks, long long M, int C, float eps,
-                                                                float* __restrict__ mean, float* __restrict__ invstd) {
-  __shared__ double sh[32][2][8];
-  const int c = blockIdx.x * 8 + (threadIdx.x & 7), zl = threadIdx.x >> 3;
+__global__ __launch_bounds__(FIN_THREADS) void bn_stats_finalize_kernel(const T* __restrict__ x, const float* __restrict__ part,
+                                                                        int chunks, long long M, int C, float eps,
+                                                                        float* __restrict__ mean, float* __restrict__ invstd) {
+  __shared__ double sh[FIN_THREADS / 64][2][8];
+  const int c = blockIdx.x * 8 + (threadIdx.x & 7);
   double s1, s2;
-  sum_chunks<float>(part, chunks, C, c, zl, sh, s1, s2);
-  if (zl != 0 || c >= C) return;
+  sum_chunks<float>(part, chunks, C, c, sh, s1, s2);
+  if (threadIdx.x >= 8 || c >= C) return;
   double pivot = (double)to_f32<T>(x[c]);
   double ms = s1 / (double)M;
   double var = s2 / (double)M - ms * ms;
@@ -311,13 +322,13 @@ __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict_
   }
 }
 
-__global__ __launch_bounds__(256) void bn_vjp_finalize_kernel(const double* __restrict__ part, int chunks, int C,
-                                                              float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  __shared__ double sh[32][2][8];
-  const int c = blockIdx.x * 8 + (threadIdx.x & 7), zl = threadIdx.x >> 3;
+__global__ __launch_bounds__(FIN_THREADS) void bn_vjp_finalize_kernel(const double* __restrict__ part, int chunks, int C,
+                                                                      float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  __shared__ double sh[FIN_THREADS / 64][2][8];
+  const int c = blockIdx.x * 8 + (threadIdx.x & 7);
   double s1, s2;
-  sum_chunks<double>(part, chunks, C, c, zl, sh, s1, s2);
-  if (zl != 0 || c >= C) return;
+  sum_chunks<double>(part, chunks, C, c, sh, s1, s2);
+  if (threadIdx.x >= 8 || c >= C) return;
   dbeta[c] = (float)s1;
   dgamma[c] = (float)s2;
 }
@@ -412,9 +423,9 @@ int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* g
     BN_LAUNCH(bn_stats_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(float), (const T*)x, part, M, C, pr.cvb, pr.per);
     if ((rc = launch_status("bn_stats")) != S4TF_OK) return rc;
     if (d.dtype == S4TF_BF16)
-      hipLaunchKernelGGL((bn_stats_finalize_kernel<bf16_t>), dim3((C + 7) / 8), dim3(256), 0, st, (const bf16_t*)x, part, pr.chunks, M, C, d.eps, mean, invstd);
+      hipLaunchKernelGGL((bn_stats_finalize_kernel<bf16_t>), dim3((C + 7) / 8), dim3(FIN_THREADS), 0, st, (const bf16_t*)x, part, pr.chunks, M, C, d.eps, mean, invstd);
     else
-      hipLaunchKernelGGL((bn_stats_finalize_kernel<float>), dim3((C + 7) / 8), dim3(256), 0, st, (const float*)x, part, pr.chunks, M, C, d.eps, mean, invstd);
+      hipLaunchKernelGGL((bn_stats_finalize_kernel<float>), dim3((C + 7) / 8), dim3(FIN_THREADS), 0, st, (const float*)x, part, pr.chunks, M, C, d.eps, mean, invstd);
     if ((rc = launch_status("bn_stats_finalize")) != S4TF_OK) return rc;
   }
   ProfScope ps(PC_BN_APPLY, st);
@@ -427,7 +438,7 @@ int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gam
            void* ws, hipStream_t st) {
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
-  const Plan pr = make_plan((size_t)M, C, d.dtype, 1024, 16);
+  const Plan pr = make_plan((size_t)M, C, d.dtype, 1024, UNROLL);
   const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, UNROLL);
   double* part = static_cast<double*>(ws);
   int rc;
@@ -436,7 +447,7 @@ int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gam
     BN_LAUNCH(bn_vjp_reduce_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(double), (const T*)x, (const T*)y, (const T*)dy,
               mean, invstd, part, M, C, pr.cvb, pr.per, d.act);
     if ((rc = launch_status("bn_vjp_reduce")) != S4TF_OK) return rc;
-    hipLaunchKernelGGL(bn_vjp_finalize_kernel, dim3((C + 7) / 8), dim3(256), 0, st, part, pr.chunks, C, dgamma, dbeta);
+    hipLaunchKernelGGL(bn_vjp_finalize_kernel, dim3((C + 7) / 8), dim3(FIN_THREADS), 0, st, part, pr.chunks, C, dgamma, dbeta);
     if ((rc = launch_status("bn_vjp_finalize")) != S4TF_OK) return rc;
   }
   ProfScope ps(PC_BN_VJP_APPLY, st);

@@ -238,27 +238,31 @@ template <int ROWS> struct DgradB {
 };
 
 // ---- row-contiguous operands ---------------------------------------------------------------------
-// Stored [k][row] as they lie in memory, a k-row being CPR 16-byte chunks of 8 adjacent rows, except that
-// chunk c of k-row k sits at chunk position c ^ 2*(k & 3): a transpose read fetches, per group of 16
-// lanes, 32 bytes from each of four consecutive k-rows, and k-rows are a whole number of bank sweeps
-// apart, so unswizzled those four pieces would collide on the same 8 banks.
+// Stored [k][row] as they lie in memory, a k-row being CPR 16-byte chunks of 8 adjacent rows, except for
+// a swizzle of the chunk position.  LDS reads go through 64 banks of 4 bytes: a transpose read (8 bytes
+// per lane) is served 32 lanes = 256 bytes at a time, and those 32 lanes fetch 64 bytes (4 chunks) from
+// each of four consecutive k-rows.  k-rows lie a whole or half a 256-byte bank sweep apart, so left alone
+// the four pieces would fall on the same banks; chunk c of k-row k therefore sits at position
+// c ^ 4*s(k), where s(k) counts through the k-rows that share a bank window: k & 3 for 128-row tiles
+// (one k-row per sweep), (k >> 1) & 1 for 64-row tiles (two per sweep).
 // Wave w fills units u = w*UPW + i; a unit is KPU k-rows; lane l fills position l%CPR of k-row
 // u*KPU + l/CPR (KPU is a multiple of 4, so the swizzle depends on the lane only).
 template <int ROWS> struct RTile {
   static constexpr int UPW = ROWS / 32;
   static constexpr int CPR = ROWS / 8;   // chunks per k-row
   static constexpr int KPU = 64 / CPR;   // k-rows per 1 KiB unit
-  static_assert(KPU % 4 == 0 && CPR >= 8, "swizzle assumes whole groups of four k-rows per unit");
+  static_assert(ROWS == 64 || ROWS == 128, "swizzle is written for 64- and 128-row tiles");
+  __device__ static int swz(int k) { return ROWS == 128 ? ((k & 3) << 2) : (((k >> 1) & 1) << 2); }
   __device__ static int k_of(int wave, int i, int lane) { return (wave * UPW + i) * KPU + lane / CPR; }
   // the chunk of its k-row (8 adjacent rows of the tile) that a lane fetches
-  __device__ static int chunk_of(int lane) { return (lane % CPR) ^ (((lane / CPR) & 3) << 1); }
+  __device__ static int chunk_of(int lane) { return (lane % CPR) ^ swz(lane / CPR); }
   // byte address a lane hands to ds_read_b64_tr_b16 to receive, for its own row nf + (lane & 31), the
   // 4 k-values kb .. kb+3 (kb a multiple of 4): lanes 16g..16g+15 together read k-rows kb..kb+3 x rows
   // nf+16g .. nf+16g+15
   __device__ static int tr_off(int kb, int nf, int lane) {
     const int j = lane & 15, g = (lane >> 4) & 1;
     const int k = kb + (j >> 2), n = nf + 16 * g + 4 * (j & 3);
-    return k * ROWS * 2 + (((n >> 3) ^ ((k & 3) << 1)) << 4) + (n & 7) * 2;
+    return k * ROWS * 2 + (((n >> 3) ^ swz(k)) << 4) + (n & 7) * 2;
   }
 };
 
