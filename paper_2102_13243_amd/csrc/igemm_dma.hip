@@ -14,6 +14,8 @@
 //     transpose load of gfx950, which hands each lane 4 consecutive k for its own row.
 // The loads are buffer loads: padding (image borders, ragged tiles, stride holes in dgrad) is an
 // out-of-range offset, which the hardware turns into zeros, so every lane always loads.  MFMA: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+#include <utility>
+
 #include "s4tf_internal.h"
 #include "igemm_args.h"
 
@@ -93,6 +95,7 @@ template <int ROWS, bool DGRAD> struct Gather {
   typedef KTile<ROWS> TL;
   i32x4 rsrc;
   int loff[TL::UPW], kc[TL::UPW];
+  uint32_t toffv[TL::UPW];  // uniform-tap path: this lane's offset for the current tap, or OOB if the tap is padding
   uint64_t mask[TL::UPW];
   int r, s, tap, cb, kt, toff;  // uniform: tap (r,s), its offset, and the channel base of the next k-tile
   int CH, WI, taps, S, invS, logC;
@@ -160,23 +163,27 @@ template <int ROWS, bool DGRAD> struct Gather {
     s = tap % g.S;
     r = tap / g.S;
     toff = tap_off(r, s, g);
+    new_tap();
+  }
+  __device__ void new_tap() {
+    const bool in = tap < taps;
+#pragma unroll
+    for (int i = 0; i < TL::UPW; ++i)
+      toffv[i] = (in && ((mask[i] >> tap) & 1)) ? (uint32_t)(loff[i] + toff * 2) : OOB;
   }
   __device__ void issue(const Args& a, uint32_t tile, int wave) {
     const ConvGeom& g = a.g;
     if (uniform_tap) {
-      const int uni = (toff + cb) * 2;
-      const bool in = tap < taps;
+      const uint32_t uni = (uint32_t)(cb * 2);  // OOB + uni stays out of range
 #pragma unroll
-      for (int i = 0; i < TL::UPW; ++i) {
-        const bool ok = in && ((mask[i] >> tap) & 1);
-        dma16(ok ? (uint32_t)(loff[i] + uni) : OOB, rsrc, tile + (uint32_t)((wave * TL::UPW + i) * 1024));
-      }
+      for (int i = 0; i < TL::UPW; ++i) dma16(toffv[i] + uni, rsrc, tile + (uint32_t)((wave * TL::UPW + i) * 1024));
       cb += BK;
-      if (cb >= CH) {  // next tap: the only place that pays for its offset
+      if (cb >= CH) {  // next tap: the only place that pays for its offset and its padding test
         cb = 0;
         ++tap;
         if (++s == g.S) { s = 0; ++r; }
         toff = tap_off(r, s, g);
+        new_tap();
       }
     } else {
 #pragma unroll
@@ -344,20 +351,41 @@ template <int ROWS> struct Sel<PASS_DGRAD, ROWS, false> { typedef DgradB<ROWS> t
 template <int ROWS> struct Sel<PASS_WGRAD, ROWS, true> { typedef WgradA<ROWS> type; static constexpr bool KC = false; };
 template <int ROWS> struct Sel<PASS_WGRAD, ROWS, false> { typedef PlainR<ROWS> type; static constexpr bool KC = false; };
 
-// fragment of 32 rows x 16 k for the MFMA: 8 k-values per lane (k = 16*ks + 8*(lane>>5) + 0..7)
-template <bool KC, int ROWS> __device__ inline bf16x8 load_frag(const char* tile, int row0, int ks, int lane) {
-  if constexpr (KC) {
-    const int row = row0 + (lane & 31), kc = ks * 2 + (lane >> 5);
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + KTile<ROWS>::frag_off(row, kc)));
-  } else {
-    const int kb = ks * 16 + 8 * (lane >> 5);
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4*)(tile + RTile<ROWS>::tr_off(kb, row0, lane)));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4*)(tile + RTile<ROWS>::tr_off(kb + 4, row0, lane)));
-    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    return __builtin_bit_cast(bf16x8, v);
+// Fragments of 32 rows x 16 k for the MFMA: 8 k-values per lane (k = 16*ks + 8*(lane>>5) + 0..7).
+// Their LDS addresses are a per-lane part, computed once before the k-loop, plus a part that is known
+// at compile time (ring slot, k-step): the reads in the loop need no address arithmetic at all.
+template <bool KC, int ROWS> struct Frag {
+  // KC: the XOR swizzle does not commute with the k-step, so one base per k-step; else one base
+  static constexpr int NB = KC ? BK / 16 : 1;
+  uint32_t base[NB];
+  __device__ void init(uint32_t tile0, int row0, int lane) {
+    if constexpr (KC) {
+#pragma unroll
+      for (int ks = 0; ks < NB; ++ks)
+        base[ks] = tile0 + KTile<ROWS>::frag_off(row0 + (lane & 31), ks * 2 + (lane >> 5));
+    } else {
+      base[0] = tile0 + RTile<ROWS>::tr_off(8 * (lane >> 5), row0, lane);
+    }
   }
+  // slot_off: byte offset of the ring slot (and operand) inside the ring, a compile-time constant at the call
+  __device__ bf16x8 load(int slot_off, int ks) const {
+    if constexpr (KC) {
+      return __builtin_bit_cast(bf16x8, *(const __attribute__((address_space(3))) uint4*)(uintptr_t)(base[ks] + slot_off));
+    } else {
+      const uint32_t a = base[0] + slot_off + ks * 16 * ROWS * 2;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)a);
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)(a + 4 * ROWS * 2));
+      s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, v);
+    }
+  }
+};
+
+template <typename F, int... I> __device__ inline void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F> __device__ inline void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 // Staging patch of the bf16 epilogue: per wavefront 32 rows x (FN*32) columns of fp32, rows 4 banks apart
@@ -403,24 +431,46 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
   la.init(a, m0, wave, lane, kt0);
   lb.init(a, n0, wave, lane, kt0);
 
-  // one k-tile: four k-steps of 16; `between(ks)` runs after the MFMAs of step ks are issued, which
-  // is where the loop puts the address work and the issue of the next direct loads, so that they
-  // overlap the matrix pipeline instead of delaying the first LDS reads after the barrier
-  auto multiply = [&](const char* As, auto between) {
-    const char* Bs = As + A_BYTES;
+  Frag<SA::KC, BM> fa[FM];
+  Frag<SB::KC, BN> fb[FN];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[FM], bf[FN];
+  for (int i = 0; i < FM; ++i) fa[i].init(ring, arow + i * 32, lane);
 #pragma unroll
-      for (int i = 0; i < FM; ++i) af[i] = load_frag<SA::KC, BM>(As, arow + i * 32, ks, lane);
+  for (int j = 0; j < FN; ++j) fb[j].init(ring + A_BYTES, brow + j * 32, lane);
+
+  // one k-tile out of ring slot `slot` (a compile-time constant): four k-steps of 16; `between(ks)` runs
+  // after the MFMAs of step ks are issued, which is where the loop puts the issue of the next direct
+  // loads, so that their address work overlaps the matrix pipeline instead of delaying the first LDS
+  // reads after the barrier
+  auto multiply = [&](auto slot, auto between) {
+    constexpr int off = decltype(slot)::value * STAGE_BYTES;
+    constexpr int NKS = BK / 16;
+    // All fragment reads of the k-tile are issued first, in the order the MFMAs consume them: LDS
+    // returns data in order, so the first MFMA waits for one LDS latency and the rest of the reads
+    // stream in behind the running matrix pipeline (one exposed latency per k-tile instead of one
+    // per k-step).  The scheduling barrier keeps the compiler from re-interleaving the two phases.
+    // (The ring-less 128x128 variant runs four workgroups per CU on 128 registers: it reads per k-step.)
+    constexpr int AHEAD = (STAGES == 1 && FM * FN == 4) ? 1 : NKS;
+    bf16x8 af[NKS][FM], bf[NKS][FN];
 #pragma unroll
-      for (int j = 0; j < FN; ++j) bf[j] = load_frag<SB::KC, BN>(Bs, brow + j * 32, ks, lane);
+    for (int k0 = 0; k0 < NKS; k0 += AHEAD) {
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
+      for (int ks = k0; ks < k0 + AHEAD; ++ks) {
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-      between(ks);
+        for (int i = 0; i < FM; ++i) af[ks][i] = fa[i].load(off, ks);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) bf[ks][j] = fb[j].load(off, ks);
+      }
+      if (AHEAD == NKS) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = k0; ks < k0 + AHEAD; ++ks) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bf[ks][j], acc[i][j], 0, 0, 0);
+        between(ks);
+      }
     }
   };
 
@@ -431,7 +481,7 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
       lb.issue(a, ring + A_BYTES, wave);
       wait_vmcnt<0>();
       __syncthreads();
-      multiply(smem, [](int) {});
+      multiply(std::integral_constant<int, 0>{}, [](int) {});
     }
   } else {
     // prologue: k-tiles kt0 .. kt0+STAGES-2 (tiles past the end fetch zeros: the counts stay uniform)
@@ -440,16 +490,21 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
       la.issue(a, ring + s * STAGE_BYTES, wave);
       lb.issue(a, ring + s * STAGE_BYTES + A_BYTES, wave);
     }
-    int cur = 0, nxt = STAGES - 1;  // ring slots of k-tile kt and of k-tile kt+STAGES-1 (the one kt-1 used)
-    for (int kt = kt0; kt < kt1; ++kt) {
-      wait_vmcnt<(STAGES - 2) * LOADS>();  // this lane's direct loads of k-tile kt have landed
-      __syncthreads();                     // ... and everyone's; everyone is done reading tile kt-1
-      multiply(smem + cur * STAGE_BYTES, [&](int ks) {
-        if (ks == 0) la.issue(a, ring + nxt * STAGE_BYTES, wave);
-        if (ks == 1) lb.issue(a, ring + nxt * STAGE_BYTES + A_BYTES, wave);
+    // the loop body is written out once per ring slot, so that every LDS address in it is a register
+    // plus a constant
+    for (int kt = kt0; kt < kt1;) {
+      static_for<STAGES>([&](auto slot) {
+        if (kt < kt1) {
+          constexpr int nxt = (decltype(slot)::value + STAGES - 1) % STAGES;  // the slot k-tile kt-1 used
+          wait_vmcnt<(STAGES - 2) * LOADS>();  // this lane's direct loads of k-tile kt have landed
+          __syncthreads();                     // ... and everyone's; everyone is done reading tile kt-1
+          multiply(slot, [&](int ks) {
+            if (ks == 0) la.issue(a, ring + nxt * STAGE_BYTES, wave);
+            if (ks == 1) lb.issue(a, ring + nxt * STAGE_BYTES + A_BYTES, wave);
+          });
+          ++kt;
+        }
       });
-      cur = cur + 1 == STAGES ? 0 : cur + 1;
-      nxt = nxt + 1 == STAGES ? 0 : nxt + 1;
     }
   }
   if constexpr (PASS == PASS_FWD) {
