@@ -32,11 +32,8 @@ def conv_flops(net, shapes):
             out[pre + "wgrad" + suf] += f
             if op["in"] != 0:
                 out[pre + "dgrad" + suf] += f
-        elif op["kind"] == "head":   # its dense layer runs on the same kernels
-            f = 2.0 * n * c * op["classes"]
-            out["conv_fwd_igemm"] += f
-            out["conv_wgrad_igemm"] += f
-            out["conv_dgrad_igemm"] += f
+        elif op["kind"] == "head":   # the filter gradient of its dense layer runs on the conv kernel
+            out["conv_wgrad_igemm"] += 2.0 * n * c * op["classes"]
     return out
 
 
@@ -110,7 +107,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
         # a bounded sample of the same workload: same net and image size at a small batch, one step
-        sb = {"resnet50": 8, "mobilenetv2": 8, "resnet56": 64}.get(args.workload, batch)
+        sb = {"resnet50": 32, "mobilenetv2": 32, "resnet56": 64}.get(args.workload, batch)
         sb = min(sb, batch)
         snet = nets.CONFIGS[args.workload](batch=sb)
         swl = nets.make_workload(snet)
