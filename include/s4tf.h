@@ -239,7 +239,13 @@ int s4tf_net_tensor_layout(const s4tf_net_desc* net, int64_t* act_off, int64_t* 
 
 /* One training step: forward, loss, pullbacks in reverse op order (cotangents of a tensor
  * with several consumers are summed in reverse consumer order), then one SGD-momentum
- * update of the whole arena.  Enqueues on batch->stream; never synchronises. */
+ * update of the whole arena.  Enqueues on batch->stream; never synchronises the host.
+ * The parameter-gradient kernels of the convolutions run on a second stream that the
+ * library creates once per device (default priority, kept until the process ends); the
+ * step orders it after the work already queued on batch->stream and makes batch->stream
+ * wait for it before the update, also when the step fails half way, so in stream order on
+ * batch->stream the step is complete (and its workspace reusable) when its last kernel is.
+ * Steps on the same device share that second stream. */
 int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_batch* batch, float lr);
 
 /* ---- measurement hook -------------------------------------------------------------------
