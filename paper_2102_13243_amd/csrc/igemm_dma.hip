@@ -112,7 +112,7 @@ template <int ROWS, bool DGRAD> struct Gather {
     CH = DGRAD ? g.K : g.C;
     S = g.S;
     taps = g.R * g.S;
-    invS = (65536 + g.S - 1) / g.S;
+    invS = g.S == 1 ? 65536 : g.S == 3 ? 21846 : (65536 + g.S - 1) / g.S;
     uniform_tap = (CH % BK) == 0;
     logC = log2_of(CH);
 #pragma unroll
@@ -157,11 +157,15 @@ template <int ROWS, bool DGRAD> struct Gather {
       mask[i] = m;
     }
     kt = kt0;
-    const int kk = kt0 * BK;
-    cb = kk % CH;
-    tap = kk / CH;
-    s = tap % g.S;
-    r = tap / g.S;
+    if (kt0 == 0) {  // forward and dgrad launches: no division
+      cb = 0; tap = 0; s = 0; r = 0;
+    } else {
+      const int kk = kt0 * BK;
+      cb = kk % CH;
+      tap = kk / CH;
+      s = tap % g.S;
+      r = tap / g.S;
+    }
     toff = tap_off(r, s, g);
     new_tap();
   }
@@ -220,9 +224,13 @@ template <int ROWS> struct DgradB {
       loff[i] = crow[i] < a.Ng ? (uint32_t)((crow[i] * g.K + (uniform_tap ? kc[i] * 8 : 0)) * 2) : OOB;
     }
     kt = kt0;
-    const int kk = kt0 * BK;
-    kob = kk % g.K;
-    rs = kk / g.K;
+    if (kt0 == 0) {
+      kob = 0; rs = 0;
+    } else {
+      const int kk = kt0 * BK;
+      kob = kk % g.K;
+      rs = kk / g.K;
+    }
   }
   __device__ void issue(const Args& a, uint32_t tile, int wave) {
     const ConvGeom& g = a.g;
@@ -381,6 +389,14 @@ template <bool KC, int ROWS> struct Frag {
   }
 };
 
+// the value that lane ^ 32 holds
+__device__ inline float other_half(float v) {
+  typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const u32x2 sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);  // [lo, lo], [hi, hi]
+  return __builtin_bit_cast(float, (threadIdx.x & 32) ? sw[0] : sw[1]);
+}
+
 template <typename F, int... I> __device__ inline void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
   (f(std::integral_constant<int, I>{}), ...);
 }
@@ -515,30 +531,28 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
       const int rbase = m0 + arow;
       const int cnt = min(max(a.Mg - rbase, 0), FM * 32);
       float* part = a.stats + (long long)(rbase / (FM * 32)) * 2 * a.Ng;
+      const bool full = rbase + FM * 32 <= a.Mg;  // every row of the run exists
+      const float inv_cnt = cnt > 0 ? 1.f / (float)cnt : 0.f;
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
-        float r[FM][16];
-        float s1 = 0.f;
+        // One pass: sum and sum of squares of the rounded values, four independent chains each, then the
+        // other half of the column from lane ^ 32.  A run is at most 64 values, so taking the squared
+        // deviations as sum(r^2) - sum(r)^2/n in fp32 loses about 1e-7 * (1 + mean^2/variance) of them.
+        float s4[4] = {0.f, 0.f, 0.f, 0.f}, q4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            const int row = rbase + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-            r[i][v] = row < a.Mg ? bf16_to_f32(f32_to_bf16(acc[i][j][v])) : 0.f;
-            s1 += r[i][v];
+            float rv = bf16_to_f32(f32_to_bf16(acc[i][j][v]));
+            if (!full) rv = (rbase + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4) < a.Mg) ? rv : 0.f;
+            s4[v % 4] += rv;
+            q4[v % 4] = fmaf(rv, rv, q4[v % 4]);
           }
-        s1 += __shfl_xor(s1, 32, 64);
-        const float mean = cnt > 0 ? s1 / (float)cnt : 0.f;
-        float m2 = 0.f;
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = rbase + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-            const float dlt = r[i][v] - mean;
-            if (row < a.Mg) m2 += dlt * dlt;
-          }
-        m2 += __shfl_xor(m2, 32, 64);
+        float s1 = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+        float q1 = (q4[0] + q4[1]) + (q4[2] + q4[3]);
+        s1 += other_half(s1);
+        q1 += other_half(q1);
+        const float m2 = fmaxf(q1 - s1 * s1 * inv_cnt, 0.f);
         const int col = n0 + brow + j * 32 + (lane & 31);
         if (lane < 32 && col < a.Ng && cnt > 0) {  // a run with no valid row has no slot
           part[col] = s1;
@@ -562,6 +576,10 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
     constexpr int CPRO = WCOLS / 8;  // 16-byte output chunks per patch row
     constexpr int ITERS = 32 * CPRO / 64;
     const bool scatter = PASS == PASS_DGRAD && a.scatter2;
+    // forward only: the activation as a clamp (relu: [0, inf), relu6: [0, 6], none: everything)
+    const bool plain_out = PASS != PASS_FWD || (a.bias == nullptr && a.act == S4TF_ACT_NONE);
+    const float act_lo = (PASS == PASS_FWD && a.act != S4TF_ACT_NONE) ? 0.f : -__builtin_inff();
+    const float act_hi = (PASS == PASS_FWD && a.act == S4TF_ACT_RELU6) ? 6.f : __builtin_inff();
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
       // where this lane's chunks go (-1: outside the matrix); a 1x1 / stride-2 dgrad runs over the
@@ -602,14 +620,17 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
           float v8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
           bf16_t* dst = out + dsto[it];
           if constexpr (PASS == PASS_FWD) {
-            if (a.bias) {
-              const float4 b0 = *reinterpret_cast<const float4*>(a.bias + col);
-              const float4 b1 = *reinterpret_cast<const float4*>(a.bias + col + 4);
-              v8[0] += b0.x; v8[1] += b0.y; v8[2] += b0.z; v8[3] += b0.w;
-              v8[4] += b1.x; v8[5] += b1.y; v8[6] += b1.z; v8[7] += b1.w;
-            }
+            if (!plain_out) {  // bias and activation: one uniform branch per chunk, none per element
+              float b8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+              if (a.bias) {
+                const float4 b0 = *reinterpret_cast<const float4*>(a.bias + col);
+                const float4 b1 = *reinterpret_cast<const float4*>(a.bias + col + 4);
+                b8[0] = b0.x; b8[1] = b0.y; b8[2] = b0.z; b8[3] = b0.w;
+                b8[4] = b1.x; b8[5] = b1.y; b8[6] = b1.z; b8[7] = b1.w;
+              }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v8[e] = act_apply(v8[e], a.act);
+              for (int e = 0; e < 8; ++e) v8[e] = fminf(fmaxf(v8[e] + b8[e], act_lo), act_hi);
+            }
           }
           if (PASS == PASS_DGRAD && a.accumulate) {
 #pragma unroll
