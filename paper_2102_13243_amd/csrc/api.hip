@@ -167,6 +167,7 @@ static int conv_vjp_impl(const s4tf_conv_desc& d, const void* x, const void* w, 
 struct SideStream {
   hipStream_t stream = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
+  hipEvent_t back[8] = {};  // side -> main dependencies inside a step (side branches), used round-robin
 };
 static std::mutex g_side_mutex;
 static SideStream g_side[64];
@@ -182,6 +183,9 @@ static int side_stream(SideStream** out) {
         hipEventCreateWithFlags(&e0, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&e1, hipEventDisableTiming) != hipSuccess)
       return fail(S4TF_ERR_DEVICE, "cannot create the second stream of the train step: %s", hipGetErrorString(hipGetLastError()));
+    for (int k = 0; k < 8; ++k)
+      if (hipEventCreateWithFlags(&s.back[k], hipEventDisableTiming) != hipSuccess)
+        return fail(S4TF_ERR_DEVICE, "cannot create the events of the train step: %s", hipGetErrorString(hipGetLastError()));
     s.stream = st; s.fork = e0; s.join = e1;
   }
   *out = &s;
@@ -208,6 +212,14 @@ struct NetPlan {
   size_t param_count;
   size_t scratch_off, scratch_bytes, total_bytes;
   size_t wscratch_off, wscratch_bytes;  // scratch of the filter-gradient kernels, which run on a stream of their own
+  // Side branches: a convolution + BatchNorm pair whose only use is as the residual input of a later
+  // BatchNorm (the projection shortcut of a residual block), while other ops lie between the pair and
+  // the op that made its input.  Forward, the pair runs on the second stream as soon as its input
+  // exists, beside the main branch; its pullback runs there too.  branch_of[op]: the pair's number or
+  // -1; start_after[op]: the pair to start once op is queued; needs[op]: the pair whose output op reads.
+  std::vector<int> branch_of, start_after, needs;
+  std::vector<int> branch_conv;         // per pair: its convolution's op index
+  size_t sscratch_off;                  // scratch of the side branches (as large as the main scratch)
 };
 
 static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
@@ -344,7 +356,30 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
   pl.scratch_bytes = align_up(scratch, 256);
   pl.wscratch_off = pl.scratch_off + pl.scratch_bytes;
   pl.wscratch_bytes = align_up(wscratch, 256);
-  pl.total_bytes = pl.wscratch_off + pl.wscratch_bytes;
+  pl.sscratch_off = pl.wscratch_off + pl.wscratch_bytes;
+  pl.total_bytes = pl.sscratch_off + pl.scratch_bytes;
+  // side branches
+  pl.branch_of.assign(nops, -1);
+  pl.start_after.assign(nops, -1);
+  pl.needs.assign(nops, -1);
+  pl.branch_conv.clear();
+  for (int j = 0; j + 2 < nops; ++j) {
+    const s4tf_op& cv = net->ops[j];
+    const s4tf_op& bn = net->ops[j + 1];
+    if (cv.kind != S4TF_OP_CONV || cv.groups != 1 || pl.pad_c[j] || bn.kind != S4TF_OP_BN || bn.in != j + 1 || bn.res >= 0) continue;
+    const int X = cv.in;
+    if (X <= 0 || pl.t[X].root != X || X >= j) continue;             // its input: a tensor of its own, made at least one op earlier
+    if (pl.t[j + 2].consumers != 1) continue;
+    int user = -1;
+    for (int r = j + 2; r < nops; ++r)
+      if (net->ops[r].kind == S4TF_OP_BN && net->ops[r].res == j + 2) { user = r; break; }
+    if (user < 0 || pl.start_after[X - 1] >= 0 || pl.needs[user] >= 0) continue;
+    const int id = (int)pl.branch_conv.size();
+    pl.branch_conv.push_back(j);
+    pl.branch_of[j] = pl.branch_of[j + 1] = id;
+    pl.start_after[X - 1] = id;
+    pl.needs[user] = id;
+  }
   pl.param_count = pcount;
   return S4TF_OK;
 }
@@ -566,8 +601,24 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   };
 
   // ---- forward ----
-  int stats_rows = 0;  // > 0: the previous op, a convolution, left partial statistics of its output in scratch
-  for (int i = 0; i < nops - 1; ++i) {
+  void* sscratch = ws + pl.sscratch_off;
+  // side -> main dependencies: the event a side branch's output (forward) or a tensor's cotangent
+  // (backward) is ready at; `st` waits for it where it first touches that data
+  int back_next = 0;
+  std::vector<int> branch_event(pl.branch_conv.size(), -1);
+  auto side_done = [&](int& slot) -> int {  // marks what the side stream has been given so far
+    slot = back_next++ % 8;
+    if (hipEventRecord(side->back[slot], side->stream) != hipSuccess) return fail(S4TF_ERR_DEVICE, "train step: event record failed");
+    return S4TF_OK;
+  };
+  auto wait_side = [&](int& slot) -> int {
+    if (slot < 0) return S4TF_OK;
+    if (hipStreamWaitEvent(st, side->back[slot], 0) != hipSuccess) return fail(S4TF_ERR_DEVICE, "train step: event wait failed");
+    slot = -1;
+    return S4TF_OK;
+  };
+  // one forward op on stream s with scratch scr; stats_rows: in, what the op before left in scr; out, what this one leaves
+  auto fwd_op = [&](int i, hipStream_t s, void* scr, int& stats_rows) -> int {
     const s4tf_op& op = net->ops[i];
     const TensorPlan& in = pl.t[op.in];
     const int prev_stats_rows = stats_rows;
@@ -577,34 +628,52 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         s4tf_conv_desc d = conv_desc(i, 0);
         const float* bias = op.has_bias ? params->master + pl.poff[2 * i + 1] : nullptr;
         const bool bn_next = net->ops[i + 1].kind == S4TF_OP_BN && net->ops[i + 1].in == i + 1 && op.groups == 1;
-        float* sp = bn_next ? static_cast<float*>(scratch) : nullptr;
+        float* sp = bn_next ? static_cast<float*>(scr) : nullptr;
         int* sr = bn_next ? &stats_rows : nullptr;
         if (pl.pad_c[i]) {  // zero-padded channels contribute nothing: same result, 16-byte loaders
-          CHECK(pad_channels(dt, act_ptr(op.in), ws + pl.xpad_off[i], (long long)in.n * in.h * in.w, in.c, pl.pad_c[i], 1, st));
-          CHECK(pad_channels(dt, conv_w(i), ws + pl.wpad_off[i], (long long)op.r * op.s, in.c, pl.pad_c[i], op.k, st));
+          CHECK(pad_channels(dt, act_ptr(op.in), ws + pl.xpad_off[i], (long long)in.n * in.h * in.w, in.c, pl.pad_c[i], 1, s));
+          CHECK(pad_channels(dt, conv_w(i), ws + pl.wpad_off[i], (long long)op.r * op.s, in.c, pl.pad_c[i], op.k, s));
           d.c = pl.pad_c[i];
-          CHECK(conv_fwd_impl(d, ws + pl.xpad_off[i], ws + pl.wpad_off[i], bias, out_ptr(i + 1), st, sp, sr));
+          CHECK(conv_fwd_impl(d, ws + pl.xpad_off[i], ws + pl.wpad_off[i], bias, out_ptr(i + 1), s, sp, sr));
           break;
         }
-        CHECK(conv_fwd_impl(d, act_ptr(op.in), conv_w(i), bias, out_ptr(i + 1), st, sp, sr));
+        CHECK(conv_fwd_impl(d, act_ptr(op.in), conv_w(i), bias, out_ptr(i + 1), s, sp, sr));
         break;
       }
       case S4TF_OP_BN: {
         s4tf_bn_desc d = {in.n, in.h, in.w, in.c, op.eps, op.act, dt, 0};
         float* stats = reinterpret_cast<float*>(ws + pl.stat_off[i]);
         CHECK(bn_fwd(d, act_ptr(op.in), op.res >= 0 ? act_ptr(op.res) : nullptr, params->master + pl.poff[2 * i],
-                     params->master + pl.poff[2 * i + 1], out_ptr(i + 1), stats, stats + in.c, scratch, st,
-                     prev_stats_rows > 0 ? static_cast<const float*>(scratch) : nullptr, prev_stats_rows));
+                     params->master + pl.poff[2 * i + 1], out_ptr(i + 1), stats, stats + in.c, scr, s,
+                     prev_stats_rows > 0 ? static_cast<const float*>(scr) : nullptr, prev_stats_rows));
         break;
       }
       case S4TF_OP_AVGPOOL2:
       case S4TF_OP_MAXPOOL3S2: {
         s4tf_pool_desc d = {in.n, in.h, in.w, in.c, op.kind == S4TF_OP_AVGPOOL2 ? S4TF_POOL_AVG2 : S4TF_POOL_MAX3S2, dt, 0};
-        CHECK(pool_fwd(d, act_ptr(op.in), out_ptr(i + 1), st));
+        CHECK(pool_fwd(d, act_ptr(op.in), out_ptr(i + 1), s));
         break;
       }
       default:
         break;  // flatten: a reinterpretation
+    }
+    return S4TF_OK;
+  };
+  int stats_rows = 0;  // > 0: the previous op, a convolution, left partial statistics of its output in scratch
+  for (int i = 0; i < nops - 1; ++i) {
+    if (pl.branch_of[i] >= 0) {  // ran on the side stream when its input appeared
+      stats_rows = 0;
+      continue;
+    }
+    if (pl.needs[i] >= 0) CHECK(wait_side(branch_event[pl.needs[i]]));
+    CHECK(fwd_op(i, st, scratch, stats_rows));
+    if (pl.start_after[i] >= 0) {  // the input of a side branch is queued: the branch starts beside what follows
+      const int b = pl.start_after[i], j = pl.branch_conv[b];
+      CHECK(fork());
+      int sr = 0;
+      CHECK(fwd_op(j, side->stream, sscratch, sr));
+      CHECK(fwd_op(j + 1, side->stream, sscratch, sr));
+      CHECK(side_done(branch_event[b]));
     }
   }
   auto resolve = [&](int t) -> int { return pl.t[t].root; };
@@ -624,19 +693,43 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
     written[src] = 1;
   }
   // ---- pullbacks in reverse op order ----
+  // Ops of a side branch run on the side stream (after the op that feeds them their cotangent, which
+  // the fork orders); a cotangent they write is waited for where the main stream first touches it.
+  std::vector<int> grad_event(nops + 1, -1);   // per tensor: pending side-stream write of its cotangent
+  std::vector<char> branch_forked(pl.branch_conv.size(), 0);
   for (int i = nops - 2; i >= 0; --i) {
     const s4tf_op& op = net->ops[i];
     const TensorPlan& in = pl.t[op.in];
     const int src = resolve(op.in);
     const bool want_dx = src != 0;
     void* dy = grad_ptr(i + 1);
+    const int br = pl.branch_of[i];
+    const bool on_side = br >= 0;
+    hipStream_t s = on_side ? side->stream : st;
+    void* scr = on_side ? sscratch : scratch;
+    if (on_side) {
+      if (!branch_forked[br]) {  // everything queued on `st` so far (its cotangent's producer included) comes first
+        CHECK(fork());
+        branch_forked[br] = 1;
+      }
+    } else {
+      CHECK(wait_side(grad_event[resolve(i + 1)]));
+      if (want_dx) CHECK(wait_side(grad_event[src]));
+    }
     switch (op.kind) {
       case S4TF_OP_CONV: {
         s4tf_conv_desc d = conv_desc(i, written[src] ? 1 : 0);
         if (op.act != S4TF_ACT_NONE)  // in place: dy is not needed once dz exists
-          CHECK(act_vjp(dt, op.act, out_ptr(i + 1), dy, dy, pl.t[i + 1].elems, st));
-        // dz is final: the parameter gradients go to the side stream, the input cotangent stays here
-        CHECK(fork());
+          CHECK(act_vjp(dt, op.act, out_ptr(i + 1), dy, dy, pl.t[i + 1].elems, s));
+        // dz is final.  The input cotangent is computed first; the parameter gradients go to the side
+        // stream and start when it is done, so that they run beside the bandwidth-bound BatchNorm pullback
+        // of the layer before rather than beside this layer's other matrix kernel (measured: 2 % of the step).
+        if (want_dx && !pl.pad_c[i]) {
+          CHECK(conv_dgrad_impl(d, conv_w(i), dy, grad_ptr(src), s));
+          written[src] = 1;
+          if (on_side) CHECK(side_done(grad_event[src]));
+        }
+        if (!on_side) CHECK(fork());
         float* dbias = op.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr;
         if (pl.pad_c[i]) {  // the batch has no cotangent; the filter gradient of the padded channels is dropped
           d.c = pl.pad_c[i];
@@ -647,20 +740,17 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         }
         CHECK(conv_param_grads_impl(d, act_ptr(src), dy, params->grad + pl.poff[2 * i], dbias, wscratch, pl.wscratch_bytes,
                                     side->stream));
-        if (want_dx) {
-          CHECK(conv_dgrad_impl(d, conv_w(i), dy, grad_ptr(src), st));
-          written[src] = 1;
-        }
         break;
       }
       case S4TF_OP_BN: {
         const int rsrc = op.res >= 0 ? resolve(op.res) : -1;
+        if (!on_side && rsrc > 0) CHECK(wait_side(grad_event[rsrc]));
         s4tf_bn_desc d = {in.n, in.h, in.w, in.c, op.eps, op.act, dt, (rsrc > 0 && written[rsrc]) ? 1 : 0};
         float* stats = reinterpret_cast<float*>(ws + pl.stat_off[i]);
         void* dxb = grad_ptr(src);  // src != 0: checked when the net was planned
         void* dres = rsrc > 0 ? grad_ptr(rsrc) : nullptr;
         CHECK(bn_vjp(d, act_ptr(src), out_ptr(i + 1), params->master + pl.poff[2 * i], stats, stats + in.c, dy, dxb,
-                     dres, params->grad + pl.poff[2 * i], params->grad + pl.poff[2 * i + 1], scratch, st));
+                     dres, params->grad + pl.poff[2 * i], params->grad + pl.poff[2 * i + 1], scr, s));
         written[src] = 1;
         if (rsrc > 0) written[rsrc] = 1;
         break;
@@ -670,7 +760,7 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         if (!want_dx) break;
         s4tf_pool_desc d = {in.n, in.h, in.w, in.c, op.kind == S4TF_OP_AVGPOOL2 ? S4TF_POOL_AVG2 : S4TF_POOL_MAX3S2, dt,
                             written[src] ? 1 : 0};
-        CHECK(pool_vjp(d, act_ptr(src), dy, grad_ptr(src), st));
+        CHECK(pool_vjp(d, act_ptr(src), dy, grad_ptr(src), s));
         written[src] = 1;
         break;
       }
