@@ -753,6 +753,31 @@ int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, voi
     fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
     return igemm_dma_launch(PASS_DGRAD, a, 1, st);
   }
+  if (dtype == S4TF_BF16 && g.stride == 2 && g.R >= 2 && g.S >= 2 && g.K % 64 == 0 && g.H >= 2 && g.W >= 2 &&
+      igemm_dma_ok(PASS_DGRAD, g, a)) {
+    // An input pixel meets only the taps whose parity matches its own: r = (h + pad) mod 2 (+2, +4, ...),
+    // s likewise.  One GEMM per parity class over its pixels and its taps does a quarter of the work of
+    // one GEMM over all pixels and all taps, three quarters of which would multiply zeros.
+    a.cls = 1;
+    int nk_max = 0;
+    for (int p = 0; p < 2; ++p) {
+      a.cls_r0[p] = a.cls_s0[p] = (p + g.pad) % 2;
+      a.cls_Hc[p] = (g.H - p + 1) / 2;
+      a.cls_Wc[p] = (g.W - p + 1) / 2;
+      magic_div(a.cls_Hc[p], a.cls_magicHc[p], a.cls_shiftHc[p]);
+      magic_div(a.cls_Wc[p], a.cls_magicWc[p], a.cls_shiftWc[p]);
+    }
+    for (int c = 0; c < 4; ++c) {  // slot c: class 3 - c, so that the class with the most taps is dispatched first
+      const int ph = (3 - c) >> 1, pw = (3 - c) & 1;
+      const int nr = (g.R - a.cls_r0[ph] + 1) / 2, ns = (g.S - a.cls_s0[pw] + 1) / 2;
+      a.cls_Mg[c] = g.N * a.cls_Hc[ph] * a.cls_Wc[pw];
+      a.cls_nk[c] = nr * ns * g.K / Cfg<bf16_t>::BK;
+      if (a.cls_nk[c] > nk_max) nk_max = a.cls_nk[c];
+    }
+    fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
+    a.nk = a.nk_per_split = nk_max;  // picks the kernel variant; every workgroup takes its class's count
+    return igemm_dma_launch(PASS_DGRAD, a, 1, st);
+  }
   if (dtype == S4TF_BF16) {
     fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
     return launch<bf16_t, PASS_DGRAD>(a, 1, st);

@@ -19,6 +19,17 @@ struct Args {
   int Mg, Ng, Kg;
   int act, accumulate, simple;
   int scatter2;                     // dgrad of a 1x1 / stride 2 / no padding layer run over the pixels of dy
+  // dgrad of a strided layer with a filter wider than its stride, one launch per parity class (ph, pw):
+  // rows are the input pixels (stride*hc + ph, stride*wc + pw), 0 <= hc < Hc, 0 <= wc < Wc, and k runs over
+  // the taps r = r0, r0 + stride, ..., s = s0, s0 + stride, ... only (the others never meet such a pixel)
+  int cls, ph, pw, r0, s0, Hc, Wc;
+  uint32_t magicWc, magicHc;
+  int shiftWc, shiftHc;
+  // the classes of one launch: slot c holds class 2*ph + pw = 3 - c and takes the workgroups cls_end[c-1] .. cls_end[c]-1; the
+  // kernel copies its class's entries into the fields above (and into Mg, nk, tiles_m)
+  int cls_end[4], cls_Mg[4], cls_nk[4], cls_tiles_m[4];
+  int cls_r0[2], cls_s0[2], cls_Hc[2], cls_Wc[2], cls_shiftHc[2], cls_shiftWc[2];
+  uint32_t cls_magicHc[2], cls_magicWc[2];
   int nk, nk_per_split, splits;
   long long split_stride;
   int tiles_m, tiles_n;
@@ -36,8 +47,8 @@ struct Args {
 // slice of both operands.  With at least as many splits as XCDs, whole splits are dealt round-robin
 // instead (all tiles of a split on one XCD).  Either way every XCD gets work even when there are fewer
 // tiles than XCDs.  False: this workgroup has nothing to do.
-__device__ inline bool block_to_tile(const Args& a, int& logical, int& split) {
-  const int x = blockIdx.x % NUM_XCD, j = blockIdx.x / NUM_XCD;
+__device__ inline bool block_to_tile(const Args& a, int bid, int& logical, int& split) {
+  const int x = bid % NUM_XCD, j = bid / NUM_XCD;
   const int tiles = a.tiles_m * a.tiles_n;
   if (a.splits >= NUM_XCD) {
     split = (j / tiles) * NUM_XCD + x;
@@ -49,6 +60,9 @@ __device__ inline bool block_to_tile(const Args& a, int& logical, int& split) {
   split = u / tiles;
   logical = u - split * tiles;
   return j < per_xcd && u < units;
+}
+__device__ inline bool block_to_tile(const Args& a, int& logical, int& split) {
+  return block_to_tile(a, (int)blockIdx.x, logical, split);
 }
 inline unsigned grid_blocks(const Args& a) {
   const int tiles = a.tiles_m * a.tiles_n;

@@ -98,6 +98,7 @@ template <int ROWS, bool DGRAD> struct Gather {
   uint32_t toffv[TL::UPW];  // uniform-tap path: this lane's offset for the current tap, or OOB if the tap is padding
   uint64_t mask[TL::UPW];
   int r, s, tap, cb, kt, toff;  // uniform: tap (r,s), its offset, and the channel base of the next k-tile
+  int s0, tstep;                // taps visited: r = r0, r0 + tstep, ..., s likewise (all of them unless a parity class runs)
   int CH, WI, taps, S, invS, logC;
   bool uniform_tap;
   // x / stride for x >= 0
@@ -137,8 +138,18 @@ template <int ROWS, bool DGRAD> struct Gather {
           for (int rr = rlo; rr < rhi; ++rr) m |= cols << (rr * g.S);
         }
       } else {
-        const int t = fast_div(row, a.magicW, a.shiftW), w = row - t * g.W;
-        const int n = fast_div(t, a.magicH, a.shiftH), h = t - n * g.H;
+        int n, h, w;
+        if (a.cls) {  // rows run over the pixels (stride*hc + ph, stride*wc + pw) only
+          const int t = fast_div(row, a.magicWc, a.shiftWc), wc = row - t * a.Wc;
+          n = fast_div(t, a.magicHc, a.shiftHc);
+          h = g.stride * (t - n * a.Hc) + a.ph;
+          w = g.stride * wc + a.pw;
+        } else {
+          const int t = fast_div(row, a.magicW, a.shiftW);
+          w = row - t * g.W;
+          n = fast_div(t, a.magicH, a.shiftH);
+          h = t - n * g.H;
+        }
         const int hp0 = h + g.pad, wp0 = w + g.pad;
         loff[i] = (((n * g.P + sdiv(hp0, g.stride)) * g.Q + sdiv(wp0, g.stride)) * g.K + kco) * 2;
         // tap (rr, ss) reads dy at ((hp0 - rr)/stride, (wp0 - ss)/stride) when both divide exactly and
@@ -157,7 +168,13 @@ template <int ROWS, bool DGRAD> struct Gather {
       mask[i] = m;
     }
     kt = kt0;
-    if (kt0 == 0) {  // forward and dgrad launches: no division
+    s0 = 0;
+    tstep = 1;
+    if (DGRAD && a.cls) {
+      s0 = a.s0;
+      tstep = g.stride;
+      cb = 0; r = a.r0; s = a.s0; tap = r * g.S + s;
+    } else if (kt0 == 0) {  // forward and dgrad launches: no division
       cb = 0; tap = 0; s = 0; r = 0;
     } else {
       const int kk = kt0 * BK;
@@ -184,8 +201,9 @@ template <int ROWS, bool DGRAD> struct Gather {
       cb += BK;
       if (cb >= CH) {  // next tap: the only place that pays for its offset and its padding test
         cb = 0;
-        ++tap;
-        if (++s == g.S) { s = 0; ++r; }
+        s += tstep;
+        if (s >= g.S) { s = s0; r += tstep; }
+        tap = r * g.S + s;
         toff = tap_off(r, s, g);
         new_tap();
       }
@@ -211,6 +229,7 @@ template <int ROWS> struct DgradB {
   uint32_t loff[TL::UPW];
   int kc[TL::UPW], crow[TL::UPW];
   int rs, kob, kt, logK;
+  int r, s, s0, tstep;  // the tap behind rs = r*S + s and how it advances (see Gather)
   bool uniform_tap;
   __device__ void init(const Args& a, int row0, int wave, int lane, int kt0) {
     const ConvGeom& g = a.g;
@@ -224,13 +243,22 @@ template <int ROWS> struct DgradB {
       loff[i] = crow[i] < a.Ng ? (uint32_t)((crow[i] * g.K + (uniform_tap ? kc[i] * 8 : 0)) * 2) : OOB;
     }
     kt = kt0;
-    if (kt0 == 0) {
-      kob = 0; rs = 0;
+    s0 = 0;
+    tstep = 1;
+    if (a.cls) {
+      s0 = a.s0;
+      tstep = g.stride;
+      kob = 0; r = a.r0; s = a.s0;
+    } else if (kt0 == 0) {
+      kob = 0; r = 0; s = 0;
     } else {
       const int kk = kt0 * BK;
       kob = kk % g.K;
-      rs = kk / g.K;
+      const int t = kk / g.K;
+      r = t / g.S;
+      s = t - r * g.S;
     }
+    rs = r * g.S + s;
   }
   __device__ void issue(const Args& a, uint32_t tile, int wave) {
     const ConvGeom& g = a.g;
@@ -239,7 +267,12 @@ template <int ROWS> struct DgradB {
 #pragma unroll
       for (int i = 0; i < TL::UPW; ++i) dma16(loff[i] + uni, rsrc, tile + (wave * TL::UPW + i) * 1024);
       kob += BK;
-      if (kob >= g.K) { kob = 0; ++rs; }
+      if (kob >= g.K) {
+        kob = 0;
+        s += tstep;
+        if (s >= g.S) { s = s0; r += tstep; }
+        rs = r * g.S + s;
+      }
     } else {
 #pragma unroll
       for (int i = 0; i < TL::UPW; ++i) {
@@ -414,7 +447,7 @@ template <int FN> struct Patch {
 // phases interleave: the better trade for GEMMs with only one or two k-tiles, where a ring has
 // nothing to overlap and the run time is load latency plus epilogue.
 template <int PASS, int STAGES, int WM, int WN, int FM, int FN>
-__global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void igemm_dma_kernel(const Args a) {
+__global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void igemm_dma_kernel(const Args a0) {
   static_assert(WM * WN == 4, "four wavefronts");
   constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
   constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE_BYTES = A_BYTES + B_BYTES;
@@ -427,8 +460,30 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t ring = lds_addr(smem);
+  Args a = a0;
+  int bid = blockIdx.x;
+  if constexpr (PASS == PASS_DGRAD) {
+    if (a.cls) {  // one launch over the four parity classes: which one this workgroup belongs to
+      const int c = (bid >= a.cls_end[0]) + (bid >= a.cls_end[1]) + (bid >= a.cls_end[2]);
+      bid -= c == 0 ? 0 : c == 1 ? a.cls_end[0] : c == 2 ? a.cls_end[1] : a.cls_end[2];
+      a.ph = (3 - c) >> 1;  // slot c holds class 3 - c: the classes with the most taps start first
+      a.pw = (3 - c) & 1;
+      a.r0 = a.ph ? a.cls_r0[1] : a.cls_r0[0];
+      a.s0 = a.pw ? a.cls_s0[1] : a.cls_s0[0];
+      a.Hc = a.ph ? a.cls_Hc[1] : a.cls_Hc[0];
+      a.Wc = a.pw ? a.cls_Wc[1] : a.cls_Wc[0];
+      a.magicHc = a.ph ? a.cls_magicHc[1] : a.cls_magicHc[0];
+      a.shiftHc = a.ph ? a.cls_shiftHc[1] : a.cls_shiftHc[0];
+      a.magicWc = a.pw ? a.cls_magicWc[1] : a.cls_magicWc[0];
+      a.shiftWc = a.pw ? a.cls_shiftWc[1] : a.cls_shiftWc[0];
+      a.Mg = c == 0 ? a.cls_Mg[0] : c == 1 ? a.cls_Mg[1] : c == 2 ? a.cls_Mg[2] : a.cls_Mg[3];
+      a.nk = c == 0 ? a.cls_nk[0] : c == 1 ? a.cls_nk[1] : c == 2 ? a.cls_nk[2] : a.cls_nk[3];
+      a.nk_per_split = a.nk;
+      a.tiles_m = c == 0 ? a.cls_tiles_m[0] : c == 1 ? a.cls_tiles_m[1] : c == 2 ? a.cls_tiles_m[2] : a.cls_tiles_m[3];
+    }
+  }
   int logical, split;
-  if (!block_to_tile(a, logical, split)) return;
+  if (!block_to_tile(a, bid, logical, split)) return;
   const int m0 = (logical / a.tiles_n) * BM, n0 = (logical % a.tiles_n) * BN;
   const int kt0 = split * a.nk_per_split;
   const int kt1 = min(a.nk, kt0 + a.nk_per_split);
@@ -594,7 +649,11 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
         dsto[it] = -1;
         if (row < a.Mg && col < a.Ng) {
           long long orow = row;
-          if (scatter) {
+          if (PASS == PASS_DGRAD && a.cls) {
+            const int t = fast_div(row, a.magicWc, a.shiftWc), wc = row - t * a.Wc;
+            const int n = fast_div(t, a.magicHc, a.shiftHc), hc = t - n * a.Hc;
+            orow = ((long long)n * a.g.H + a.g.stride * hc + a.ph) * a.g.W + a.g.stride * wc + a.pw;
+          } else if (scatter) {
             const int t = fast_div(row, a.magicQ, a.shiftQ), q = row - t * a.g.Q;
             const int n = fast_div(t, a.magicP, a.shiftP), p = t - n * a.g.P;
             orow = ((long long)n * a.g.H + 2 * p) * a.g.W + 2 * q;
@@ -716,7 +775,18 @@ static void launch_tile(Args& a, int splits, hipStream_t st) {
   a.tiles_n = (a.Ng + BN - 1) / BN;
   a.splits = splits;
   a.stats_rows = FM * 32;
-  dim3 grid(grid_blocks(a));
+  unsigned blocks_all = grid_blocks(a);
+  if (PASS == PASS_DGRAD && a.cls) {  // the four classes side by side, each dealt to the XCDs like a launch of its own
+    blocks_all = 0;
+    for (int c = 0; c < 4; ++c) {
+      Args t = a;
+      t.tiles_m = a.cls_tiles_m[c] = (a.cls_Mg[c] + BM - 1) / BM;
+      blocks_all += grid_blocks(t);
+      a.cls_end[c] = (int)blocks_all;
+    }
+    a.tiles_m = a.cls_tiles_m[3];
+  }
+  dim3 grid(blocks_all);
   // GEMMs with at most SHORT_NK k-tiles: no ring, twice the workgroups per CU
   // Ring depth.  LDS decides how many workgroups share a CU (160 KiB); a grid with more workgroups than
   // that keeps the CUs busiest with many short rings, a grid that cannot fill them anyway is better
@@ -724,7 +794,7 @@ static void launch_tile(Args& a, int splits, hipStream_t st) {
   constexpr int STAGE = (BM + BN) * ROWB;
   constexpr int DEEP2 = 2 * 3 * STAGE <= 160 * 1024 ? 3 : 2;  // two workgroups per CU
   constexpr int DEEP1 = 5 * STAGE <= 160 * 1024 ? 5 : 4;      // one workgroup per CU
-  const long long blocks = (long long)a.tiles_m * a.tiles_n * splits;
+  const long long blocks = (PASS == PASS_DGRAD && a.cls) ? (long long)blocks_all : (long long)a.tiles_m * a.tiles_n * splits;
   if (PASS != PASS_WGRAD && a.nk <= SHORT_NK)  // no ring, four workgroups per CU
     hipLaunchKernelGGL((igemm_dma_kernel<PASS, (PASS == PASS_WGRAD ? 2 : 1), 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
   else if (blocks <= 256 && a.nk_per_split >= 8)

@@ -82,6 +82,10 @@ CONV_SHAPES = [
     (3, 20, 20, 64, 64, 3, 1, 1),     # 64-wide GEMMs in all three passes, several ragged row tiles
     (2, 30, 30, 64, 256, 1, 1, 0),    # one k-tile forward (no ring), two in dgrad
     (2, 9, 9, 256, 64, 1, 1, 0),      # four k-tiles forward, one in dgrad
+    (2, 16, 16, 64, 128, 3, 2, 1),    # strided 3x3, fast path: dgrad as one GEMM per parity class of input pixels
+    (2, 15, 13, 128, 64, 3, 2, 1),    # ... odd extents: the four classes differ in size
+    (1, 11, 11, 64, 64, 5, 2, 2),     # ... 5x5: two or three taps per axis and class
+    (2, 14, 14, 64, 64, 3, 2, 0),     # ... no padding: the last input row and column meet no output pixel
 ]
 
 
