@@ -697,6 +697,7 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   // the fork orders); a cotangent they write is waited for where the main stream first touches it.
   std::vector<int> grad_event(nops + 1, -1);   // per tensor: pending side-stream write of its cotangent
   std::vector<char> branch_forked(pl.branch_conv.size(), 0);
+  int early_join = -1;  // event slot: everything the side stream got before the first op's filter gradient
   for (int i = nops - 2; i >= 0; --i) {
     const s4tf_op& op = net->ops[i];
     const TensorPlan& in = pl.t[op.in];
@@ -730,6 +731,10 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
           if (on_side) CHECK(side_done(grad_event[src]));
         }
         if (!on_side) CHECK(fork());
+        // The filter gradient queued next is the last piece of side-stream work when this is the first op
+        // of the net: mark the point before it, so that the optimizer can start on every other parameter
+        // while that gradient is still being computed.
+        if (i == 0 && pl.poff[0] == 0) CHECK(side_done(early_join));
         float* dbias = op.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr;
         if (pl.pad_c[i]) {  // the batch has no cotangent; the filter gradient of the padded channels is dropped
           d.c = pl.pad_c[i];
@@ -769,6 +774,15 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
     }
   }
   // ---- optimizer: one launch over the whole arena, once the side stream's gradients are in ----
+  if (early_join >= 0) {  // all parameters but the first op's, then, after the join, those
+    const s4tf_op& op0 = net->ops[0];  // its parameters lie at the start of the arena, padded to 8 elements each
+    const size_t head = op0.has_bias ? (size_t)pl.poff[1] + align_up((size_t)pl.psize[1], 8) : align_up((size_t)pl.psize[0], 8);
+    CHECK(wait_side(early_join));
+    CHECK(sgd(params->count - head, params->master + head, params->velocity + head, params->grad + head,
+              bf16 ? (void*)(static_cast<bf16_t*>(params->lowp) + head) : nullptr, lr, net->momentum, st));
+    CHECK(join.now());
+    return sgd(head, params->master, params->velocity, params->grad, bf16 ? params->lowp : nullptr, lr, net->momentum, st);
+  }
   CHECK(join.now());
   return sgd(params->count, params->master, params->velocity, params->grad, bf16 ? params->lowp : nullptr, lr,
              net->momentum, st);
