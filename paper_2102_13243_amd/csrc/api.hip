@@ -128,6 +128,8 @@ static size_t conv_vjp_ws_parts(const s4tf_conv_desc& d, size_t* dz_bytes) {
   size_t dz = d.act != S4TF_ACT_NONE ? align_up((size_t)g.N * g.P * g.Q * g.K * dtype_size(d.dtype), 256) : 0;
   if (dz_bytes) *dz_bytes = dz;
   size_t wg = d.groups == 1 ? igemm_wgrad_workspace(g, d.dtype) : dwconv_wgrad_workspace(g);
+  const size_t cs = colsum_workspace((size_t)g.N * g.P * g.Q, g.K);  // bias gradient: used before the filter gradient, same bytes
+  if (cs > wg) wg = cs;
   return dz + align_up(wg, 256);
 }
 
@@ -148,7 +150,7 @@ static int conv_dgrad_impl(const s4tf_conv_desc& d, const void* w, const void* d
 static int conv_param_grads_impl(const s4tf_conv_desc& d, const void* x, const void* dz, float* dw, float* dbias,
                                  void* wg_ws, size_t wg_bytes, hipStream_t st) {
   ConvGeom g = conv_geom(d);
-  if (dbias) CHECK(colsum(d.dtype, dz, (size_t)g.N * g.P * g.Q, g.K, dbias, st));
+  if (dbias) CHECK(colsum(d.dtype, dz, (size_t)g.N * g.P * g.Q, g.K, dbias, st, wg_ws, wg_bytes));
   if (d.groups == 1) return igemm_wgrad(g, d.dtype, x, dz, dw, wg_ws, wg_bytes, st);
   return dwconv_wgrad(g, d.dtype, x, dz, dw, wg_ws, st);
 }
@@ -266,6 +268,10 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
         }
         size_t ws = op.groups == 1 ? igemm_wgrad_workspace(g, net->dtype) : dwconv_wgrad_workspace(g);
         if (ws > wscratch) wscratch = ws;
+        if (op.has_bias) {
+          ws = colsum_workspace((size_t)g.N * g.P * g.Q, g.K);
+          if (ws > wscratch) wscratch = ws;
+        }
         // a BatchNorm right behind takes its statistics from partial sums the convolution leaves in scratch
         if (i + 1 < nops && net->ops[i + 1].kind == S4TF_OP_BN && net->ops[i + 1].in == i + 1 && op.groups == 1) {
           ws = igemm_fwd_stats_bytes(g);

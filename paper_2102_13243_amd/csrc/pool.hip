@@ -180,6 +180,7 @@ __global__ void act_vjp_kernel(const T* __restrict__ y, const T* dy, T* dz, long
 }
 
 // ---- out[c] = sum over rows of a[row][c]; one block per 64 columns, fixed summation order ------
+constexpr int COLSUM_CHUNKS = 512;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ a, long long rows, int cols, float* __restrict__ out) {
   __shared__ double red[4][64];
@@ -191,6 +192,30 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ a, lo
   red[rl][cl] = s;
   __syncthreads();
   if (rl == 0 && c < cols) out[c] = (float)(red[0][cl] + red[1][cl] + red[2][cl] + red[3][cl]);
+}
+
+// The same in two stages for tall matrices: chunk z adds its rows (four row lanes per column, as above)
+// into part[z][c], then the chunks are added in order.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_part_kernel(const T* __restrict__ a, long long rows, int cols, long long per,
+                                                          double* __restrict__ part) {
+  __shared__ double red[4][64];
+  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
+  const long long r0 = (long long)blockIdx.y * per, r1 = r0 + per < rows ? r0 + per : rows;
+  double s = 0.0;
+  if (c < cols)
+    for (long long r = r0 + rl; r < r1; r += 4) s += (double)to_f32<T>(a[r * cols + c]);
+  red[rl][cl] = s;
+  __syncthreads();
+  if (rl == 0 && c < cols) part[(long long)blockIdx.y * cols + c] = red[0][cl] + red[1][cl] + red[2][cl] + red[3][cl];
+}
+__global__ __launch_bounds__(64) void colsum_final_kernel(const double* __restrict__ part, int chunks, int cols, float* __restrict__ out) {
+  const int c = blockIdx.x * 64 + threadIdx.x;
+  if (c >= cols) return;
+  double s = 0.0;
+  for (int z = 0; z < chunks; ++z) s += part[(long long)z * cols + c];
+  out[c] = (float)s;
 }
 
 // ---- zero padding of one axis: dst[o][c][i] = c < C ? src[o][c][i] : 0 with Cp >= C channels -------
@@ -319,9 +344,25 @@ int act_vjp(int dtype, int act, const void* y, const void* dy, void* dz, size_t 
   return launch_status("act_vjp");
 }
 
-int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStream_t st) {
+size_t colsum_workspace(size_t rows, int cols) {
+  return rows >= 4096 ? (size_t)COLSUM_CHUNKS * cols * sizeof(double) : 0;
+}
+
+int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStream_t st, void* ws, size_t ws_bytes) {
   ProfScope ps(PC_ELEMENTWISE, st);
   dim3 grid((cols + 63) / 64), block(256);
+  const size_t need = colsum_workspace(rows, cols);
+  if (need > 0 && ws && ws_bytes >= need) {  // tall: one block per 64 columns alone would walk all rows
+    const long long per = ((long long)rows + COLSUM_CHUNKS - 1) / COLSUM_CHUNKS;
+    const int chunks = (int)(((long long)rows + per - 1) / per);
+    double* part = static_cast<double*>(ws);
+    if (dtype == S4TF_BF16)
+      hipLaunchKernelGGL(colsum_part_kernel<bf16_t>, dim3(grid.x, chunks), block, 0, st, (const bf16_t*)a, (long long)rows, cols, per, part);
+    else
+      hipLaunchKernelGGL(colsum_part_kernel<float>, dim3(grid.x, chunks), block, 0, st, (const float*)a, (long long)rows, cols, per, part);
+    hipLaunchKernelGGL(colsum_final_kernel, grid, dim3(64), 0, st, part, chunks, cols, out);
+    return launch_status("colsum");
+  }
   if (dtype == S4TF_BF16)
     hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)a, (long long)rows, cols, out);
   else

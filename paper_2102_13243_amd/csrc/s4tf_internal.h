@@ -108,7 +108,10 @@ int dwconv_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, fl
 
 // elementwise / reductions
 int act_vjp(int dtype, int act, const void* y, const void* dy, void* dz, size_t count, hipStream_t st);
-int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStream_t st);
+// ws (optional, colsum_workspace(rows, cols) bytes): lets a tall matrix be summed by many blocks in two stages
+size_t colsum_workspace(size_t rows, int cols);
+int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStream_t st, void* ws = nullptr,
+           size_t ws_bytes = 0);
 
 // zero-pad / strip the channel axis of [outer][C][inner] tensors
 int pad_channels(int dtype, const void* src, void* dst, long long outer, int C, int Cp, int inner, hipStream_t st);
