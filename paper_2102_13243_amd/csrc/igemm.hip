@@ -671,15 +671,56 @@ void fill_tiles(Args& a, int BM, int BN, int BK) {
   a.split_stride = 0;
 }
 
+// Tile of the generic fp32 kernel for a GEMM with Mg rows and Ng columns.  The MFMA work of a tile does
+// not shrink with the part of it that lies inside the matrix, so a side that fills a small part of
+// 128 takes a narrower tile; a narrower tile reads more LDS per MFMA, hence the weights.
+void f32_tile(int Mg, int Ng, int& BM, int& BN) {
+  const int bn[3] = {128, 64, 32};
+  const float wn[3] = {1.f, 1.15f, 1.4f};
+  float best = 0.f;
+  BN = 128;
+  for (int i = 0; i < 3; ++i) {
+    const float cost = (float)((Ng + bn[i] - 1) / bn[i] * bn[i]) * wn[i];
+    if (i == 0 || cost < best) { best = cost; BN = bn[i]; }
+  }
+  BM = 128;
+  if (BN >= 64) {
+    const float c128 = (float)((Mg + 127) / 128 * 128), c64 = (float)((Mg + 63) / 64 * 64) * 1.15f;
+    if (c64 < c128) BM = 64;
+  }
+}
+
+template <typename T, int PASS, int WM, int WN, int FM, int FN> void launch_shape(const Args& a, dim3 grid, hipStream_t st) {
+  if (vec_ok<T>(a.g))
+    hipLaunchKernelGGL((igemm_kernel<T, PASS, true, WM, WN, FM, FN>), grid, dim3(NT), 0, st, a);
+  else
+    hipLaunchKernelGGL((igemm_kernel<T, PASS, false, WM, WN, FM, FN>), grid, dim3(NT), 0, st, a);
+}
+
+// a.tiles_m / a.tiles_n must come from fill_tiles with the tile this picks: 128x128 for bf16,
+// f32_tile's for fp32
 template <typename T, int PASS> int launch(Args& a, int splits, hipStream_t st) {
   if (sizeof(T) == 2 && igemm_dma_ok(PASS, a.g, a)) return igemm_dma_launch(PASS, a, splits, st);
   a.splits = splits;
   dim3 grid(grid_blocks(a));
-  if (vec_ok<T>(a.g))
-    hipLaunchKernelGGL((igemm_kernel<T, PASS, true, 2, 2, 2, 2>), grid, dim3(NT), 0, st, a);
-  else
-    hipLaunchKernelGGL((igemm_kernel<T, PASS, false, 2, 2, 2, 2>), grid, dim3(NT), 0, st, a);
+  if constexpr (sizeof(T) == 4) {
+    int BM, BN;
+    f32_tile(a.Mg, a.Ng, BM, BN);
+    if (BM == 128 && BN == 128) launch_shape<T, PASS, 2, 2, 2, 2>(a, grid, st);
+    else if (BM == 128 && BN == 64) launch_shape<T, PASS, 2, 2, 2, 1>(a, grid, st);
+    else if (BM == 128 && BN == 32) launch_shape<T, PASS, 4, 1, 1, 1>(a, grid, st);
+    else if (BM == 64 && BN == 128) launch_shape<T, PASS, 2, 2, 1, 2>(a, grid, st);
+    else launch_shape<T, PASS, 2, 2, 1, 1>(a, grid, st);
+  } else {
+    launch_shape<T, PASS, 2, 2, 2, 2>(a, grid, st);
+  }
   return launch_status("igemm");
+}
+
+void fill_tiles_f32(Args& a) {
+  int BM, BN;
+  f32_tile(a.Mg, a.Ng, BM, BN);
+  fill_tiles(a, BM, BN, Cfg<float>::BK);
 }
 
 // Split of the wgrad reduction axis (output pixels) over workgroups.  The fast bf16 kernel keeps two
@@ -697,7 +738,9 @@ void wgrad_split(const ConvGeom& g, int dtype, int& splits, int& nk_per_split) {
     const long long tiles = (long long)((Mg + BM - 1) / BM) * ((g.K + BN - 1) / BN);
     want = 512 / tiles;
   } else {
-    const long long tiles = (long long)((Mg + 127) / 128) * ((g.K + 127) / 128);
+    int BM = 128, BN = 128;
+    if (dtype != S4TF_BF16) f32_tile(Mg, g.K, BM, BN);
+    const long long tiles = (long long)((Mg + BM - 1) / BM) * ((g.K + BN - 1) / BN);
     want = (1024 + tiles - 1) / tiles;
   }
   if (want > nk) want = nk;
@@ -727,7 +770,7 @@ int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const 
     }
     return launch<bf16_t, PASS_FWD>(a, 1, st);
   }
-  fill_tiles(a, 128, 128, Cfg<float>::BK);
+  fill_tiles_f32(a);
   return launch<float, PASS_FWD>(a, 1, st);
 }
 
@@ -782,7 +825,7 @@ int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, voi
     fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
     return launch<bf16_t, PASS_DGRAD>(a, 1, st);
   }
-  fill_tiles(a, 128, 128, Cfg<float>::BK);
+  fill_tiles_f32(a);
   return launch<float, PASS_DGRAD>(a, 1, st);
 }
 
@@ -805,7 +848,8 @@ int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, flo
   const long long n = (long long)a.Mg * a.Ng;
   if (splits > 1 && ws_bytes < (size_t)splits * n * sizeof(float))
     return fail(S4TF_ERR_WORKSPACE, "wgrad needs %zu workspace bytes, got %zu", (size_t)splits * n * sizeof(float), ws_bytes);
-  fill_tiles(a, 128, 128, dtype == S4TF_BF16 ? Cfg<bf16_t>::BK : Cfg<float>::BK);
+  if (dtype == S4TF_BF16) fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
+  else fill_tiles_f32(a);
   a.nk_per_split = per;
   a.split_stride = n;
   a.out = splits > 1 ? ws : (void*)dw;
