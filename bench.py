@@ -15,6 +15,30 @@ import numpy as np
 
 METRIC = "train images/sec (fwd+VJP+SGD), ResNet-50 shape bs64 bf16; MFMA util %"
 PEAK = {"bf16": 2500.0, "f32": 157.3}   # dense MFMA TFLOP/s, MI355X
+HBM_PEAK_TBPS = 8.0
+
+# HBM bytes per launch (reads + writes, averaged over one step's launches of the class) from the hardware
+# counters FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a copy kernel of known size.  The
+# figures belong to the kernel sources whose digest is given; with other sources they are not reported.
+TRAFFIC = {
+    "resnet50": {"sources_sha256": "57cd31f04d1e2be59d68a2408e8f6a1d80fea934c322ebfd2149293453f64975",
+                 "bytes_per_launch": {"conv_wgrad_igemm": 86.10e6, "conv_dgrad_igemm": 73.37e6, "conv_fwd_igemm": 60.86e6}},
+}
+TRAFFIC_SOURCES = ("igemm.hip", "igemm_dma.hip", "igemm_args.h")
+
+
+def measured_traffic(workload, cls):
+    import hashlib
+    import os
+    rec = TRAFFIC.get(workload)
+    if not rec or cls not in rec["bytes_per_launch"]:
+        return None
+    h = hashlib.sha256()
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2102_13243_amd", "csrc")
+    for f in TRAFFIC_SOURCES:
+        with open(os.path.join(src, f), "rb") as fh:
+            h.update(fh.read())
+    return rec["bytes_per_launch"][cls] if h.hexdigest() == rec["sources_sha256"] else None
 
 
 def conv_flops(net, shapes):
@@ -37,6 +61,34 @@ def conv_flops(net, shapes):
     return out
 
 
+def class_bytes(net, shapes, n_params):
+    """Algorithmic HBM bytes of one step for the classes that no contraction bounds: every operand a
+    kernel class must read or write once, at the storage width (es) of activations; fp32 elsewhere.
+      bn_apply       x -> y (+ residual read)                       (2 + res) * numel * es
+      bn_vjp_reduce  x, dy (+ y for the activation mask)            (2 + act) * numel * es
+      bn_vjp_apply   x, dy (+ y) -> dx (+ residual cotangent)       (3 + act + res) * numel * es
+      dwconv_fwd     x -> y;  dwconv_dgrad  dy -> dx;  dwconv_wgrad  x, dy      (in + out) * es each
+      sgd            p, v, g read, p, v written (fp32) (+ the bf16 working copy written)
+    """
+    es = 2 if net["dtype"] == "bf16" else 4
+    out = {"bn_apply": 0.0, "bn_vjp_reduce": 0.0, "bn_vjp_apply": 0.0, "dwconv_fwd": 0.0, "dwconv_dgrad": 0.0,
+           "dwconv_wgrad": 0.0, "sgd": n_params * (20.0 + (2.0 if es == 2 else 0.0))}
+    for i, op in enumerate(net["ops"]):
+        numel = float(np.prod(shapes[op["in"]]))
+        if op["kind"] == "bn":
+            res = 1 if op["res"] >= 0 else 0
+            act = 0 if op["act"] == "none" else 1
+            out["bn_apply"] += (2 + res) * numel * es
+            out["bn_vjp_reduce"] += (2 + act) * numel * es
+            out["bn_vjp_apply"] += (3 + act + res) * numel * es
+        elif op["kind"] == "conv" and op["groups"] > 1:
+            io = (numel + float(np.prod(shapes[i + 1]))) * es
+            out["dwconv_fwd"] += io
+            out["dwconv_dgrad"] += io
+            out["dwconv_wgrad"] += io
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +97,9 @@ def main():
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="launch only a plain copy kernel of known size (reads and writes 256 MiB, three times): "
+                         "the reference reading for the FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -55,6 +110,16 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.calibrate_copy:
+        n = 64 * 1024 * 1024
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_kernel": "torch.mul(src, 1.0, out=dst)", "bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 3}))
+        return
     kw = {"batch": args.batch} if args.batch else {}
     net = nets.CONFIGS[args.workload](**kw)
     wl = nets.make_workload(net)
@@ -89,13 +154,18 @@ def main():
         classes[name] = {"ms_per_step": ms / prof_steps, "launches_per_step": cnt / prof_steps}
         if flops.get(name):
             classes[name]["tflops"] = flops[name] / (ms / prof_steps * 1e-3) / 1e12
+    nbytes = class_bytes(net, shapes, nets.param_count(wl["params"]))
+    for name, b in nbytes.items():
+        if b and name in classes:
+            classes[name]["hbm_tbps"] = b / (classes[name]["ms_per_step"] * 1e-3) / 1e12
+            classes[name]["hbm_frac"] = classes[name]["hbm_tbps"] / HBM_PEAK_TBPS
     dom = max(classes, key=lambda k: classes[k]["ms_per_step"])
     dtype = net["dtype"]
     roofline = None
     if flops.get(dom) and dom.startswith("conv_"):
         ach = classes[dom]["tflops"]
         roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": PEAK[dtype], "unit": "TFLOP/s",
-                    "frac": round(ach / PEAK[dtype], 4), "traffic": None,
+                    "frac": round(ach / PEAK[dtype], 4), "traffic": measured_traffic(args.workload, dom),
                     "launches_per_step": classes[dom]["launches_per_step"],
                     "avg_launch_ms": classes[dom]["ms_per_step"] / classes[dom]["launches_per_step"],
                     "flops_per_step": flops[dom]}
