@@ -88,17 +88,36 @@ __global__ void maxpool3s2_fwd_kernel(const T* __restrict__ x, T* __restrict__ y
 // the four windows (a..a+1, b..b+1) and in no other; each window is scanned once in window order with
 // a strict '>' (the first maximum keeps the title) and hands its dy to the cell pixel that won, if any.
 template <typename T, int V>
-__global__ void maxpool3s2_vjp_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int N,
-                                      int H, int W, int C, int accumulate) {
+__global__ __launch_bounds__(256) void maxpool3s2_vjp_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx,
+                                                             int N, int H, int W, int C, int accumulate) {
   const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1, CV = C / V;
   const int HA = (H + 1) / 2, WB = (W + 1) / 2;
   const long long total = (long long)N * HA * WB * CV;
-  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long long)gridDim.x * blockDim.x) {
-    int c = (int)(idx % CV) * V;
+  // Consecutive workgroup ids run on different XCDs, each with an L2 of its own.  Cells in adjacent rows
+  // share two of their four input rows, so every XCD gets a contiguous run of cells (the grid is a multiple
+  // of 8 workgroups) and finds the rows its previous workgroups fetched in its own L2.
+  const unsigned per_xcd = gridDim.x / 8;
+  const unsigned lb = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  for (long long idx = (long long)lb * blockDim.x + threadIdx.x; idx < total; idx += (long long)gridDim.x * blockDim.x) {
+    const int c = (int)(idx % CV) * V;
     long long t = idx / CV;
-    int b = (int)(t % WB);
+    const int b = (int)(t % WB);
     t /= WB;
-    int a = (int)(t % HA), n = (int)(t / HA);
+    const int a = (int)(t % HA), n = (int)(t / HA);
+    // the 5x5 pixels (2a-1..2a+3, 2b-1..2b+3) that the cell's four windows cover, loaded once (36 loads
+    // window by window); a pixel outside the image is loaded from the nearest one inside and counts as -inf
+    Pack<T, V> nb[5][5];
+    bool in[5][5];
+#pragma unroll
+    for (int r = 0; r < 5; ++r) {
+      const int hh = 2 * a - 1 + r, hc = hh < 0 ? 0 : (hh >= H ? H - 1 : hh);
+#pragma unroll
+      for (int s = 0; s < 5; ++s) {
+        const int ww = 2 * b - 1 + s, wc = ww < 0 ? 0 : (ww >= W ? W - 1 : ww);
+        nb[r][s] = ldp<T, V>(x + (((long long)n * H + hc) * W + wc) * C + c);
+        in[r][s] = hh == hc && ww == wc;
+      }
+    }
     float g[2][2][V];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
@@ -117,21 +136,14 @@ __global__ void maxpool3s2_vjp_kernel(const T* __restrict__ x, const T* __restri
 #pragma unroll
         for (int v = 0; v < V; ++v) { best[v] = -INFINITY; bi[v] = -1; }
 #pragma unroll
-        for (int r = 0; r < 3; ++r) {
-          const int hh = 2 * p + r - 1;
-          if (hh < 0 || hh >= H) continue;
+        for (int r = 0; r < 3; ++r)
 #pragma unroll
-          for (int s = 0; s < 3; ++s) {
-            const int ww = 2 * q + s - 1;
-            if (ww < 0 || ww >= W) continue;
-            const Pack<T, V> xv = ldp<T, V>(x + (((long long)n * H + hh) * W + ww) * C + c);
+          for (int s = 0; s < 3; ++s)
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-              const float e = xv.get(v);
+              const float e = in[2 * i + r][2 * j + s] ? nb[2 * i + r][2 * j + s].get(v) : -INFINITY;
               if (e > best[v]) { best[v] = e; bi[v] = r * 3 + s; }
             }
-          }
-        }
         const Pack<T, V> dv = ldp<T, V>(dy + (((long long)n * P + p) * Q + q) * C + c);
         // cell pixel (dh, dw) sits at window position (dh + 1 - 2i, dw + 1 - 2j)
 #pragma unroll
@@ -316,9 +328,9 @@ int pool_vjp(const s4tf_pool_desc& d, const void* x, const void* dy, void* dx, h
   const bool vec = d.c % V == 0 && aligned16(x) && aligned16(dy) && aligned16(dx);
   dim3 vgrid(blocks_for((long long)d.n * d.h * d.w * d.c / V));
   const long long cells = (long long)d.n * ((d.h + 1) / 2) * ((d.w + 1) / 2);  // max pool: a thread per 2x2 cell
-  if (!avg) {
-    grid = dim3(blocks_for(cells * d.c));
-    vgrid = dim3(blocks_for(cells * d.c / V));
+  if (!avg) {  // a multiple of 8 workgroups: the kernel hands each XCD an equal run of them
+    grid = dim3((blocks_for(cells * d.c) + 7) / 8 * 8);
+    vgrid = dim3((blocks_for(cells * d.c / V) + 7) / 8 * 8);
   }
   if (d.dtype == S4TF_BF16) {
     typedef bf16_t T;

@@ -136,7 +136,14 @@ def test_conv2d_fwd_and_vjp(shape, bf16):
 
 # n h w c r stride pad
 DW_SHAPES = [(2, 14, 14, 32, 3, 1, 1), (2, 15, 15, 96, 3, 2, 1), (1, 7, 7, 960, 3, 1, 1), (3, 9, 9, 6, 3, 1, 1),
-             (2, 28, 28, 144, 3, 2, 1)]
+             (2, 28, 28, 144, 3, 2, 1),
+             (2, 13, 18, 24, 3, 1, 1),      # not square, widths that leave a ragged last strip
+             (2, 13, 18, 24, 3, 2, 1),
+             (2, 12, 17, 40, 3, 2, 1),      # even height, odd width, stride 2
+             (8, 15, 64, 1024, 3, 1, 1),    # enough threads for the longest row walk (14 rows), last chunk of one row
+             (8, 29, 128, 1024, 3, 2, 1),   # ... and for 7-row walks at stride 2
+             (2, 9, 9, 16, 3, 1, 0),        # no padding: the general kernels
+             (2, 11, 11, 8, 2, 2, 0)]       # 2x2 filter
 
 
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
@@ -160,6 +167,20 @@ def test_depthwise_conv(shape, bf16):
     B.s4tf_conv2d_vjp(d, xd, wd, None, to_dev(dy, bf16), dx, dw, None, wsp)
     assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < (4e-3 if bf16 else 2e-5)
     assert rel_l2(to_host(dw), dw_ref) < (2e-3 if bf16 else 1e-4)
+    if n * h * w * c > 4_000_000:
+        return
+    # bias and activation in the forward pass; the pullback accumulating into an existing cotangent
+    bias = RNG.standard_normal(c).astype(np.float32)
+    d2 = B.ConvDesc(n, h, w, c, c, r, r, stride, pad, c, B.S4TF_BF16 if bf16 else B.S4TF_F32, B.ACT["relu6"], 0)
+    B.s4tf_conv2d_fwd(d2, xd, wd, to_dev(bias), y)
+    y2_ref = orc.bias_act_fwd(orc.conv2d_fwd(x, wt, bias, stride, pad, groups=c), None, "relu6")
+    assert rel_l2(to_host(y), orc.round_bf16(y2_ref) if bf16 else y2_ref) < (4e-3 if bf16 else 2e-5)
+    base = grid(RNG.standard_normal((n, h, w, c)), bf16)
+    d3 = B.ConvDesc(n, h, w, c, c, r, r, stride, pad, c, B.S4TF_BF16 if bf16 else B.S4TF_F32, B.ACT["none"], 1)
+    dx2 = to_dev(base, bf16)
+    B.s4tf_conv2d_vjp(d3, xd, wd, None, to_dev(dy, bf16), dx2, dw, None, wsp)
+    want = base + dx_ref
+    assert rel_l2(to_host(dx2), orc.round_bf16(want) if bf16 else want) < (4e-3 if bf16 else 2e-5)
 
 
 BN_SHAPES = [(2, 5, 7, 16), (4, 16, 16, 64), (3, 9, 9, 6), (2, 7, 7, 960), (64, 8, 8, 32), (1, 1, 3, 8)]
