@@ -78,8 +78,8 @@ __device__ inline uint32_t half_of(const uint4& v, int e) {  // 16-bit element e
 
 // ---- loaders --------------------------------------------------------------------------------
 // K-contiguous sources: a thread owns one 16-byte chunk column (kc) of ROWS/64 rows.
-template <typename T, int ROWS> struct KLoaderBase {
-  static constexpr int VEC = Cfg<T>::VEC, BK = Cfg<T>::BK, STRIDE = BK + Cfg<T>::PAD;
+template <typename T, int ROWS, int BK_> struct KLoaderBase {
+  static constexpr int VEC = Cfg<T>::VEC, BK = BK_, STRIDE = BK + Cfg<T>::PAD;
   static constexpr int CPR = BK / VEC;       // chunks per row
   static constexpr int RPP = NT / CPR;       // rows per pass
   static constexpr int NP = (ROWS + RPP - 1) / RPP;
@@ -94,8 +94,8 @@ template <typename T, int ROWS> struct KLoaderBase {
 };
 
 // forward A: rows are output pixels (n,p,q), k = (r,s,c)
-template <typename T, int ROWS> struct FwdALoader : KLoaderBase<T, ROWS> {
-  typedef KLoaderBase<T, ROWS> B_;
+template <typename T, int ROWS, int BK_> struct FwdALoader : KLoaderBase<T, ROWS, BK_> {
+  typedef KLoaderBase<T, ROWS, BK_> B_;
   const T* x;
   long long base[B_::NP];
   int h0[B_::NP], w0[B_::NP];
@@ -136,8 +136,8 @@ template <typename T, int ROWS> struct FwdALoader : KLoaderBase<T, ROWS> {
 };
 
 // dgrad A: rows are input pixels (n,h,w), k = (r,s,ko); gathers dy
-template <typename T, int ROWS> struct DgradALoader : KLoaderBase<T, ROWS> {
-  typedef KLoaderBase<T, ROWS> B_;
+template <typename T, int ROWS, int BK_> struct DgradALoader : KLoaderBase<T, ROWS, BK_> {
+  typedef KLoaderBase<T, ROWS, BK_> B_;
   const T* dy;
   long long base[B_::NP];
   int hp0[B_::NP], wp0[B_::NP];
@@ -189,8 +189,8 @@ template <typename T, int ROWS> struct DgradALoader : KLoaderBase<T, ROWS> {
 };
 
 // dgrad B: rows are input channels c, k = (r,s,ko); filters are contiguous along ko
-template <typename T, int ROWS> struct DgradBLoader : KLoaderBase<T, ROWS> {
-  typedef KLoaderBase<T, ROWS> B_;
+template <typename T, int ROWS, int BK_> struct DgradBLoader : KLoaderBase<T, ROWS, BK_> {
+  typedef KLoaderBase<T, ROWS, BK_> B_;
   const T* w;
   int cidx[B_::NP];
   bool rv[B_::NP];
@@ -220,8 +220,8 @@ template <typename T, int ROWS> struct DgradBLoader : KLoaderBase<T, ROWS> {
 
 // Row-contiguous sources.  A thread owns VEC adjacent rows at KP consecutive k positions and
 // scatters them into the k-contiguous LDS tile (bf16: packs KP values per row into one store).
-template <typename T, int ROWS> struct RLoaderBase {
-  static constexpr int VEC = Cfg<T>::VEC, BK = Cfg<T>::BK, STRIDE = BK + Cfg<T>::PAD;
+template <typename T, int ROWS, int BK_> struct RLoaderBase {
+  static constexpr int VEC = Cfg<T>::VEC, BK = BK_, STRIDE = BK + Cfg<T>::PAD;
   static constexpr int RC = ROWS / VEC;                       // row chunks
   static constexpr int KG = (NT / RC) < BK ? (NT / RC) : BK;  // k groups
   static constexpr int KP = BK / KG;                          // k positions per thread
@@ -259,8 +259,8 @@ template <typename T, int ROWS> struct RLoaderBase {
 };
 
 // plain [k][ld] matrix: filters in the forward pass ([(r,s,c)][ko]) and dy in wgrad ([(n,p,q)][ko])
-template <typename T, int ROWS> struct PlainRLoader : RLoaderBase<T, ROWS> {
-  typedef RLoaderBase<T, ROWS> B_;
+template <typename T, int ROWS, int BK_> struct PlainRLoader : RLoaderBase<T, ROWS, BK_> {
+  typedef RLoaderBase<T, ROWS, BK_> B_;
   const T* src;
   int j0, kk;
   bool rv;
@@ -281,8 +281,8 @@ template <typename T, int ROWS> struct PlainRLoader : RLoaderBase<T, ROWS> {
 };
 
 // wgrad A: rows are (r,s,c) (contiguous along c), k = output pixel (n,p,q); gathers x
-template <typename T, int ROWS> struct WgradALoader : RLoaderBase<T, ROWS> {
-  typedef RLoaderBase<T, ROWS> B_;
+template <typename T, int ROWS, int BK_> struct WgradALoader : RLoaderBase<T, ROWS, BK_> {
+  typedef RLoaderBase<T, ROWS, BK_> B_;
   const T* x;
   int r, s, c0;
   bool rv;
@@ -334,8 +334,8 @@ template <typename T, int ROWS> struct WgradALoader : RLoaderBase<T, ROWS> {
 // Element-wise fallback for channel counts that are not a multiple of the vector width
 // (first layers with 1 or 3 channels, 6- and 10-wide outputs).  Full index arithmetic per
 // element: slow, used only where the tensors are tiny or the layer is a stem.
-template <typename T, int PASS, int ROWS, bool IS_A> struct ScalarLoader {
-  static constexpr int BK = Cfg<T>::BK, STRIDE = BK + Cfg<T>::PAD;
+template <typename T, int PASS, int ROWS, bool IS_A, int BK_> struct ScalarLoader {
+  static constexpr int BK = BK_, STRIDE = BK + Cfg<T>::PAD;
   static constexpr int E = ROWS * BK / NT;
   static constexpr bool KFAST = IS_A ? (PASS != PASS_WGRAD) : (PASS == PASS_DGRAD);
   T v[E];
@@ -368,18 +368,17 @@ template <typename T, int PASS, int ROWS, bool IS_A> struct ScalarLoader {
   }
 };
 
-template <typename T, int PASS, int ROWS, bool VECMODE, bool IS_A> struct LoaderSel;
-template <typename T, int ROWS> struct LoaderSel<T, PASS_FWD, ROWS, true, true> { typedef FwdALoader<T, ROWS> type; };
-template <typename T, int ROWS> struct LoaderSel<T, PASS_FWD, ROWS, true, false> { typedef PlainRLoader<T, ROWS> type; };
-template <typename T, int ROWS> struct LoaderSel<T, PASS_DGRAD, ROWS, true, true> { typedef DgradALoader<T, ROWS> type; };
-template <typename T, int ROWS> struct LoaderSel<T, PASS_DGRAD, ROWS, true, false> { typedef DgradBLoader<T, ROWS> type; };
-template <typename T, int ROWS> struct LoaderSel<T, PASS_WGRAD, ROWS, true, true> { typedef WgradALoader<T, ROWS> type; };
-template <typename T, int ROWS> struct LoaderSel<T, PASS_WGRAD, ROWS, true, false> { typedef PlainRLoader<T, ROWS> type; };
+template <typename T, int PASS, int ROWS, bool VECMODE, bool IS_A, int BK_> struct LoaderSel;
+template <typename T, int ROWS, int BK_> struct LoaderSel<T, PASS_FWD, ROWS, true, true, BK_> { typedef FwdALoader<T, ROWS, BK_> type; };
+template <typename T, int ROWS, int BK_> struct LoaderSel<T, PASS_FWD, ROWS, true, false, BK_> { typedef PlainRLoader<T, ROWS, BK_> type; };
+template <typename T, int ROWS, int BK_> struct LoaderSel<T, PASS_DGRAD, ROWS, true, true, BK_> { typedef DgradALoader<T, ROWS, BK_> type; };
+template <typename T, int ROWS, int BK_> struct LoaderSel<T, PASS_DGRAD, ROWS, true, false, BK_> { typedef DgradBLoader<T, ROWS, BK_> type; };
+template <typename T, int ROWS, int BK_> struct LoaderSel<T, PASS_WGRAD, ROWS, true, true, BK_> { typedef WgradALoader<T, ROWS, BK_> type; };
+template <typename T, int ROWS, int BK_> struct LoaderSel<T, PASS_WGRAD, ROWS, true, false, BK_> { typedef PlainRLoader<T, ROWS, BK_> type; };
 
 // ---- MFMA over one staged k-tile ----------------------------------------------------------------
-template <typename T, int FM, int FN, int STRIDE>
+template <typename T, int FM, int FN, int STRIDE, int BK>
 __device__ inline void mma_tile(const T* As, const T* Bs, int arow, int brow, int lane, f32x16 (&acc)[FM][FN]) {
-  constexpr int BK = Cfg<T>::BK;
   if constexpr (sizeof(T) == 2) {
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
@@ -415,13 +414,19 @@ __device__ inline void mma_tile(const T* As, const T* Bs, int arow, int brow, in
   }
 }
 
-// WM x WN wavefronts, each FM x FN MFMA blocks of 32x32
-template <typename T, int PASS, bool VECMODE, int WM, int WN, int FM, int FN>
+// WM x WN x WK wavefronts, each FM x FN MFMA blocks of 32x32.  With WK > 1 the WK wavefronts that share
+// an output sub-tile each multiply a WK-th of every k-tile's depth and their accumulators are added
+// through LDS before the epilogue: small output tiles (many workgroups for GEMMs with few rows) that
+// still keep four wavefronts busy.
+template <typename T, int PASS, bool VECMODE, int WM, int WN, int FM, int FN, int BK_, int WK = 1>
 __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
-  static_assert(WM * WN == 4, "four wavefronts");
+  static_assert(WM * WN * WK == 4, "four wavefronts");
+  static_assert(WK == 1 || sizeof(T) == 4, "the k split over wavefronts is for the fp32 epilogue only");
   constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
-  constexpr int BK = Cfg<T>::BK, STRIDE = BK + Cfg<T>::PAD;
+  constexpr int BK = BK_, STRIDE = BK + Cfg<T>::PAD;
+  constexpr int KW = BK / WK;  // depth of a k-tile one wavefront multiplies
   constexpr int TILE = (BM + BN) * STRIDE;
+  static_assert((WK - 1) * FM * FN * 16 * 64 * 4 <= 2 * TILE * (int)sizeof(T), "accumulators must fit in the tile buffers");
   __shared__ __attribute__((aligned(16))) T smem[2 * TILE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -441,11 +446,13 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int arow = (wave / WN) * FM * 32, brow = (wave % WN) * FN * 32;
+  const int wk = wave / (WM * WN), wmn = wave % (WM * WN);
+  const int arow = (wmn / WN) * FM * 32, brow = (wmn % WN) * FN * 32;
+  const int koff = wk * KW;
 
   if constexpr (VECMODE) {
-    typename LoaderSel<T, PASS, BM, true, true>::type la;
-    typename LoaderSel<T, PASS, BN, true, false>::type lb;
+    typename LoaderSel<T, PASS, BM, true, true, BK>::type la;
+    typename LoaderSel<T, PASS, BN, true, false, BK>::type lb;
     la.init(a, m0, tid, kt0);
     lb.init(a, n0, tid, kt0);
     la.load(a);
@@ -460,7 +467,7 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
         la.load(a);
         lb.load(a);
       }
-      mma_tile<T, FM, FN, STRIDE>(smem + cur * TILE, smem + cur * TILE + BM * STRIDE, arow, brow, lane, acc);
+      mma_tile<T, FM, FN, STRIDE, KW>(smem + cur * TILE + koff, smem + cur * TILE + BM * STRIDE + koff, arow, brow, lane, acc);
       if (more) {
         la.store(smem + (cur ^ 1) * TILE, tid);
         lb.store(smem + (cur ^ 1) * TILE + BM * STRIDE, tid);
@@ -468,8 +475,8 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
       __syncthreads();
     }
   } else {
-    ScalarLoader<T, PASS, BM, true> la;
-    ScalarLoader<T, PASS, BN, false> lb;
+    ScalarLoader<T, PASS, BM, true, BK> la;
+    ScalarLoader<T, PASS, BN, false, BK> lb;
     la.init(a, m0, tid, kt0);
     lb.init(a, n0, tid, kt0);
     la.load(a, tid);
@@ -484,13 +491,39 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
         la.load(a, tid);
         lb.load(a, tid);
       }
-      mma_tile<T, FM, FN, STRIDE>(smem + cur * TILE, smem + cur * TILE + BM * STRIDE, arow, brow, lane, acc);
+      mma_tile<T, FM, FN, STRIDE, KW>(smem + cur * TILE + koff, smem + cur * TILE + BM * STRIDE + koff, arow, brow, lane, acc);
       if (more) {
         la.store(smem + (cur ^ 1) * TILE, tid);
         lb.store(smem + (cur ^ 1) * TILE + BM * STRIDE, tid);
       }
       __syncthreads();
     }
+  }
+
+  if constexpr (WK > 1) {
+    // the k-loop ended with a barrier: the tile buffers are free.  Wavefronts wk = 1 .. WK-1 hand their
+    // accumulators over, wavefront wk = 0 adds them in that order and alone runs the epilogue.
+    float* red = reinterpret_cast<float*>(smem);
+    if (wk > 0) {
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            red[((((wk - 1) * WM * WN + wmn) * FM * FN + i * FN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+    }
+    __syncthreads();
+    if (wk > 0) return;
+#pragma unroll
+    for (int k = 0; k < WK - 1; ++k)
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            acc[i][j][v] += red[(((k * WM * WN + wmn) * FM * FN + i * FN + j) * 16 + v) * 64 + lane];
   }
 
   // epilogue.  A 32x32 accumulator block: lane holds column (lane & 31) and, in register v,
@@ -540,6 +573,40 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
       *reinterpret_cast<uint4*>(dst) = o;
     }
     return;
+  }
+  if constexpr (PASS == PASS_FWD && sizeof(T) == 4) {
+    // Optional by-product for a BatchNorm that follows (no bias, no activation here): per channel
+    // (column) and run of 32 output rows, the sum of the outputs and the sum of their squared deviations
+    // from the run's own mean.  Lanes l and l ^ 32 hold the two halves of a column of a 32x32 block.
+    if (a.stats) {
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        const int rbase = m0 + arow + i * 32;
+        const int cnt = min(max(a.Mg - rbase, 0), 32);
+        float* part = a.stats + (long long)(rbase / 32) * 2 * a.Ng;
+        const float inv_cnt = cnt > 0 ? 1.f / (float)cnt : 0.f;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          float s2[2] = {0.f, 0.f}, q2[2] = {0.f, 0.f};
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = rbase + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+            const float val = row < a.Mg ? acc[i][j][v] : 0.f;
+            s2[v & 1] += val;
+            q2[v & 1] = fmaf(val, val, q2[v & 1]);
+          }
+          float s1 = s2[0] + s2[1], q1 = q2[0] + q2[1];
+          s1 += __shfl_xor(s1, 32, 64);
+          q1 += __shfl_xor(q1, 32, 64);
+          const float m2 = fmaxf(q1 - s1 * s1 * inv_cnt, 0.f);
+          const int col = n0 + brow + j * 32 + (lane & 31);
+          if (lane < 32 && col < a.Ng && cnt > 0) {  // a run with no valid row has no slot
+            part[col] = s1;
+            part[a.Ng + col] = m2;
+          }
+        }
+      }
+    }
   }
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -674,7 +741,7 @@ void fill_tiles(Args& a, int BM, int BN, int BK) {
 // Tile of the generic fp32 kernel for a GEMM with Mg rows and Ng columns.  The MFMA work of a tile does
 // not shrink with the part of it that lies inside the matrix, so a side that fills a small part of
 // 128 takes a narrower tile; a narrower tile reads more LDS per MFMA, hence the weights.
-void f32_tile(int Mg, int Ng, int& BM, int& BN) {
+void f32_tile(int Mg, int Ng, long long Kg, bool splits_k, int& BM, int& BN) {
   const int bn[3] = {128, 64, 32};
   const float wn[3] = {1.f, 1.15f, 1.4f};
   float best = 0.f;
@@ -688,48 +755,68 @@ void f32_tile(int Mg, int Ng, int& BM, int& BN) {
     const float c128 = (float)((Mg + 127) / 128 * 128), c64 = (float)((Mg + 63) / 64 * 64) * 1.15f;
     if (c64 < c128) BM = 64;
   }
+  if (splits_k) return;  // the filter gradient gets its workgroups from splitting the reduction axis
+  if ((long long)Mg * Ng * Kg < (1LL << 25)) return;  // too little work for the tile shape to matter
+  // fewer tiles than CUs: smaller tiles, down to 32x32 (whose four wavefronts split the k-tile's depth)
+  const int bm2[3] = {64, 64, 32}, bn2[3] = {64, 32, 32};
+  for (int i = 0; i < 3; ++i) {
+    if ((long long)((Mg + BM - 1) / BM) * ((Ng + BN - 1) / BN) >= 256) break;
+    if (bm2[i] <= BM && bn2[i] <= BN) { BM = bm2[i]; BN = bn2[i]; }
+  }
 }
 
-template <typename T, int PASS, int WM, int WN, int FM, int FN> void launch_shape(const Args& a, dim3 grid, hipStream_t st) {
+// k-tile depth of the fp32 kernel: 32 for every tile shape whose two double-buffered operand tiles fit into
+// 64 KB of LDS with it (all but 128x128), which halves the number of load-wait-multiply rounds of a
+// workgroup; 128x128 keeps 16
+int f32_bk(int BM, int BN) { return (BM == 128 && BN == 128) ? 16 : (BN == 32 && BM <= 64) ? 64 : 32; }
+
+template <typename T, int PASS, int WM, int WN, int FM, int FN, int BK, int WK = 1> void launch_shape(const Args& a, dim3 grid, hipStream_t st) {
   if (vec_ok<T>(a.g))
-    hipLaunchKernelGGL((igemm_kernel<T, PASS, true, WM, WN, FM, FN>), grid, dim3(NT), 0, st, a);
+    hipLaunchKernelGGL((igemm_kernel<T, PASS, true, WM, WN, FM, FN, BK, WK>), grid, dim3(NT), 0, st, a);
   else
-    hipLaunchKernelGGL((igemm_kernel<T, PASS, false, WM, WN, FM, FN>), grid, dim3(NT), 0, st, a);
+    hipLaunchKernelGGL((igemm_kernel<T, PASS, false, WM, WN, FM, FN, BK, WK>), grid, dim3(NT), 0, st, a);
 }
 
-// a.tiles_m / a.tiles_n must come from fill_tiles with the tile this picks: 128x128 for bf16,
-// f32_tile's for fp32
+// a.tiles_m / a.tiles_n / a.nk must come from fill_tiles with the tile this picks: 128x128 for bf16,
+// f32_tile's (and f32_bk's depth) for fp32
 template <typename T, int PASS> int launch(Args& a, int splits, hipStream_t st) {
   if (sizeof(T) == 2 && igemm_dma_ok(PASS, a.g, a)) return igemm_dma_launch(PASS, a, splits, st);
   a.splits = splits;
   dim3 grid(grid_blocks(a));
   if constexpr (sizeof(T) == 4) {
     int BM, BN;
-    f32_tile(a.Mg, a.Ng, BM, BN);
-    if (BM == 128 && BN == 128) launch_shape<T, PASS, 2, 2, 2, 2>(a, grid, st);
-    else if (BM == 128 && BN == 64) launch_shape<T, PASS, 2, 2, 2, 1>(a, grid, st);
-    else if (BM == 128 && BN == 32) launch_shape<T, PASS, 4, 1, 1, 1>(a, grid, st);
-    else if (BM == 64 && BN == 128) launch_shape<T, PASS, 2, 2, 1, 2>(a, grid, st);
-    else launch_shape<T, PASS, 2, 2, 1, 1>(a, grid, st);
+    f32_tile(a.Mg, a.Ng, a.Kg, PASS == PASS_WGRAD, BM, BN);
+    if (BM == 128 && BN == 128) launch_shape<T, PASS, 2, 2, 2, 2, 16>(a, grid, st);
+    else if (BM == 64 && BN == 32) launch_shape<T, PASS, 2, 1, 1, 1, 64, 2>(a, grid, st);
+    else if (BM == 32 && BN == 32) launch_shape<T, PASS, 1, 1, 1, 1, 64, 4>(a, grid, st);
+    else if (BM == 128 && BN == 64) launch_shape<T, PASS, 2, 2, 2, 1, 32>(a, grid, st);
+    else if (BM == 128 && BN == 32) launch_shape<T, PASS, 4, 1, 1, 1, 32>(a, grid, st);
+    else if (BM == 64 && BN == 128) launch_shape<T, PASS, 2, 2, 1, 2, 32>(a, grid, st);
+    else launch_shape<T, PASS, 2, 2, 1, 1, 32>(a, grid, st);
   } else {
-    launch_shape<T, PASS, 2, 2, 2, 2>(a, grid, st);
+    launch_shape<T, PASS, 2, 2, 2, 2, Cfg<bf16_t>::BK>(a, grid, st);
   }
   return launch_status("igemm");
 }
 
-void fill_tiles_f32(Args& a) {
+void fill_tiles_f32(Args& a, bool splits_k) {
   int BM, BN;
-  f32_tile(a.Mg, a.Ng, BM, BN);
-  fill_tiles(a, BM, BN, Cfg<float>::BK);
+  f32_tile(a.Mg, a.Ng, a.Kg, splits_k, BM, BN);
+  fill_tiles(a, BM, BN, f32_bk(BM, BN));
 }
 
 // Split of the wgrad reduction axis (output pixels) over workgroups.  The fast bf16 kernel keeps two
 // workgroups per CU resident, so one full wave of 512 equally long workgroups is the target; each
 // extra split costs a tile of fp32 partials written and read again.
 void wgrad_split(const ConvGeom& g, int dtype, int& splits, int& nk_per_split) {
-  const int BK = dtype == S4TF_BF16 ? Cfg<bf16_t>::BK : Cfg<float>::BK;
   const int Mg = g.R * g.S * g.C;
   const long long Kg = (long long)g.N * g.P * g.Q;
+  int BK = Cfg<bf16_t>::BK;
+  if (dtype != S4TF_BF16) {
+    int BM, BN;
+    f32_tile(Mg, g.K, Kg, true, BM, BN);
+    BK = f32_bk(BM, BN);
+  }
   const long long nk = (Kg + BK - 1) / BK;
   long long want;
   if (dtype == S4TF_BF16 && igemm_dma_geom_ok(PASS_WGRAD, g)) {
@@ -739,7 +826,7 @@ void wgrad_split(const ConvGeom& g, int dtype, int& splits, int& nk_per_split) {
     want = 512 / tiles;
   } else {
     int BM = 128, BN = 128;
-    if (dtype != S4TF_BF16) f32_tile(Mg, g.K, BM, BN);
+    if (dtype != S4TF_BF16) f32_tile(Mg, g.K, Kg, true, BM, BN);
     const long long tiles = (long long)((Mg + BM - 1) / BM) * ((g.K + BN - 1) / BN);
     want = (1024 + tiles - 1) / tiles;
   }
@@ -770,7 +857,11 @@ int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const 
     }
     return launch<bf16_t, PASS_FWD>(a, 1, st);
   }
-  fill_tiles_f32(a);
+  fill_tiles_f32(a, false);
+  if (stats_part && stats_rows && !bias && act == S4TF_ACT_NONE) {
+    a.stats = stats_part;
+    *stats_rows = 32;
+  }
   return launch<float, PASS_FWD>(a, 1, st);
 }
 
@@ -825,7 +916,7 @@ int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, voi
     fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
     return launch<bf16_t, PASS_DGRAD>(a, 1, st);
   }
-  fill_tiles_f32(a);
+  fill_tiles_f32(a, false);
   return launch<float, PASS_DGRAD>(a, 1, st);
 }
 
@@ -849,7 +940,7 @@ int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, flo
   if (splits > 1 && ws_bytes < (size_t)splits * n * sizeof(float))
     return fail(S4TF_ERR_WORKSPACE, "wgrad needs %zu workspace bytes, got %zu", (size_t)splits * n * sizeof(float), ws_bytes);
   if (dtype == S4TF_BF16) fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
-  else fill_tiles_f32(a);
+  else fill_tiles_f32(a, true);
   a.nk_per_split = per;
   a.split_stride = n;
   a.out = splits > 1 ? ws : (void*)dw;

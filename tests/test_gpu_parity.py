@@ -86,6 +86,7 @@ CONV_SHAPES = [
     (2, 15, 13, 128, 64, 3, 2, 1),    # ... odd extents: the four classes differ in size
     (1, 11, 11, 64, 64, 5, 2, 2),     # ... 5x5: two or three taps per axis and class
     (2, 14, 14, 64, 64, 3, 2, 0),     # ... no padding: the last input row and column meet no output pixel
+    (2, 64, 64, 32, 64, 3, 1, 1),     # fp32: enough work and few enough tiles for the 64x32 and 32x32 tiles
 ]
 
 
