@@ -417,8 +417,11 @@ __device__ inline void mma_tile(const T* As, const T* Bs, int arow, int brow, in
 // WM x WN x WK wavefronts, each FM x FN MFMA blocks of 32x32.  With WK > 1 the WK wavefronts that share
 // an output sub-tile each multiply a WK-th of every k-tile's depth and their accumulators are added
 // through LDS before the epilogue: small output tiles (many workgroups for GEMMs with few rows) that
-// still keep four wavefronts busy.
-template <typename T, int PASS, bool VECMODE, int WM, int WN, int FM, int FN, int BK_, int WK = 1>
+// still keep four wavefronts busy.  NBUF = 2 stores the next k-tile into a second LDS buffer while the current
+// one is multiplied; NBUF = 1 has one buffer and a second barrier per k-tile instead, which lets twice as many
+// workgroups share a CU: for GEMMs whose k-loop is a handful of tiles, where what hides the load latency is
+// other workgroups and not this one's own pipeline.
+template <typename T, int PASS, bool VECMODE, int WM, int WN, int FM, int FN, int BK_, int WK = 1, int NBUF = 2>
 __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
   static_assert(WM * WN * WK == 4, "four wavefronts");
   static_assert(WK == 1 || sizeof(T) == 4, "the k split over wavefronts is for the fp32 epilogue only");
@@ -426,8 +429,8 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
   constexpr int BK = BK_, STRIDE = BK + Cfg<T>::PAD;
   constexpr int KW = BK / WK;  // depth of a k-tile one wavefront multiplies
   constexpr int TILE = (BM + BN) * STRIDE;
-  static_assert((WK - 1) * FM * FN * 16 * 64 * 4 <= 2 * TILE * (int)sizeof(T), "accumulators must fit in the tile buffers");
-  __shared__ __attribute__((aligned(16))) T smem[2 * TILE];
+  static_assert((WK - 1) * FM * FN * 16 * 64 * 4 <= NBUF * TILE * (int)sizeof(T), "accumulators must fit in the tile buffers");
+  __shared__ __attribute__((aligned(16))) T smem[NBUF * TILE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // consecutive workgroup ids land on different XCDs; give each XCD a contiguous run of
@@ -461,16 +464,17 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
     lb.store(smem + BM * STRIDE, tid);
     __syncthreads();
     for (int kt = kt0; kt < kt1; ++kt) {
-      const int cur = (kt - kt0) & 1;
+      const int cur = NBUF == 2 ? (kt - kt0) & 1 : 0, nxt = NBUF == 2 ? cur ^ 1 : 0;
       const bool more = kt + 1 < kt1;
       if (more) {
         la.load(a);
         lb.load(a);
       }
       mma_tile<T, FM, FN, STRIDE, KW>(smem + cur * TILE + koff, smem + cur * TILE + BM * STRIDE + koff, arow, brow, lane, acc);
+      if (NBUF == 1) __syncthreads();  // everyone is done reading the only buffer
       if (more) {
-        la.store(smem + (cur ^ 1) * TILE, tid);
-        lb.store(smem + (cur ^ 1) * TILE + BM * STRIDE, tid);
+        la.store(smem + nxt * TILE, tid);
+        lb.store(smem + nxt * TILE + BM * STRIDE, tid);
       }
       __syncthreads();
     }
@@ -485,16 +489,17 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
     lb.store(smem + BM * STRIDE, tid);
     __syncthreads();
     for (int kt = kt0; kt < kt1; ++kt) {
-      const int cur = (kt - kt0) & 1;
+      const int cur = NBUF == 2 ? (kt - kt0) & 1 : 0, nxt = NBUF == 2 ? cur ^ 1 : 0;
       const bool more = kt + 1 < kt1;
       if (more) {
         la.load(a, tid);
         lb.load(a, tid);
       }
       mma_tile<T, FM, FN, STRIDE, KW>(smem + cur * TILE + koff, smem + cur * TILE + BM * STRIDE + koff, arow, brow, lane, acc);
+      if (NBUF == 1) __syncthreads();  // everyone is done reading the only buffer
       if (more) {
-        la.store(smem + (cur ^ 1) * TILE, tid);
-        lb.store(smem + (cur ^ 1) * TILE + BM * STRIDE, tid);
+        la.store(smem + nxt * TILE, tid);
+        lb.store(smem + nxt * TILE + BM * STRIDE, tid);
       }
       __syncthreads();
     }
@@ -532,7 +537,7 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
     // 16-bit outputs with channel counts that are multiples of 8: stage the fp32 tile in LDS (the k-loop's buffers are free now) so that each
     // lane then writes 8 adjacent outputs (16 bytes) and a wavefront writes whole rows of the tile
     constexpr int CS = BN + 4;  // row stride in floats: rows 4 banks apart, conflict-free column writes
-    static_assert(BM * CS * 4 <= 2 * TILE * (int)sizeof(T), "C tile must fit in the staging buffers");
+    static_assert(BM * CS * 4 <= NBUF * TILE * (int)sizeof(T), "C tile must fit in the staging buffers");
     float* cs = reinterpret_cast<float*>(smem);
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -770,11 +775,12 @@ void f32_tile(int Mg, int Ng, long long Kg, bool splits_k, int& BM, int& BN) {
 // workgroup; 128x128 keeps 16
 int f32_bk(int BM, int BN) { return (BM == 128 && BN == 128) ? 16 : (BN == 32 && BM <= 64) ? 64 : 32; }
 
-template <typename T, int PASS, int WM, int WN, int FM, int FN, int BK, int WK = 1> void launch_shape(const Args& a, dim3 grid, hipStream_t st) {
+template <typename T, int PASS, int WM, int WN, int FM, int FN, int BK, int WK = 1, int NBUF = 2>
+void launch_shape(const Args& a, dim3 grid, hipStream_t st) {
   if (vec_ok<T>(a.g))
-    hipLaunchKernelGGL((igemm_kernel<T, PASS, true, WM, WN, FM, FN, BK, WK>), grid, dim3(NT), 0, st, a);
+    hipLaunchKernelGGL((igemm_kernel<T, PASS, true, WM, WN, FM, FN, BK, WK, NBUF>), grid, dim3(NT), 0, st, a);
   else
-    hipLaunchKernelGGL((igemm_kernel<T, PASS, false, WM, WN, FM, FN, BK, WK>), grid, dim3(NT), 0, st, a);
+    hipLaunchKernelGGL((igemm_kernel<T, PASS, false, WM, WN, FM, FN, BK, WK, NBUF>), grid, dim3(NT), 0, st, a);
 }
 
 // a.tiles_m / a.tiles_n / a.nk must come from fill_tiles with the tile this picks: 128x128 for bf16,
@@ -790,7 +796,7 @@ template <typename T, int PASS> int launch(Args& a, int splits, hipStream_t st) 
     else if (BM == 64 && BN == 32) launch_shape<T, PASS, 2, 1, 1, 1, 64, 2>(a, grid, st);
     else if (BM == 32 && BN == 32) launch_shape<T, PASS, 1, 1, 1, 1, 64, 4>(a, grid, st);
     else if (BM == 128 && BN == 64) launch_shape<T, PASS, 2, 2, 2, 1, 32>(a, grid, st);
-    else if (BM == 128 && BN == 32) launch_shape<T, PASS, 4, 1, 1, 1, 32>(a, grid, st);
+    else if (BM == 128 && BN == 32) launch_shape<T, PASS, 4, 1, 1, 1, 32, 1, 1>(a, grid, st);
     else if (BM == 64 && BN == 128) launch_shape<T, PASS, 2, 2, 1, 2, 32>(a, grid, st);
     else launch_shape<T, PASS, 2, 2, 1, 1, 32>(a, grid, st);
   } else {
