@@ -147,16 +147,19 @@ def main():
     torch.cuda.synchronize()
     prof = B.s4tf_profile_collect()
     B.s4tf_profile_enable(False)
+    # a pair of events also sees the dispatch of the kernel between them; a kernel trace does not
+    bracket_ms = max(B.s4tf_profile_bracket_overhead(None, 64), 0.0)
     shapes = nets.tensor_shapes(net)
     flops = conv_flops(net, shapes)
     classes = {}
     for name, (ms, cnt) in prof.items():
+        ms = max(ms - cnt * bracket_ms, 0.0)
         classes[name] = {"ms_per_step": ms / prof_steps, "launches_per_step": cnt / prof_steps}
         if flops.get(name):
             classes[name]["tflops"] = flops[name] / (ms / prof_steps * 1e-3) / 1e12
     nbytes = class_bytes(net, shapes, nets.param_count(wl["params"]))
     for name, b in nbytes.items():
-        if b and name in classes:
+        if b and name in classes and classes[name]["ms_per_step"] > 0:
             classes[name]["hbm_tbps"] = b / (classes[name]["ms_per_step"] * 1e-3) / 1e12
             classes[name]["hbm_frac"] = classes[name]["hbm_tbps"] / HBM_PEAK_TBPS
     dom = max(classes, key=lambda k: classes[k]["ms_per_step"])
@@ -197,6 +200,7 @@ def main():
                    "params": nets.param_count(wl["params"]), "loss_after": round(loss, 5)},
         "roofline": roofline, "cpu_baseline": cpu,
         "mfma_util_convs": None if mfma_util is None else round(mfma_util, 4),
+        "event_pair_overhead_us": round(bracket_ms * 1e3, 3),
         "kernel_classes": {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in sorted(classes.items())},
     }
     print(json.dumps(out))

@@ -256,6 +256,13 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
 #define S4TF_PROF_CLASSES 16
 int s4tf_profile_enable(int on);
 int s4tf_profile_collect(double* ms, int64_t* launches);
+/* What one such pair of events adds to the kernel between them: the mean elapsed time, in
+ * milliseconds, of `reps` (1..4096) pairs around a one-wavefront kernel that waits 20 us on
+ * the device's real-time counter, less those 20 us, on `stream` (a device stream handle as
+ * void*, NULL = the default stream), written to *ms_per_pair (host).  Synchronises the
+ * stream.  A kernel trace sees a kernel's execution only; the events also see its dispatch,
+ * so elapsed - this is what compares with a trace. */
+int s4tf_profile_bracket_overhead(void* stream, int reps, double* ms_per_pair);
 const char* s4tf_profile_class_name(int cls);
 
 #ifdef __cplusplus

@@ -102,6 +102,7 @@ def lib():
     L.s4tf_train_step.argtypes = [P(NetDesc), P(Params), P(Batch), c_f32]
     L.s4tf_profile_enable.argtypes = [ctypes.c_int]
     L.s4tf_profile_collect.argtypes = [P(ctypes.c_double), P(ctypes.c_int64)]
+    L.s4tf_profile_bracket_overhead.argtypes = [ctypes.c_void_p, ctypes.c_int, P(ctypes.c_double)]
     L.s4tf_profile_class_name.restype = ctypes.c_char_p
     L.s4tf_profile_class_name.argtypes = [ctypes.c_int]
     for name in ("s4tf_conv2d_fwd", "s4tf_conv2d_vjp", "s4tf_bn_relu_fwd", "s4tf_bn_relu_vjp", "s4tf_pool2d_fwd",
@@ -231,6 +232,12 @@ def s4tf_train_step(net_desc, params, batch, lr):
 
 def s4tf_profile_enable(on):
     _check(lib().s4tf_profile_enable(1 if on else 0))
+
+
+def s4tf_profile_bracket_overhead(stream=None, reps=256):
+    ms = ctypes.c_double(0.0)
+    _check(lib().s4tf_profile_bracket_overhead(stream, int(reps), ctypes.byref(ms)))
+    return ms.value
 
 
 def s4tf_profile_collect():

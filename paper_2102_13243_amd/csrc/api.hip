@@ -390,6 +390,16 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
   return S4TF_OK;
 }
 
+// What s4tf_profile_bracket_overhead brackets: one wavefront that waits until the constant-rate (100 MHz)
+// real-time counter has advanced by `ticks`; the iteration cap ends it whatever the counter does.
+__global__ void prof_spin_kernel(unsigned long long ticks) {
+  const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+  for (int i = 0; i < (1 << 20); ++i) {
+    if (__builtin_amdgcn_s_memrealtime() - t0 >= ticks) break;
+    __builtin_amdgcn_s_sleep(4);
+  }
+}
+
 }  // namespace s4tf
 
 using namespace s4tf;
@@ -814,6 +824,37 @@ int s4tf_profile_collect(double* ms, int64_t* launches) {
     (void)hipEventDestroy(r.e1);
   }
   g_prof->clear();
+  return rc;
+}
+int s4tf_profile_bracket_overhead(void* stream, int reps, double* ms_per_pair) {
+  clear_error();
+  if (!ms_per_pair) return fail(S4TF_ERR_NULL, "ms_per_pair is NULL");
+  if (reps < 1 || reps > 4096) return fail(S4TF_ERR_SHAPE, "reps must be in 1..4096");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const unsigned long long kSpinTicks = 2000;  // 20 us: the length of a typical kernel of the step
+  std::vector<hipEvent_t> ev(2 * (size_t)reps, nullptr);
+  int rc = S4TF_OK;
+  for (hipEvent_t& e : ev)
+    if (hipEventCreate(&e) != hipSuccess) { rc = fail(S4TF_ERR_DEVICE, "profile: event create failed"); break; }
+  if (rc == S4TF_OK) {
+    hipLaunchKernelGGL(s4tf::prof_spin_kernel, dim3(1), dim3(64), 0, st, kSpinTicks);  // first launch: loads the code
+    (void)hipStreamSynchronize(st);
+    for (int i = 0; i < reps; ++i) {
+      (void)hipEventRecord(ev[2 * i], st);
+      hipLaunchKernelGGL(s4tf::prof_spin_kernel, dim3(1), dim3(64), 0, st, kSpinTicks);
+      (void)hipEventRecord(ev[2 * i + 1], st);
+    }
+    double sum = 0.0;
+    if (hipStreamSynchronize(st) != hipSuccess) rc = fail(S4TF_ERR_DEVICE, "profile: synchronize failed");
+    for (int i = 0; i < reps && rc == S4TF_OK; ++i) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, ev[2 * i], ev[2 * i + 1]) != hipSuccess) rc = fail(S4TF_ERR_DEVICE, "profile: event read failed");
+      sum += (double)t;
+    }
+    if (rc == S4TF_OK) *ms_per_pair = sum / reps - (double)kSpinTicks * 1e-5;  // 100 MHz: 1e-5 ms per tick
+  }
+  for (hipEvent_t e : ev)
+    if (e) (void)hipEventDestroy(e);
   return rc;
 }
 const char* s4tf_profile_class_name(int cls) {
