@@ -128,13 +128,17 @@ int s4tf_conv2d_vjp(const s4tf_conv_desc* d, const void* x, const void* w, const
  * vjp:  dz = dy*act'(y);  dresidual (+)= dz;  dbeta = sum dz;  dgamma = sum dz*xhat;
  *       dx = gamma*invstd*(dz - dbeta/m - xhat*dgamma/m)
  * residual / dresidual may be NULL.  gamma, beta, statistics and their gradients are fp32
- * arrays of c elements.  y may be NULL in vjp when act is NONE. */
+ * arrays of c elements.  y may be NULL in vjp when act is NONE.
+ * beta in vjp is optional (NULL: act'(y) is read off y).  Give it only if the forward call had
+ * no residual: with beta given and dresidual NULL the pullback rebuilds z = gamma*xhat + beta
+ * from x with the forward pass's own arithmetic, takes act' from it and does not read y (which
+ * may then be NULL): one tensor less to fetch. */
 size_t s4tf_bn_relu_workspace_bytes(const s4tf_bn_desc* d);
 int s4tf_bn_relu_fwd(const s4tf_bn_desc* d, const void* x, const void* residual, const float* gamma,
                      const float* beta, void* y, float* save_mean, float* save_invstd,
                      void* workspace, size_t workspace_bytes, void* stream);
 int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const float* gamma,
-                     const float* save_mean, const float* save_invstd, const void* dy, void* dx,
+                     const float* beta, const float* save_mean, const float* save_invstd, const void* dy, void* dx,
                      void* dresidual, float* dgamma, float* dbeta, void* workspace,
                      size_t workspace_bytes, void* stream);
 

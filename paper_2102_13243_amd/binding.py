@@ -87,7 +87,7 @@ def lib():
     L.s4tf_conv2d_fwd.argtypes = [P(ConvDesc), c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     L.s4tf_conv2d_vjp.argtypes = [P(ConvDesc), c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     L.s4tf_bn_relu_fwd.argtypes = [P(BnDesc), c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
-    L.s4tf_bn_relu_vjp.argtypes = [P(BnDesc)] + [c_vp] * 11 + [c_sz, c_vp]
+    L.s4tf_bn_relu_vjp.argtypes = [P(BnDesc)] + [c_vp] * 12 + [c_sz, c_vp]
     L.s4tf_pool2d_fwd.argtypes = [P(PoolDesc), c_vp, c_vp, c_vp]
     L.s4tf_pool2d_vjp.argtypes = [P(PoolDesc), c_vp, c_vp, c_vp, c_vp]
     L.s4tf_pool_dense_xent_fwd_vjp.argtypes = [P(HeadDesc)] + [c_vp] * 10 + [c_sz, c_vp]
@@ -172,9 +172,9 @@ def s4tf_bn_relu_fwd(d, x, residual, gamma, beta, y, save_mean, save_invstd, wor
                                   _p(save_invstd), _p(workspace), _nbytes(workspace), _stream(stream)))
 
 
-def s4tf_bn_relu_vjp(d, x, y, gamma, save_mean, save_invstd, dy, dx, dresidual, dgamma, dbeta, workspace,
+def s4tf_bn_relu_vjp(d, x, y, gamma, beta, save_mean, save_invstd, dy, dx, dresidual, dgamma, dbeta, workspace,
                      stream=None):
-    _check(lib().s4tf_bn_relu_vjp(ctypes.byref(d), _p(x), _p(y), _p(gamma), _p(save_mean), _p(save_invstd), _p(dy),
+    _check(lib().s4tf_bn_relu_vjp(ctypes.byref(d), _p(x), _p(y), _p(gamma), _p(beta), _p(save_mean), _p(save_invstd), _p(dy),
                                   _p(dx), _p(dresidual), _p(dgamma), _p(dbeta), _p(workspace), _nbytes(workspace),
                                   _stream(stream)))
 

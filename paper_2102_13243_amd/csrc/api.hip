@@ -466,7 +466,7 @@ int s4tf_bn_relu_fwd(const s4tf_bn_desc* d, const void* x, const void* residual,
   CHECK(check_ws(workspace, workspace_bytes, bn_workspace((size_t)d->n * d->h * d->w, d->c)));
   return bn_fwd(*d, x, residual, gamma, beta, y, save_mean, save_invstd, workspace, (hipStream_t)stream);
 }
-int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const float* gamma,
+int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const float* gamma, const float* beta,
                      const float* save_mean, const float* save_invstd, const void* dy, void* dx, void* dresidual,
                      float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
@@ -474,9 +474,10 @@ int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const 
   CHECK(need(x, "x")); CHECK(need(gamma, "gamma")); CHECK(need(save_mean, "save_mean"));
   CHECK(need(save_invstd, "save_invstd")); CHECK(need(dy, "dy")); CHECK(need(dx, "dx"));
   CHECK(need(dgamma, "dgamma")); CHECK(need(dbeta, "dbeta")); CHECK(opt(dresidual, "dresidual"));
-  if (d->act != S4TF_ACT_NONE) CHECK(need(y, "y (required when act != NONE)"));
+  CHECK(opt(beta, "beta"));
+  if (d->act != S4TF_ACT_NONE && !(beta && !dresidual)) CHECK(need(y, "y (required when act != NONE, unless beta is given and there is no residual)"));
   CHECK(check_ws(workspace, workspace_bytes, bn_workspace((size_t)d->n * d->h * d->w, d->c)));
-  return bn_vjp(*d, x, y, gamma, save_mean, save_invstd, dy, dx, dresidual, dgamma, dbeta, workspace, (hipStream_t)stream);
+  return bn_vjp(*d, x, y, gamma, beta, save_mean, save_invstd, dy, dx, dresidual, dgamma, dbeta, workspace, (hipStream_t)stream);
 }
 
 // ---- pooling ----------------------------------------------------------------------------------------------
@@ -770,7 +771,9 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         float* stats = reinterpret_cast<float*>(ws + pl.stat_off[i]);
         void* dxb = grad_ptr(src);  // src != 0: checked when the net was planned
         void* dres = rsrc > 0 ? grad_ptr(rsrc) : nullptr;
-        CHECK(bn_vjp(d, act_ptr(src), out_ptr(i + 1), params->master + pl.poff[2 * i], stats, stats + in.c, dy, dxb,
+        // no residual in the forward pass: the pullback rebuilds the activation mask from x and skips y
+        const float* beta = op.res < 0 ? params->master + pl.poff[2 * i + 1] : nullptr;
+        CHECK(bn_vjp(d, act_ptr(src), out_ptr(i + 1), params->master + pl.poff[2 * i], beta, stats, stats + in.c, dy, dxb,
                      dres, params->grad + pl.poff[2 * i], params->grad + pl.poff[2 * i + 1], scr, s));
         written[src] = 1;
         if (rsrc > 0) written[rsrc] = 1;

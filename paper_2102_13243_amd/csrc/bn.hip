@@ -222,6 +222,16 @@ __global__ __launch_bounds__(1024) void bn_stats_from_runs_kernel(const float* _
   invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
 }
 
+// z of the forward pass.  The pullback recomputes it (and from it the activation mask) with the same
+// operations in the same order, so the two agree bit for bit.
+__device__ inline float bn_z(float x, float mu, float sc, float be) { return fmaf(x - mu, sc, be); }
+// act'(y) read off z: y = round_T(act(z)) is positive exactly when z is (rounding keeps the sign; an fp32
+// z below 2^-133 that bf16 flushes to zero is the one exception, and harmless), and below 6 exactly when z
+// is below 6 (fp32) or below 6 - 2^-6, the tie that rounds up to 6 (bf16).
+template <typename T> __device__ inline float remask_hi(int act) {
+  return act == S4TF_ACT_RELU6 ? (sizeof(T) == 2 ? 5.984375f : 6.f) : __builtin_inff();
+}
+
 template <typename T, int V>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
@@ -251,7 +261,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
                 Pack<T, V> o;
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
-                  float z = (xv[u].get(e) - mu[e]) * sc[e] + be[e];
+                  float z = bn_z(xv[u].get(e), mu[e], sc[e], be[e]);
                   if (res) z += rv[u].get(e);
                   o.set(e, act_apply(z, act));
                 }
@@ -265,25 +275,32 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
 // one group of UNROLL pixels, are fp32 (their rounding errors are independent and average out; what
 // must not happen is a long running sum in fp32), which keeps the double work to two additions per
 // channel and group.
-template <typename T, int V>
-__global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict__ x, const T* __restrict__ y,
-                                                            const T* __restrict__ dy, const float* __restrict__ mean,
-                                                            const float* __restrict__ invstd, double* __restrict__ part,
-                                                            long long M, int C, int cvb, long long per, int act) {
+template <typename T, int V, bool REMASK>
+__device__ __forceinline__ void bn_vjp_reduce_body(const T* __restrict__ x, const T* __restrict__ y,
+                                                   const T* __restrict__ dy, const float* __restrict__ mean,
+                                                   const float* __restrict__ invstd, const float* __restrict__ gamma,
+                                                   const float* __restrict__ beta, double* __restrict__ part,
+                                                   long long M, int C, int cvb, long long per, int act) {
   extern __shared__ double redd[];
   const int CV = C / V, pl_count = blockDim.x / cvb;
   const int cvl = threadIdx.x % cvb, pl = threadIdx.x / cvb;
   const int cv = blockIdx.x * cvb + cvl;
   const bool live = cv < CV;
   const int c = live ? cv * V : 0;
+  // beta given (the forward pass had no residual): the activation mask comes from z recomputed out of x,
+  // and y is not read
+  constexpr bool remask = REMASK;  // a template parameter: each version holds only the registers it needs
+  const float mhi = remask_hi<T>(act);
   double acc[2 * V];
-  float grp[2 * V], mu[V], is[V];
+  float grp[2 * V], mu[V], is[V], sc[V], be[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) {
     acc[e] = acc[V + e] = 0.0;
     grp[e] = grp[V + e] = 0.f;
     mu[e] = mean[c + e];
     is[e] = invstd[c + e];
+    sc[e] = remask ? gamma[c + e] * is[e] : 0.f;
+    be[e] = remask ? beta[c + e] : 0.f;
   }
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
   if (live) {
@@ -292,7 +309,7 @@ __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict_
                 [&](long long m, int u) {
                   xv[u] = ldp<T, V>(x + m * C + c);
                   dv[u] = ldp<T, V>(dy + m * C + c);
-                  if (act != S4TF_ACT_NONE) yv[u] = ldp<T, V>(y + m * C + c);
+                  if (act != S4TF_ACT_NONE && !remask) yv[u] = ldp<T, V>(y + m * C + c);
                 },
                 [&](long long, int u) {
 #pragma unroll
@@ -303,7 +320,12 @@ __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict_
                       grp[e] = grp[V + e] = 0.f;
                     }
                     float dz = dv[u].get(e);
-                    if (act != S4TF_ACT_NONE) dz *= act_mask(yv[u].get(e), act);
+                    if (remask) {
+                      const float z = bn_z(xv[u].get(e), mu[e], sc[e], be[e]);
+                      dz = (z > 0.f && z < mhi) ? dz : 0.f;
+                    } else if (act != S4TF_ACT_NONE) {
+                      dz *= act_mask(yv[u].get(e), act);
+                    }
                     grp[e] += dz;
                     grp[V + e] += dz * ((xv[u].get(e) - mu[e]) * is[e]);
                   }
@@ -322,6 +344,17 @@ __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(const T* __restrict_
   }
 }
 
+#define BN_VJP_REDUCE_ARGS                                                                                           \
+  const T *__restrict__ x, const T *__restrict__ y, const T *__restrict__ dy, const float *__restrict__ mean,        \
+      const float *__restrict__ invstd, const float *__restrict__ gamma, const float *__restrict__ beta,             \
+      double *__restrict__ part, long long M, int C, int cvb, long long per, int act
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_reduce_kernel(BN_VJP_REDUCE_ARGS) {
+  bn_vjp_reduce_body<T, V, false>(x, y, dy, mean, invstd, gamma, beta, part, M, C, cvb, per, act);
+}
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_reduce_remask_kernel(BN_VJP_REDUCE_ARGS) {
+  bn_vjp_reduce_body<T, V, true>(x, y, dy, mean, invstd, gamma, beta, part, M, C, cvb, per, act);
+}
+
 __global__ __launch_bounds__(FIN_THREADS) void bn_vjp_finalize_kernel(const double* __restrict__ part, int chunks, int C,
                                                                       float* __restrict__ dgamma, float* __restrict__ dbeta) {
   __shared__ double sh[FIN_THREADS / 64][2][8];
@@ -333,10 +366,11 @@ __global__ __launch_bounds__(FIN_THREADS) void bn_vjp_finalize_kernel(const doub
   dgamma[c] = (float)s2;
 }
 
-template <typename T, int V>
-__global__ __launch_bounds__(256) void bn_vjp_apply_kernel(const T* __restrict__ x, const T* __restrict__ y,
+template <typename T, int V, bool REMASK>
+__device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const T* __restrict__ y,
                                                            const T* __restrict__ dy, const float* __restrict__ gamma,
                                                            const float* __restrict__ mean, const float* __restrict__ invstd,
+                                                           const float* __restrict__ beta,
                                                            const float* __restrict__ dgamma, const float* __restrict__ dbeta,
                                                            T* __restrict__ dx, T* dres, int acc_dres, long long M, int C,
                                                            int cvb, long long per, int act) {
@@ -346,14 +380,19 @@ __global__ __launch_bounds__(256) void bn_vjp_apply_kernel(const T* __restrict__
   if (cv >= CV) return;
   const int c = cv * V;
   const float invM = 1.0f / (float)M;
-  float mu[V], is[V], gs[V], mb[V], mg[V];
+  constexpr bool remask = REMASK;  // as in the reduction kernel
+  const float mhi = remask_hi<T>(act);
+  // dx = gs*(dz - dbeta/M - xhat*dgamma/M) with xhat = (x - mu)*invstd, as  gs*dz - (x - mu)*a2 - a0:
+  // four values per channel (five with beta) instead of five (six)
+  float mu[V], gs[V], a0[V], a2[V], be[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) {
+    const float is = invstd[c + e];
     mu[e] = mean[c + e];
-    is[e] = invstd[c + e];
-    gs[e] = gamma[c + e] * is[e];
-    mb[e] = dbeta[c + e] * invM;
-    mg[e] = dgamma[c + e] * invM;
+    be[e] = remask ? beta[c + e] : 0.f;
+    gs[e] = gamma[c + e] * is;
+    a0[e] = gs[e] * (dbeta[c + e] * invM);
+    a2[e] = gs[e] * (is * (dgamma[c + e] * invM));
   }
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
   Pack<T, V> xv[UNROLL], dv[UNROLL], yv[UNROLL], ov[UNROLL];
@@ -361,7 +400,7 @@ __global__ __launch_bounds__(256) void bn_vjp_apply_kernel(const T* __restrict__
               [&](long long m, int u) {
                 xv[u] = ldp<T, V>(x + m * C + c);
                 dv[u] = ldp<T, V>(dy + m * C + c);
-                if (act != S4TF_ACT_NONE) yv[u] = ldp<T, V>(y + m * C + c);
+                if (act != S4TF_ACT_NONE && !remask) yv[u] = ldp<T, V>(y + m * C + c);
                 if (dres && acc_dres) ov[u] = ldp<T, V>(dres + m * C + c);
               },
               [&](long long m, int u) {
@@ -369,13 +408,30 @@ __global__ __launch_bounds__(256) void bn_vjp_apply_kernel(const T* __restrict__
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                   float dz = dv[u].get(e);
-                  if (act != S4TF_ACT_NONE) dz *= act_mask(yv[u].get(e), act);
-                  o.set(e, gs[e] * (dz - mb[e] - (xv[u].get(e) - mu[e]) * is[e] * mg[e]));
+                  const float xc = xv[u].get(e) - mu[e];
+                  if (remask) {
+                    const float z = fmaf(xc, gs[e], be[e]);  // bn_z, sharing the subtraction
+                    dz = (z > 0.f && z < mhi) ? dz : 0.f;
+                  } else if (act != S4TF_ACT_NONE) {
+                    dz *= act_mask(yv[u].get(e), act);
+                  }
+                  o.set(e, fmaf(gs[e], dz, -fmaf(xc, a2[e], a0[e])));
                   if (dres) r.set(e, acc_dres ? ov[u].get(e) + dz : dz);
                 }
                 stp<T, V>(dx + m * C + c, o);
                 if (dres) stp<T, V>(dres + m * C + c, r);
               });
+}
+#define BN_VJP_APPLY_ARGS                                                                                            \
+  const T *__restrict__ x, const T *__restrict__ y, const T *__restrict__ dy, const float *__restrict__ gamma,       \
+      const float *__restrict__ mean, const float *__restrict__ invstd, const float *__restrict__ beta,              \
+      const float *__restrict__ dgamma, const float *__restrict__ dbeta, T *__restrict__ dx, T *dres, int acc_dres,  \
+      long long M, int C, int cvb, long long per, int act
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply_kernel(BN_VJP_APPLY_ARGS) {
+  bn_vjp_apply_body<T, V, false>(x, y, dy, gamma, mean, invstd, beta, dgamma, dbeta, dx, dres, acc_dres, M, C, cvb, per, act);
+}
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply_remask_kernel(BN_VJP_APPLY_ARGS) {
+  bn_vjp_apply_body<T, V, true>(x, y, dy, gamma, mean, invstd, beta, dgamma, dbeta, dx, dres, acc_dres, M, C, cvb, per, act);
 }
 
 }  // namespace
@@ -433,26 +489,35 @@ int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* g
   return launch_status("bn_apply");
 }
 
-int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* mean,
+int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* beta, const float* mean,
            const float* invstd, const void* dy, void* dx, void* dres, float* dgamma, float* dbeta,
            void* ws, hipStream_t st) {
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
+  if (dres || d.act == S4TF_ACT_NONE) beta = nullptr;  // with a residual z cannot be rebuilt from x alone
   const Plan pr = make_plan((size_t)M, C, d.dtype, 512, UNROLL);  // measured over the ResNet-50 shapes: 512 blocks beat 1024 and 256
   const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, UNROLL);
   double* part = static_cast<double*>(ws);
   int rc;
   {
     ProfScope ps(PC_BN_VJP_REDUCE, st);
-    BN_LAUNCH(bn_vjp_reduce_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(double), (const T*)x, (const T*)y, (const T*)dy,
-              mean, invstd, part, M, C, pr.cvb, pr.per, d.act);
+    if (beta)
+      BN_LAUNCH(bn_vjp_reduce_remask_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(double), (const T*)x, (const T*)y,
+                (const T*)dy, mean, invstd, gamma, beta, part, M, C, pr.cvb, pr.per, d.act);
+    else
+      BN_LAUNCH(bn_vjp_reduce_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(double), (const T*)x, (const T*)y,
+                (const T*)dy, mean, invstd, gamma, beta, part, M, C, pr.cvb, pr.per, d.act);
     if ((rc = launch_status("bn_vjp_reduce")) != S4TF_OK) return rc;
     hipLaunchKernelGGL(bn_vjp_finalize_kernel, dim3((C + 7) / 8), dim3(FIN_THREADS), 0, st, part, pr.chunks, C, dgamma, dbeta);
     if ((rc = launch_status("bn_vjp_finalize")) != S4TF_OK) return rc;
   }
   ProfScope ps(PC_BN_VJP_APPLY, st);
-  BN_LAUNCH(bn_vjp_apply_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, dgamma, dbeta, (T*)dx,
-            (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);
+  if (beta)
+    BN_LAUNCH(bn_vjp_apply_remask_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, beta, dgamma, dbeta,
+              (T*)dx, (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);
+  else
+    BN_LAUNCH(bn_vjp_apply_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, beta, dgamma, dbeta,
+              (T*)dx, (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);
   return launch_status("bn_vjp_apply");
 }
 

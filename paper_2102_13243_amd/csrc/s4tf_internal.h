@@ -124,7 +124,7 @@ size_t bn_workspace(size_t M, int C);
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
            void* y, float* mean, float* invstd, void* ws, hipStream_t st, const float* stats_part = nullptr,
            int stats_rows = 0);
-int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* mean,
+int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* beta, const float* mean,
            const float* invstd, const void* dy, void* dx, void* dres, float* dgamma, float* dbeta,
            void* ws, hipStream_t st);
 

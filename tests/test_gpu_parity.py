@@ -211,17 +211,26 @@ def test_bn_relu_fwd_and_vjp(shape, act, use_res, bf16):
     dx_ref, dres_ref, dg_ref, db_ref = orc.bn_act_vjp(x, y_ref, gamma, mean_ref, invstd_ref, dy, act, use_res)
     dx, dres = empty(shape, bf16), (empty(shape, bf16) if use_res else None)
     dg, db = empty((c,)), empty((c,))
-    B.s4tf_bn_relu_vjp(d, xd, to_dev(y_ref, bf16), gd, to_dev(mean_ref), to_dev(invstd_ref), to_dev(dy, bf16), dx, dres,
-                       dg, db, wsp)
+    B.s4tf_bn_relu_vjp(d, xd, to_dev(y_ref, bf16), gd, None, to_dev(mean_ref), to_dev(invstd_ref), to_dev(dy, bf16), dx,
+                       dres, dg, db, wsp)
     assert rel_l2(to_host(dg), dg_ref) < 1e-4
     assert rel_l2(to_host(db), db_ref) < 1e-4
     assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < (6e-3 if bf16 else 5e-5)
+    if not use_res and act != "none":
+        # beta given, no residual: the activation mask is rebuilt from x with the statistics the GPU's own
+        # forward pass saved, y is not read (NULL).  An element whose z rounds to the other side of 0 (or 6)
+        # than the oracle's may differ; the tolerances are those of the first call.
+        dx.fill_(float("nan"))
+        B.s4tf_bn_relu_vjp(d, xd, None, gd, bd, mean, invstd, to_dev(dy, bf16), dx, None, dg, db, wsp)
+        assert rel_l2(to_host(dg), dg_ref) < 1e-4
+        assert rel_l2(to_host(db), db_ref) < 1e-4
+        assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < (6e-3 if bf16 else 5e-5)
     if use_res:
         assert rel_l2(to_host(dres), dres_ref) == 0.0
         d.accumulate_dres = 1
         base = grid(RNG.standard_normal(shape), bf16)
         dres2 = to_dev(base, bf16)
-        B.s4tf_bn_relu_vjp(d, xd, to_dev(y_ref, bf16), gd, to_dev(mean_ref), to_dev(invstd_ref), to_dev(dy, bf16), dx,
+        B.s4tf_bn_relu_vjp(d, xd, to_dev(y_ref, bf16), gd, None, to_dev(mean_ref), to_dev(invstd_ref), to_dev(dy, bf16), dx,
                            dres2, dg, db, wsp)
         want = base + dres_ref
         assert rel_l2(to_host(dres2), orc.round_bf16(want) if bf16 else want) < (4e-3 if bf16 else 1e-6)
