@@ -250,6 +250,8 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
     sc[e] = gamma[c + e] * invstd[c + e];
     be[e] = beta[c + e];
   }
+  const float act_lo = act == S4TF_ACT_NONE ? -__builtin_inff() : 0.f;
+  const float act_hi = act == S4TF_ACT_RELU6 ? 6.f : __builtin_inff();
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
   Pack<T, V> xv[UNROLL], rv[UNROLL];
   walk_pixels(p0 + pl, p1, pl_count,
@@ -258,14 +260,14 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
                 if (res) rv[u] = ldp<T, V>(res + m * C + c);
               },
               [&](long long m, int u) {
-                Pack<T, V> o;
+                float o[V];
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                   float z = bn_z(xv[u].get(e), mu[e], sc[e], be[e]);
                   if (res) z += rv[u].get(e);
-                  o.set(e, act_apply(z, act));
+                  o[e] = fminf(fmaxf(z, act_lo), act_hi);  // the activation as a clamp: no branch per element
                 }
-                stp<T, V>(y + m * C + c, o);
+                stp<T, V>(y + m * C + c, pack_of<T, V>(o));
               });
 }
 
@@ -291,6 +293,7 @@ __device__ __forceinline__ void bn_vjp_reduce_body(const T* __restrict__ x, cons
   // and y is not read
   constexpr bool remask = REMASK;  // a template parameter: each version holds only the registers it needs
   const float mhi = remask_hi<T>(act);
+  const float yhi = act == S4TF_ACT_RELU6 ? 6.f : __builtin_inff();  // act'(y) = 1 on (0, yhi); y is finite
   double acc[2 * V];
   float grp[2 * V], mu[V], is[V], sc[V], be[V];
 #pragma unroll
@@ -324,7 +327,8 @@ __device__ __forceinline__ void bn_vjp_reduce_body(const T* __restrict__ x, cons
                       const float z = bn_z(xv[u].get(e), mu[e], sc[e], be[e]);
                       dz = (z > 0.f && z < mhi) ? dz : 0.f;
                     } else if (act != S4TF_ACT_NONE) {
-                      dz *= act_mask(yv[u].get(e), act);
+                      const float yy = yv[u].get(e);
+                      dz = (yy > 0.f && yy < yhi) ? dz : 0.f;
                     }
                     grp[e] += dz;
                     grp[V + e] += dz * ((xv[u].get(e) - mu[e]) * is[e]);
@@ -382,6 +386,7 @@ __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const
   const float invM = 1.0f / (float)M;
   constexpr bool remask = REMASK;  // as in the reduction kernel
   const float mhi = remask_hi<T>(act);
+  const float yhi = act == S4TF_ACT_RELU6 ? 6.f : __builtin_inff();  // act'(y) = 1 on (0, yhi); y is finite
   // dx = gs*(dz - dbeta/M - xhat*dgamma/M) with xhat = (x - mu)*invstd, as  gs*dz - (x - mu)*a2 - a0:
   // four values per channel (five with beta) instead of five (six)
   float mu[V], gs[V], a0[V], a2[V], be[V];
@@ -404,7 +409,7 @@ __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const
                 if (dres && acc_dres) ov[u] = ldp<T, V>(dres + m * C + c);
               },
               [&](long long m, int u) {
-                Pack<T, V> o, r;
+                float o[V], r[V];
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                   float dz = dv[u].get(e);
@@ -413,13 +418,14 @@ __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const
                     const float z = fmaf(xc, gs[e], be[e]);  // bn_z, sharing the subtraction
                     dz = (z > 0.f && z < mhi) ? dz : 0.f;
                   } else if (act != S4TF_ACT_NONE) {
-                    dz *= act_mask(yv[u].get(e), act);
+                    const float yy = yv[u].get(e);
+                    dz = (yy > 0.f && yy < yhi) ? dz : 0.f;
                   }
-                  o.set(e, fmaf(gs[e], dz, -fmaf(xc, a2[e], a0[e])));
-                  if (dres) r.set(e, acc_dres ? ov[u].get(e) + dz : dz);
+                  o[e] = fmaf(gs[e], dz, -fmaf(xc, a2[e], a0[e]));
+                  r[e] = (dres && acc_dres) ? ov[u].get(e) + dz : dz;
                 }
-                stp<T, V>(dx + m * C + c, o);
-                if (dres) stp<T, V>(dres + m * C + c, r);
+                stp<T, V>(dx + m * C + c, pack_of<T, V>(o));
+                if (dres) stp<T, V>(dres + m * C + c, pack_of<T, V>(r));
               });
 }
 #define BN_VJP_APPLY_ARGS                                                                                            \

@@ -34,6 +34,28 @@ template <> struct Pack<bf16_t, 1> {
   __device__ void set(int, float v) { d = f32_to_bf16(v); }
 };
 
+// A whole vector from V fp32 values: the bf16 x8 case converts pairs with one instruction each
+// (v_cvt_pk_bf16_f32) instead of inserting eight separately converted halves.
+template <typename T, int V> __device__ inline Pack<T, V> pack_of(const float (&v)[V]) {
+  Pack<T, V> o;
+#pragma unroll
+  for (int e = 0; e < V; ++e) o.set(e, v[e]);
+  return o;
+}
+template <> __device__ inline Pack<bf16_t, 8> pack_of<bf16_t, 8>(const float (&v)[8]) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  Pack<bf16_t, 8> o;
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f32x2_t f = {v[2 * i], v[2 * i + 1]};
+    w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+  }
+  o.d = make_uint4(w[0], w[1], w[2], w[3]);
+  return o;
+}
+
 template <typename T, int V> __device__ inline Pack<T, V> ldp(const T* p) {
   return *reinterpret_cast<const Pack<T, V>*>(p);
 }
