@@ -273,10 +273,12 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
           if (ws > wscratch) wscratch = ws;
         }
         // a BatchNorm right behind takes its statistics from partial sums the convolution leaves in scratch
-        if (i + 1 < nops && net->ops[i + 1].kind == S4TF_OP_BN && net->ops[i + 1].in == i + 1 && op.groups == 1) {
-          ws = igemm_fwd_stats_bytes(g);
-          if (ws > scratch) scratch = ws;
-        }
+        // (right behind on its stream: a projection shortcut's two ops, which run on the second stream, may lie between)
+        for (int k = i + 1; k < nops && k <= i + 3 && op.groups == 1; ++k)
+          if (net->ops[k].kind == S4TF_OP_BN && net->ops[k].in == i + 1) {
+            ws = igemm_fwd_stats_bytes(g);
+            if (ws > scratch) scratch = ws;
+          }
         break;
       }
       case S4TF_OP_BN: {
@@ -644,7 +646,13 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
       case S4TF_OP_CONV: {
         s4tf_conv_desc d = conv_desc(i, 0);
         const float* bias = op.has_bias ? params->master + pl.poff[2 * i + 1] : nullptr;
-        const bool bn_next = net->ops[i + 1].kind == S4TF_OP_BN && net->ops[i + 1].in == i + 1 && op.groups == 1;
+        // the next op on this stream is a BatchNorm of this convolution's output (ops of a side branch, which run on
+        // the other stream with a scratch of their own, may lie between in op order)
+        bool bn_next = false;
+        for (int k = i + 1; k < nops && k <= i + 3 && op.groups == 1; ++k) {
+          if (net->ops[k].kind == S4TF_OP_BN && net->ops[k].in == i + 1) { bn_next = true; break; }
+          if (pl.branch_of[k] < 0 || pl.branch_of[i] >= 0) break;
+        }
         float* sp = bn_next ? static_cast<float*>(scr) : nullptr;
         int* sr = bn_next ? &stats_rows : nullptr;
         if (pl.pad_c[i]) {  // zero-padded channels contribute nothing: same result, 16-byte loaders
@@ -678,10 +686,7 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   };
   int stats_rows = 0;  // > 0: the previous op, a convolution, left partial statistics of its output in scratch
   for (int i = 0; i < nops - 1; ++i) {
-    if (pl.branch_of[i] >= 0) {  // ran on the side stream when its input appeared
-      stats_rows = 0;
-      continue;
-    }
+    if (pl.branch_of[i] >= 0) continue;  // ran on the side stream when its input appeared (and left `scratch` alone)
     if (pl.needs[i] >= 0) CHECK(wait_side(branch_event[pl.needs[i]]));
     CHECK(fwd_op(i, st, scratch, stats_rows));
     if (pl.start_after[i] >= 0) {  // the input of a side branch is queued: the branch starts beside what follows
