@@ -65,8 +65,10 @@ def class_bytes(net, shapes, n_params):
     """Algorithmic HBM bytes of one step for the classes that no contraction bounds: every operand a
     kernel class must read or write once, at the storage width (es) of activations; fp32 elsewhere.
       bn_apply       x -> y (+ residual read)                       (2 + res) * numel * es
-      bn_vjp_reduce  x, dy (+ y for the activation mask)            (2 + act) * numel * es
-      bn_vjp_apply   x, dy (+ y) -> dx (+ residual cotangent)       (3 + act + res) * numel * es
+      bn_vjp_reduce  x, dy (+ y for the activation mask, read only    (2 + act*res) * numel * es
+                     when there is a residual: without one the
+                     mask is rebuilt from x)
+      bn_vjp_apply   x, dy (+ y) -> dx (+ residual cotangent)       (3 + act*res + res) * numel * es
       dwconv_fwd     x -> y;  dwconv_dgrad  dy -> dx;  dwconv_wgrad  x, dy      (in + out) * es each
       sgd            p, v, g read, p, v written (fp32) (+ the bf16 working copy written)
     """
@@ -79,8 +81,8 @@ def class_bytes(net, shapes, n_params):
             res = 1 if op["res"] >= 0 else 0
             act = 0 if op["act"] == "none" else 1
             out["bn_apply"] += (2 + res) * numel * es
-            out["bn_vjp_reduce"] += (2 + act) * numel * es
-            out["bn_vjp_apply"] += (3 + act + res) * numel * es
+            out["bn_vjp_reduce"] += (2 + act * res) * numel * es
+            out["bn_vjp_apply"] += (3 + act * res + res) * numel * es
         elif op["kind"] == "conv" and op["groups"] > 1:
             io = (numel + float(np.prod(shapes[i + 1]))) * es
             out["dwconv_fwd"] += io
