@@ -207,8 +207,8 @@ struct NetPlan {
   std::vector<TensorPlan> t;
   std::vector<int64_t> poff, psize;  // 2 per op
   std::vector<size_t> stat_off;      // per op: save_mean/invstd (BN)
-  // a bf16 convolution on the batch itself whose channel count is not a multiple of 8 runs on
-  // zero-padded copies of the batch and of its filter (pad_c channels), see train step
+  // a convolution on the batch itself whose channel count is not a multiple of 8 (bf16) or 4 (fp32) runs
+  // on zero-padded copies of the batch and of its filter (pad_c channels), see train step
   std::vector<int> pad_c;
   std::vector<size_t> xpad_off, wpad_off, dwpad_off;
   size_t param_count;
@@ -262,8 +262,12 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
         out.h = g.P; out.w = g.Q; out.c = op.k;
         add_param(i, 0, (size_t)op.r * op.s * (in.c / op.groups) * op.k);
         if (op.has_bias) add_param(i, 1, (size_t)op.k);
-        if (net->dtype == S4TF_BF16 && in.root == 0 && op.groups == 1 && in.c % 8 != 0) {
-          pl.pad_c[i] = (int)align_up((size_t)in.c, 8);
+        // channel count of the batch not a multiple of the 16-byte loaders' vector (8 bf16, 4 fp32): padded copies
+        const int vecw = net->dtype == S4TF_BF16 ? 8 : 4;
+        // (fp32: only where the convolution is big enough to repay the two copy launches)
+        if (in.root == 0 && op.groups == 1 && in.c % vecw != 0 &&
+            (net->dtype == S4TF_BF16 || (op.k % 4 == 0 && (long long)g.N * g.P * g.Q >= 32768))) {
+          pl.pad_c[i] = (int)align_up((size_t)in.c, vecw);
           g.C = pl.pad_c[i];
         }
         size_t ws = op.groups == 1 ? igemm_wgrad_workspace(g, net->dtype) : dwconv_wgrad_workspace(g);
