@@ -206,7 +206,7 @@ struct TensorPlan {
 struct NetPlan {
   std::vector<TensorPlan> t;
   std::vector<int64_t> poff, psize;  // 2 per op
-  std::vector<size_t> stat_off;      // per op: save_mean/invstd (BN)
+  std::vector<size_t> stat_off;      // per op: save_mean/invstd (BN); max pool: the saved window positions (one byte per output)
   // a convolution on the batch itself whose channel count is not a multiple of 8 (bf16) or 4 (fp32) runs
   // on zero-padded copies of the batch and of its filter (pad_c channels), see train step
   std::vector<int> pad_c;
@@ -355,6 +355,9 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
     if (net->ops[i].kind == S4TF_OP_BN) {
       pl.stat_off[i] = off;
       off += align_up((size_t)2 * pl.t[net->ops[i].in].c * sizeof(float), 256);
+    } else if (net->ops[i].kind == S4TF_OP_MAXPOOL3S2) {
+      pl.stat_off[i] = off;
+      off += align_up(pl.t[i + 1].elems, 256);
     }
   for (int i = 0; i < nops; ++i)
     if (pl.pad_c[i]) {
@@ -680,7 +683,8 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
       case S4TF_OP_AVGPOOL2:
       case S4TF_OP_MAXPOOL3S2: {
         s4tf_pool_desc d = {in.n, in.h, in.w, in.c, op.kind == S4TF_OP_AVGPOOL2 ? S4TF_POOL_AVG2 : S4TF_POOL_MAX3S2, dt, 0};
-        CHECK(pool_fwd(d, act_ptr(op.in), out_ptr(i + 1), s));
+        unsigned char* pos = pool_saves_positions(d) ? reinterpret_cast<unsigned char*>(ws + pl.stat_off[i]) : nullptr;
+        CHECK(pool_fwd(d, act_ptr(op.in), out_ptr(i + 1), s, pos));
         break;
       }
       default:
@@ -793,7 +797,8 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         if (!want_dx) break;
         s4tf_pool_desc d = {in.n, in.h, in.w, in.c, op.kind == S4TF_OP_AVGPOOL2 ? S4TF_POOL_AVG2 : S4TF_POOL_MAX3S2, dt,
                             written[src] ? 1 : 0};
-        CHECK(pool_vjp(d, act_ptr(src), dy, grad_ptr(src), s));
+        const unsigned char* pos = pool_saves_positions(d) ? reinterpret_cast<const unsigned char*>(ws + pl.stat_off[i]) : nullptr;
+        CHECK(pool_vjp(d, act_ptr(src), dy, grad_ptr(src), s, pos));
         written[src] = 1;
         break;
       }

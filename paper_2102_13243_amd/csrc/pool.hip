@@ -50,8 +50,11 @@ __global__ void avgpool2_vjp_kernel(const T* __restrict__ dy, T* __restrict__ dx
 
 // ---- 3x3 / 2 pad 1 max pool --------------------------------------------------------------------
 // one thread per V channels of one output pixel
+// idx (optional): per output element one byte, the window position 3*r + s of the first maximum in row-major
+// window order: what the pullback needs to know, so that it does not have to scan the windows again
 template <typename T, int V>
-__global__ void maxpool3s2_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int N, int H, int W, int C) {
+__global__ void maxpool3s2_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, unsigned char* __restrict__ idx, int N,
+                                      int H, int W, int C) {
   const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1, CV = C / V;
   const long long total = (long long)N * P * Q * CV;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
@@ -61,8 +64,9 @@ __global__ void maxpool3s2_fwd_kernel(const T* __restrict__ x, T* __restrict__ y
     t /= Q;
     int p = (int)(t % P), n = (int)(t / P);
     float best[V];
+    unsigned bi[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) best[v] = -INFINITY;
+    for (int v = 0; v < V; ++v) { best[v] = -INFINITY; bi[v] = 0; }
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
       int h = 2 * p + r - 1;
@@ -73,13 +77,28 @@ __global__ void maxpool3s2_fwd_kernel(const T* __restrict__ x, T* __restrict__ y
         if (w < 0 || w >= W) continue;
         Pack<T, V> xv = ldp<T, V>(x + (((long long)n * H + h) * W + w) * C + c);
 #pragma unroll
-        for (int v = 0; v < V; ++v) best[v] = fmaxf(best[v], xv.get(v));
+        for (int v = 0; v < V; ++v) {
+          const float e = xv.get(v);
+          if (e > best[v]) { best[v] = e; bi[v] = r * 3 + s; }  // strict: the first maximum keeps the title
+        }
       }
     }
     Pack<T, V> o;
 #pragma unroll
     for (int v = 0; v < V; ++v) o.set(v, best[v]);
     stp<T, V>(y + i * V, o);
+    if (idx) {
+      if constexpr (V % 4 == 0) {  // V bytes in one store
+        uint32_t w4[V / 4];
+#pragma unroll
+        for (int k = 0; k < V / 4; ++k) w4[k] = bi[4 * k] | (bi[4 * k + 1] << 8) | (bi[4 * k + 2] << 16) | (bi[4 * k + 3] << 24);
+        if constexpr (V == 8) *reinterpret_cast<uint2*>(idx + i * V) = make_uint2(w4[0], w4[1]);
+        else *reinterpret_cast<uint32_t*>(idx + i * V) = w4[0];
+      } else {
+#pragma unroll
+        for (int v = 0; v < V; ++v) idx[i * V + v] = (unsigned char)bi[v];
+      }
+    }
   }
 }
 // gather form of the pullback: input (h,w) receives dy of every window in which it is the first
@@ -179,6 +198,79 @@ __global__ __launch_bounds__(256) void maxpool3s2_vjp_kernel(const T* __restrict
 #pragma unroll
         for (int v = 0; v < V; ++v) o.set(v, g[dh][dw][v]);
         stp<T, V>(dst, o);
+      }
+    }
+  }
+}
+
+// The same pullback from the positions the forward pass saved: a 2x2 cell of input pixels reads, for each of
+// its four windows, dy and the window's winner, and keeps dy where the winner is one of its own pixels.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void maxpool3s2_vjp_idx_kernel(const unsigned char* __restrict__ idx, const T* __restrict__ dy,
+                                                                 T* __restrict__ dx, int N, int H, int W, int C, int accumulate) {
+  static_assert(V == 4 || V == 8, "one 4- or 8-byte load of positions per window");
+  const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1, CV = C / V;
+  const int HA = (H + 1) / 2, WB = (W + 1) / 2;
+  const long long total = (long long)N * HA * WB * CV;
+  for (long long id = (long long)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += (long long)gridDim.x * blockDim.x) {
+    const int c = (int)(id % CV) * V;
+    long long t = id / CV;
+    const int b = (int)(t % WB);
+    t /= WB;
+    const int a = (int)(t % HA), n = (int)(t / HA);
+    float g[2][2][V];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int v = 0; v < V; ++v) g[u >> 1][u & 1][v] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int p = a + i;
+      if (p >= P) continue;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int q = b + j;
+        if (q >= Q) continue;
+        const long long o = (((long long)n * P + p) * Q + q) * C + c;
+        const Pack<T, V> dv = ldp<T, V>(dy + o);
+        uint32_t w4[2] = {0u, 0u};
+        if constexpr (V == 8) {
+          const uint2 u2 = *reinterpret_cast<const uint2*>(idx + o);
+          w4[0] = u2.x; w4[1] = u2.y;
+        } else {
+          w4[0] = *reinterpret_cast<const uint32_t*>(idx + o);
+        }
+        // cell pixel (dh, dw) sits at window position (dh + 1 - 2i, dw + 1 - 2j)
+#pragma unroll
+        for (int dh = 0; dh < 2; ++dh) {
+          const int r = dh + 1 - 2 * i;
+          if (r < 0) continue;
+#pragma unroll
+          for (int dw = 0; dw < 2; ++dw) {
+            const int s2 = dw + 1 - 2 * j;
+            if (s2 < 0) continue;
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+              if (((w4[v >> 2] >> (8 * (v & 3))) & 0xffu) == (unsigned)(r * 3 + s2)) g[dh][dw][v] += dv.get(v);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int dh = 0; dh < 2; ++dh) {
+      const int h = 2 * a + dh;
+      if (h >= H) continue;
+#pragma unroll
+      for (int dw = 0; dw < 2; ++dw) {
+        const int w = 2 * b + dw;
+        if (w >= W) continue;
+        T* dst = dx + (((long long)n * H + h) * W + w) * C + c;
+        if (accumulate) {
+          const Pack<T, V> old = ldp<T, V>(dst);
+#pragma unroll
+          for (int v = 0; v < V; ++v) g[dh][dw][v] += old.get(v);
+        }
+        stp<T, V>(dst, pack_of<T, V>(g[dh][dw]));
       }
     }
   }
@@ -298,7 +390,11 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ param, flo
 
 }  // namespace
 
-int pool_fwd(const s4tf_pool_desc& d, const void* x, void* y, hipStream_t st) {
+bool pool_saves_positions(const s4tf_pool_desc& d) {
+  return d.kind == S4TF_POOL_MAX3S2 && d.c % (d.dtype == S4TF_BF16 ? 8 : 4) == 0;
+}
+
+int pool_fwd(const s4tf_pool_desc& d, const void* x, void* y, hipStream_t st, unsigned char* idx) {
   ProfScope ps(PC_POOL, st);
   const bool avg = d.kind == S4TF_POOL_AVG2;
   const int P = avg ? d.h / 2 : (d.h - 1) / 2 + 1, Q = avg ? d.w / 2 : (d.w - 1) / 2 + 1;
@@ -309,19 +405,29 @@ int pool_fwd(const s4tf_pool_desc& d, const void* x, void* y, hipStream_t st) {
   if (d.dtype == S4TF_BF16) {
     typedef bf16_t T;
     if (avg) hipLaunchKernelGGL(avgpool2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
-    else if (vec) hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 8>), vgrid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
-    else hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 1>), grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+    else if (vec) hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 8>), vgrid, block, 0, st, (const T*)x, (T*)y, idx, d.n, d.h, d.w, d.c);
+    else hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 1>), grid, block, 0, st, (const T*)x, (T*)y, (unsigned char*)nullptr, d.n, d.h, d.w, d.c);
   } else {
     typedef float T;
     if (avg) hipLaunchKernelGGL(avgpool2_fwd_kernel<T>, grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
-    else if (vec) hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 4>), vgrid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
-    else hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 1>), grid, block, 0, st, (const T*)x, (T*)y, d.n, d.h, d.w, d.c);
+    else if (vec) hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 4>), vgrid, block, 0, st, (const T*)x, (T*)y, idx, d.n, d.h, d.w, d.c);
+    else hipLaunchKernelGGL((maxpool3s2_fwd_kernel<T, 1>), grid, block, 0, st, (const T*)x, (T*)y, (unsigned char*)nullptr, d.n, d.h, d.w, d.c);
   }
   return launch_status("pool_fwd");
 }
 
-int pool_vjp(const s4tf_pool_desc& d, const void* x, const void* dy, void* dx, hipStream_t st) {
+int pool_vjp(const s4tf_pool_desc& d, const void* x, const void* dy, void* dx, hipStream_t st, const unsigned char* idx) {
   ProfScope ps(PC_POOL, st);
+  if (idx && pool_saves_positions(d) && aligned16(x) && aligned16(dy) && aligned16(dx)) {  // the forward pass's own conditions
+    const long long cells = (long long)d.n * ((d.h + 1) / 2) * ((d.w + 1) / 2);
+    if (d.dtype == S4TF_BF16)
+      hipLaunchKernelGGL((maxpool3s2_vjp_idx_kernel<bf16_t, 8>), dim3(blocks_for(cells * d.c / 8)), dim3(256), 0, st, idx, (const bf16_t*)dy,
+                         (bf16_t*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+    else
+      hipLaunchKernelGGL((maxpool3s2_vjp_idx_kernel<float, 4>), dim3(blocks_for(cells * d.c / 4)), dim3(256), 0, st, idx, (const float*)dy,
+                         (float*)dx, d.n, d.h, d.w, d.c, d.accumulate_dx);
+    return launch_status("pool_vjp");
+  }
   const bool avg = d.kind == S4TF_POOL_AVG2;
   dim3 grid(blocks_for((long long)d.n * d.h * d.w * d.c)), block(256);
   const int V = d.dtype == S4TF_BF16 ? 8 : 4;

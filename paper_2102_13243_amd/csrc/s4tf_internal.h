@@ -129,8 +129,11 @@ int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gam
            void* ws, hipStream_t st);
 
 // pools
-int pool_fwd(const s4tf_pool_desc& d, const void* x, void* y, hipStream_t st);
-int pool_vjp(const s4tf_pool_desc& d, const void* x, const void* dy, void* dx, hipStream_t st);
+// idx (optional, max pool with a channel count that the 16-byte kernels take: pool_saves_positions): one byte per
+// output element, written by pool_fwd, the window position of the maximum; pool_vjp given it does not read x
+bool pool_saves_positions(const s4tf_pool_desc& d);
+int pool_fwd(const s4tf_pool_desc& d, const void* x, void* y, hipStream_t st, unsigned char* idx = nullptr);
+int pool_vjp(const s4tf_pool_desc& d, const void* x, const void* dy, void* dx, hipStream_t st, const unsigned char* idx = nullptr);
 
 // head
 size_t head_workspace(const s4tf_head_desc& d);
