@@ -728,6 +728,40 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   std::vector<int> grad_event(nops + 1, -1);   // per tensor: pending side-stream write of its cotangent
   std::vector<char> branch_forked(pl.branch_conv.size(), 0);
   int early_join = -1;  // event slot: everything the side stream got before the first op's filter gradient
+  // Filter (and bias) gradient of convolution j, on the second stream.
+  auto param_grads = [&](int j) -> int {
+    const s4tf_op& cv = net->ops[j];
+    const TensorPlan& cin = pl.t[cv.in];
+    s4tf_conv_desc d = conv_desc(j, 0);
+    void* dyj = grad_ptr(j + 1);
+    float* dbias = cv.has_bias ? params->grad + pl.poff[2 * j + 1] : nullptr;
+    if (pl.pad_c[j]) {  // the batch has no cotangent; the filter gradient of the padded channels is dropped
+      d.c = pl.pad_c[j];
+      float* dwp = reinterpret_cast<float*>(ws + pl.dwpad_off[j]);
+      CHECK(conv_param_grads_impl(d, ws + pl.xpad_off[j], dyj, dwp, dbias, wscratch, pl.wscratch_bytes, side->stream));
+      return unpad_channels_f32(dwp, params->grad + pl.poff[2 * j], (long long)cv.r * cv.s, cin.c, pl.pad_c[j], cv.k, side->stream);
+    }
+    return conv_param_grads_impl(d, act_ptr(pl.t[cv.in].root), dyj, params->grad + pl.poff[2 * j], dbias, wscratch,
+                                 pl.wscratch_bytes, side->stream);
+  };
+  // A hand-over to the second stream costs the first one 5-7 us (measured: an event record between two kernels
+  // 2.9 us, more once another stream waits on it), so the filter gradients of the main branch are handed over
+  // FORK_EVERY convolutions at a time: cotangent buffers are never reused, so a filter gradient can start any
+  // time after its convolution's output cotangent is final.
+  constexpr int FORK_EVERY = 3;
+  std::vector<int> pending;
+  auto flush_pending = [&]() -> int {
+    if (pending.empty()) return S4TF_OK;
+    CHECK(fork());
+    for (int j : pending) {
+      // The first op's filter gradient is the last piece of side-stream work: mark the point before it, so that
+      // the optimizer can start on every other parameter while that gradient is still being computed.
+      if (j == 0 && pl.poff[0] == 0) CHECK(side_done(early_join));
+      CHECK(param_grads(j));
+    }
+    pending.clear();
+    return S4TF_OK;
+  };
   for (int i = nops - 2; i >= 0; --i) {
     const s4tf_op& op = net->ops[i];
     const TensorPlan& in = pl.t[op.in];
@@ -760,21 +794,12 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
           written[src] = 1;
           if (on_side) CHECK(side_done(grad_event[src]));
         }
-        if (!on_side) CHECK(fork());
-        // The filter gradient queued next is the last piece of side-stream work when this is the first op
-        // of the net: mark the point before it, so that the optimizer can start on every other parameter
-        // while that gradient is still being computed.
-        if (i == 0 && pl.poff[0] == 0) CHECK(side_done(early_join));
-        float* dbias = op.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr;
-        if (pl.pad_c[i]) {  // the batch has no cotangent; the filter gradient of the padded channels is dropped
-          d.c = pl.pad_c[i];
-          float* dwp = reinterpret_cast<float*>(ws + pl.dwpad_off[i]);
-          CHECK(conv_param_grads_impl(d, ws + pl.xpad_off[i], dy, dwp, dbias, wscratch, pl.wscratch_bytes, side->stream));
-          CHECK(unpad_channels_f32(dwp, params->grad + pl.poff[2 * i], (long long)op.r * op.s, in.c, pl.pad_c[i], op.k, side->stream));
-          break;
+        if (on_side) {
+          CHECK(param_grads(i));
+        } else {
+          pending.push_back(i);
+          if ((int)pending.size() >= FORK_EVERY || i == 0) CHECK(flush_pending());
         }
-        CHECK(conv_param_grads_impl(d, act_ptr(src), dy, params->grad + pl.poff[2 * i], dbias, wscratch, pl.wscratch_bytes,
-                                    side->stream));
         break;
       }
       case S4TF_OP_BN: {
@@ -806,6 +831,7 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         break;
     }
   }
+  CHECK(flush_pending());
   // ---- optimizer: one launch over the whole arena, once the side stream's gradients are in ----
   if (early_join >= 0) {  // all parameters but the first op's, then, after the join, those
     const s4tf_op& op0 = net->ops[0];  // its parameters lie at the start of the arena, padded to 8 elements each
