@@ -799,7 +799,7 @@ static void launch_tile(Args& a, int splits, hipStream_t st) {
     hipLaunchKernelGGL((igemm_dma_kernel<PASS, (PASS == PASS_WGRAD ? 2 : 1), 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
   else if (blocks <= 256 && a.nk_per_split >= 8)
     hipLaunchKernelGGL((igemm_dma_kernel<PASS, DEEP1, 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
-  else if (blocks <= 512 && DEEP2 == 3)
+  else if (blocks <= 1024 && DEEP2 == 3)  // measured: up to two rounds of workgroups gain from the third stage, longer grids lose
     hipLaunchKernelGGL((igemm_dma_kernel<PASS, DEEP2, 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
   else
     hipLaunchKernelGGL((igemm_dma_kernel<PASS, 2, 2, 2, FM, FN>), grid, dim3(NT), 0, st, a);
