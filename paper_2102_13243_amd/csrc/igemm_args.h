@@ -44,17 +44,13 @@ struct Args {
 // Workgroup -> (output tile, split of the reduction axis).  Workgroup ids are dealt round-robin to the
 // XCDs, each with an L2 of its own.  The (split, tile) pairs, split-major, are cut into one contiguous
 // run per XCD: neighbours in a run share an operand row-block or, across tiles of one split, the same
-// slice of both operands.  With at least as many splits as XCDs, whole splits are dealt round-robin
-// instead (all tiles of a split on one XCD).  Either way every XCD gets work even when there are fewer
-// tiles than XCDs.  False: this workgroup has nothing to do.
+// slice of both operands, and every XCD gets the same number of workgroups (to within one), also when
+// there are fewer tiles than XCDs.  (Dealing whole splits to the XCDs, as an earlier version did, left
+// some XCDs with one workgroup more than their CUs hold at once: with 5 tiles x 102 splits six XCDs got
+// 65 workgroups for 64 slots, and the one straggler doubled the kernel's duration.)
 __device__ inline bool block_to_tile(const Args& a, int bid, int& logical, int& split) {
   const int x = bid % NUM_XCD, j = bid / NUM_XCD;
   const int tiles = a.tiles_m * a.tiles_n;
-  if (a.splits >= NUM_XCD) {
-    split = (j / tiles) * NUM_XCD + x;
-    logical = j % tiles;
-    return split < a.splits;
-  }
   const int units = tiles * a.splits, per_xcd = (units + NUM_XCD - 1) / NUM_XCD;
   const int u = x * per_xcd + j;
   split = u / tiles;
@@ -66,7 +62,6 @@ __device__ inline bool block_to_tile(const Args& a, int& logical, int& split) {
 }
 inline unsigned grid_blocks(const Args& a) {
   const int tiles = a.tiles_m * a.tiles_n;
-  if (a.splits >= NUM_XCD) return (unsigned)(NUM_XCD * ((a.splits + NUM_XCD - 1) / NUM_XCD) * tiles);
   return (unsigned)(NUM_XCD * ((tiles * a.splits + NUM_XCD - 1) / NUM_XCD));
 }
 
