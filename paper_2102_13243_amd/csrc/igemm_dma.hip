@@ -154,16 +154,26 @@ template <int ROWS, bool DGRAD> struct Gather {
         loff[i] = (((n * g.P + sdiv(hp0, g.stride)) * g.Q + sdiv(wp0, g.stride)) * g.K + kco) * 2;
         // tap (rr, ss) reads dy at ((hp0 - rr)/stride, (wp0 - ss)/stride) when both divide exactly and
         // fall inside the output: the valid set is (valid rr) x (valid ss)
-        uint64_t cols = 0;
-        for (int ss = 0; ss < g.S; ++ss) {
-          const int wp = wp0 - ss, wq = sdiv(wp, g.stride);
-          if (wp >= 0 && wq * g.stride == wp && wq < g.Q) cols |= 1ull << ss;
-        }
-        if (rv)
-          for (int rr = 0; rr < g.R; ++rr) {
-            const int hp = hp0 - rr, hq = sdiv(hp, g.stride);
-            if (hp >= 0 && hq * g.stride == hp && hq < g.P) m |= cols << (rr * g.S);
+        if (g.stride == 1) {
+          // every tap divides: the valid ones form a rectangle, rows [rlo, rhi) x columns [slo, shi), as in
+          // the forward pass (0 <= hp0 - rr < P and 0 <= wp0 - ss < Q)
+          const int rlo = max(0, hp0 - g.P + 1), rhi = min(g.R, hp0 + 1), slo = max(0, wp0 - g.Q + 1), shi = min(g.S, wp0 + 1);
+          if (rv && shi > slo) {
+            const uint64_t cols = ((1ull << shi) - 1) & ~((1ull << slo) - 1);
+            for (int rr = rlo; rr < rhi; ++rr) m |= cols << (rr * g.S);
           }
+        } else {
+          uint64_t cols = 0;
+          for (int ss = 0; ss < g.S; ++ss) {
+            const int wp = wp0 - ss, wq = sdiv(wp, g.stride);
+            if (wp >= 0 && wq * g.stride == wp && wq < g.Q) cols |= 1ull << ss;
+          }
+          if (rv)
+            for (int rr = 0; rr < g.R; ++rr) {
+              const int hp = hp0 - rr, hq = sdiv(hp, g.stride);
+              if (hp >= 0 && hq * g.stride == hp && hq < g.P) m |= cols << (rr * g.S);
+            }
+        }
       }
       mask[i] = m;
     }
