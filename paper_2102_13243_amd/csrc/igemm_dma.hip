@@ -103,6 +103,14 @@ template <int ROWS, bool DGRAD> struct Gather {
   bool uniform_tap;
   // x / stride for x >= 0
   __device__ static int sdiv(int x, int stride) { return stride == 1 ? x : stride == 2 ? (x >> 1) : x / stride; }
+  // Taps (rr, ss) with rlo <= rr < rhi, slo <= ss < shi as a bit mask (bit rr*S + ss), without a loop: the column
+  // bits, below 2^S, times the bits rr*S of the wanted rows (R*S <= 64, so the products do not overlap or carry)
+  __device__ static uint64_t rect_mask(uint64_t rowbits, int rlo, int rhi, int slo, int shi, int S) {
+    const uint64_t cols = ((1ull << shi) - 1) & ~((1ull << slo) - 1);
+    const int hb = rhi * S, lb = rlo * S;
+    const uint64_t rows = rowbits & (hb >= 64 ? ~0ull : ((1ull << hb) - 1)) & ~((1ull << lb) - 1);
+    return cols * rows;
+  }
   // tap part of the offset, in elements
   __device__ int tap_off(int rr, int ss, const ConvGeom& g) const {
     return DGRAD ? -(sdiv(rr, g.stride) * g.Q + sdiv(ss, g.stride)) * g.K : (rr * g.W + ss) * g.C;
@@ -116,6 +124,8 @@ template <int ROWS, bool DGRAD> struct Gather {
     invS = g.S == 1 ? 65536 : g.S == 3 ? 21846 : (65536 + g.S - 1) / g.S;
     uniform_tap = (CH % BK) == 0;
     logC = log2_of(CH);
+    uint64_t rowbits = 0;  // bit rr*S for every filter row rr (uniform)
+    for (int rr = 0; rr < g.R; ++rr) rowbits |= 1ull << (rr * g.S);
 #pragma unroll
     for (int i = 0; i < TL::UPW; ++i) {
       const int row = row0 + TL::row_of(wave, i, lane);
@@ -133,10 +143,7 @@ template <int ROWS, bool DGRAD> struct Gather {
         loff[i] = (((n * g.H + h0) * g.W + w0) * g.C + kco) * 2;
         // the taps inside the image form a rectangle: rows [rlo, rhi) x columns [slo, shi)
         const int rlo = max(0, -h0), rhi = min(g.R, g.H - h0), slo = max(0, -w0), shi = min(g.S, g.W - w0);
-        if (rv && shi > slo) {
-          const uint64_t cols = ((1ull << shi) - 1) & ~((1ull << slo) - 1);
-          for (int rr = rlo; rr < rhi; ++rr) m |= cols << (rr * g.S);
-        }
+        if (rv && shi > slo && rhi > rlo) m = rect_mask(rowbits, rlo, rhi, slo, shi, g.S);
       } else {
         int n, h, w;
         if (a.cls) {  // rows run over the pixels (stride*hc + ph, stride*wc + pw) only
@@ -158,10 +165,7 @@ template <int ROWS, bool DGRAD> struct Gather {
           // every tap divides: the valid ones form a rectangle, rows [rlo, rhi) x columns [slo, shi), as in
           // the forward pass (0 <= hp0 - rr < P and 0 <= wp0 - ss < Q)
           const int rlo = max(0, hp0 - g.P + 1), rhi = min(g.R, hp0 + 1), slo = max(0, wp0 - g.Q + 1), shi = min(g.S, wp0 + 1);
-          if (rv && shi > slo) {
-            const uint64_t cols = ((1ull << shi) - 1) & ~((1ull << slo) - 1);
-            for (int rr = rlo; rr < rhi; ++rr) m |= cols << (rr * g.S);
-          }
+          if (rv && shi > slo && rhi > rlo) m = rect_mask(rowbits, rlo, rhi, slo, shi, g.S);
         } else {
           uint64_t cols = 0;
           for (int ss = 0; ss < g.S; ++ss) {
