@@ -772,11 +772,13 @@ bool igemm_dma_ok(int pass, const ConvGeom& g, const Args& a) {
 void igemm_dma_tile(int pass, int Mg, int Ng, int splits, int& BM, int& BN) {
   BM = 128;
   BN = Ng <= 64 ? 64 : 128;
-  if (BN == 64) return;
+  if (BN == 64) return;  // (128x64)
   if (pass == PASS_WGRAD) {
     if (Mg <= 64) BM = 64;
   } else if ((long long)((Mg + 127) / 128) * ((Ng + 127) / 128) * splits < 512) {
     BM = 64;
+    // still fewer workgroups than CUs (the 7x7 layers): 64x64, twice as many again
+    if ((long long)((Mg + 63) / 64) * ((Ng + 127) / 128) * splits < 256) BN = 64;
   }
 }
 
@@ -822,7 +824,8 @@ static void launch_tile(Args& a, int splits, hipStream_t st) {
 template <int PASS> static void launch_pass(Args& a, int splits, hipStream_t st) {
   int BM, BN;
   igemm_dma_tile(PASS, a.Mg, a.Ng, splits, BM, BN);
-  if (BN == 64) launch_tile<PASS, 2, 1>(a, splits, st);
+  if (BN == 64 && BM == 64) launch_tile<PASS, 1, 1>(a, splits, st);
+  else if (BN == 64) launch_tile<PASS, 2, 1>(a, splits, st);
   else if (BM == 64) launch_tile<PASS, 1, 2>(a, splits, st);
   else launch_tile<PASS, 2, 2>(a, splits, st);
 }
