@@ -314,12 +314,21 @@ __global__ __launch_bounds__(256) void colsum_part_kernel(const T* __restrict__ 
   __syncthreads();
   if (rl == 0 && c < cols) part[(long long)blockIdx.y * cols + c] = red[0][cl] + red[1][cl] + red[2][cl] + red[3][cl];
 }
-__global__ __launch_bounds__(64) void colsum_final_kernel(const double* __restrict__ part, int chunks, int cols, float* __restrict__ out) {
-  const int c = blockIdx.x * 64 + threadIdx.x;
-  if (c >= cols) return;
+// second stage: 64 columns x 16 chunk lanes per block; a lane adds every 16th chunk, the 16 lane sums are added in order
+__global__ __launch_bounds__(1024) void colsum_final_kernel(const double* __restrict__ part, int chunks, int cols, float* __restrict__ out) {
+  __shared__ double red[16][64];
+  const int cl = threadIdx.x & 63, zl = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
   double s = 0.0;
-  for (int z = 0; z < chunks; ++z) s += part[(long long)z * cols + c];
-  out[c] = (float)s;
+  if (c < cols)
+    for (int z = zl; z < chunks; z += 16) s += part[(long long)z * cols + c];
+  red[zl][cl] = s;
+  __syncthreads();
+  if (zl == 0 && c < cols) {
+    double t = 0.0;
+    for (int k = 0; k < 16; ++k) t += red[k][cl];
+    out[c] = (float)t;
+  }
 }
 
 // ---- zero padding of one axis: dst[o][c][i] = c < C ? src[o][c][i] : 0 with Cp >= C channels -------
@@ -478,7 +487,7 @@ int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStrea
       hipLaunchKernelGGL(colsum_part_kernel<bf16_t>, dim3(grid.x, chunks), block, 0, st, (const bf16_t*)a, (long long)rows, cols, per, part);
     else
       hipLaunchKernelGGL(colsum_part_kernel<float>, dim3(grid.x, chunks), block, 0, st, (const float*)a, (long long)rows, cols, per, part);
-    hipLaunchKernelGGL(colsum_final_kernel, grid, dim3(64), 0, st, part, chunks, cols, out);
+    hipLaunchKernelGGL(colsum_final_kernel, grid, dim3(1024), 0, st, part, chunks, cols, out);
     return launch_status("colsum");
   }
   if (dtype == S4TF_BF16)
