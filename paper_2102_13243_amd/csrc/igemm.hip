@@ -761,7 +761,7 @@ void f32_tile(int Mg, int Ng, long long Kg, bool splits_k, int& BM, int& BN) {
     if (c64 < c128) BM = 64;
   }
   if (splits_k) return;  // the filter gradient gets its workgroups from splitting the reduction axis
-  if ((long long)Mg * Ng * Kg < (1LL << 25)) return;  // too little work for the tile shape to matter
+  if ((long long)Mg * Ng * Kg < (1LL << 20)) return;  // too little work for the tile shape to matter
   // fewer tiles than CUs: smaller tiles, down to 32x32 (whose four wavefronts split the k-tile's depth)
   const int bm2[3] = {64, 64, 32}, bn2[3] = {64, 32, 32};
   for (int i = 0; i < 3; ++i) {
