@@ -760,7 +760,10 @@ void f32_tile(int Mg, int Ng, long long Kg, bool splits_k, int& BM, int& BN) {
     const float c128 = (float)((Mg + 127) / 128 * 128), c64 = (float)((Mg + 63) / 64 * 64) * 1.15f;
     if (c64 < c128) BM = 64;
   }
-  if (splits_k) return;  // the filter gradient gets its workgroups from splitting the reduction axis
+  if (splits_k) {  // the filter gradient gets its workgroups from splitting the reduction axis
+    if (Mg <= 32) BM = 32;  // few input channels (the first layers of a net): a 32-row tile halves the padding again
+    return;
+  }
   if ((long long)Mg * Ng * Kg < (1LL << 20)) return;  // too little work for the tile shape to matter
   // fewer tiles than CUs: smaller tiles, down to 32x32 (whose four wavefronts split the k-tile's depth)
   const int bm2[3] = {64, 64, 32}, bn2[3] = {64, 32, 32};
@@ -773,7 +776,7 @@ void f32_tile(int Mg, int Ng, long long Kg, bool splits_k, int& BM, int& BN) {
 // k-tile depth of the fp32 kernel: 32 for every tile shape whose two double-buffered operand tiles fit into
 // 64 KB of LDS with it (all but 128x128), which halves the number of load-wait-multiply rounds of a
 // workgroup; 128x128 keeps 16
-int f32_bk(int BM, int BN) { return (BM == 128 && BN == 128) ? 16 : (BN == 32 && BM <= 64) ? 64 : 32; }
+int f32_bk(int BM, int BN) { return (BM == 128 && BN == 128) ? 16 : ((BN == 32 && BM <= 64) || (BM == 32 && BN == 64)) ? 64 : 32; }
 
 template <typename T, int PASS, int WM, int WN, int FM, int FN, int BK, int WK = 1, int NBUF = 2>
 void launch_shape(const Args& a, dim3 grid, hipStream_t st) {
@@ -795,6 +798,8 @@ template <typename T, int PASS> int launch(Args& a, int splits, hipStream_t st) 
     if (BM == 128 && BN == 128) launch_shape<T, PASS, 2, 2, 2, 2, 16>(a, grid, st);
     else if (BM == 64 && BN == 32) launch_shape<T, PASS, 2, 1, 1, 1, 64, 2>(a, grid, st);
     else if (BM == 32 && BN == 32) launch_shape<T, PASS, 1, 1, 1, 1, 64, 4>(a, grid, st);
+    else if (BM == 32 && BN == 64) launch_shape<T, PASS, 1, 2, 1, 1, 64, 2>(a, grid, st);
+    else if (BM == 32 && BN == 128) launch_shape<T, PASS, 1, 4, 1, 1, 32>(a, grid, st);
     else if (BM == 128 && BN == 64) launch_shape<T, PASS, 2, 2, 2, 1, 32>(a, grid, st);
     else if (BM == 128 && BN == 32) launch_shape<T, PASS, 4, 1, 1, 1, 32, 1, 1>(a, grid, st);
     else if (BM == 64 && BN == 128) launch_shape<T, PASS, 2, 2, 1, 2, 32>(a, grid, st);
