@@ -750,6 +750,9 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   // time after its convolution's output cotangent is final.
   constexpr int FORK_EVERY = 3;
   std::vector<int> pending;
+  std::vector<int> convs_before(nops, 0);  // main-branch convolutions with a smaller op index
+  for (int k = 1; k < nops; ++k)
+    convs_before[k] = convs_before[k - 1] + (net->ops[k - 1].kind == S4TF_OP_CONV && pl.branch_of[k - 1] < 0 ? 1 : 0);
   auto flush_pending = [&]() -> int {
     if (pending.empty()) return S4TF_OK;
     CHECK(fork());
@@ -798,7 +801,9 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
           CHECK(param_grads(i));
         } else {
           pending.push_back(i);
-          if ((int)pending.size() >= FORK_EVERY || i == 0) CHECK(flush_pending());
+          // (the last few of the pass one by one: whatever is still queued when the main stream runs out of work
+          // is the tail of the step)
+          if ((int)pending.size() >= FORK_EVERY || convs_before[i] < 6) CHECK(flush_pending());
         }
         break;
       }
