@@ -91,6 +91,42 @@ def class_bytes(net, shapes, n_params):
     return out
 
 
+def ablation(net, wl, steps, warmup):
+    """Eager versus fused (the comparison of the paper's Table 3, on this library's own kernels):
+    the same step, same inputs, dispatched three ways.  Each mode gets fresh parameters."""
+    import torch
+    from paper_2102_13243_amd import binding as B
+    from paper_2102_13243_amd.eager import EagerState
+
+    def timed(st):
+        xd, ld = st.upload_batch(wl["x"], wl["labels"])
+        for _ in range(warmup):
+            st.step(xd, ld)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            st.step(xd, ld)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3, float(st.loss[0].item())
+
+    batch = net["input"][0]
+    out = {"metric": "train step, fused vs op-by-op dispatch", "workload": net["name"], "batch": batch,
+           "dtype": net["dtype"], "steps": steps, "warmup": warmup, "unit": "images/s", "modes": {}}
+    for mode, make in (("fused", lambda: B.TrainState(net, wl["params"], "cuda:0")),
+                       ("eager_async", lambda: EagerState(net, wl["params"], "cuda:0", sync=False)),
+                       ("eager_sync", lambda: EagerState(net, wl["params"], "cuda:0", sync=True))):
+        st = make()
+        ms, loss = timed(st)
+        out["modes"][mode] = {"ms_per_step": round(ms, 4), "images_per_s": round(batch / ms * 1e3, 1),
+                              "loss_after": round(loss, 5)}
+        del st
+        torch.cuda.empty_cache()
+    f = out["modes"]["fused"]["ms_per_step"]
+    out["fused_speedup_over_eager_sync"] = round(out["modes"]["eager_sync"]["ms_per_step"] / f, 3)
+    out["fused_speedup_over_eager_async"] = round(out["modes"]["eager_async"]["ms_per_step"] / f, 3)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +138,10 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="launch only a plain copy kernel of known size (reads and writes 256 MiB, three times): "
                          "the reference reading for the FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--ablation", action="store_true",
+                    help="instead of the benchmark line: time the step of --workload three ways, fused "
+                         "(s4tf_train_step), op by op with asynchronous dispatch, op by op with a host "
+                         "synchronisation after every op (the paper's eager mode), and print one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -125,6 +165,9 @@ def main():
     kw = {"batch": args.batch} if args.batch else {}
     net = nets.CONFIGS[args.workload](**kw)
     wl = nets.make_workload(net)
+    if args.ablation:
+        print(json.dumps(ablation(net, wl, args.steps, args.warmup)))
+        return
     st = B.TrainState(net, wl["params"], "cuda:0")
     xd, ld = st.upload_batch(wl["x"], wl["labels"])
     batch = net["input"][0]

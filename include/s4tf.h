@@ -249,7 +249,11 @@ int s4tf_net_tensor_layout(const s4tf_net_desc* net, int64_t* act_off, int64_t* 
  * step orders it after the work already queued on batch->stream and makes batch->stream
  * wait for it before the update, also when the step fails half way, so in stream order on
  * batch->stream the step is complete (and its workspace reusable) when its last kernel is.
- * Steps on the same device share that second stream. */
+ * Steps on the same device share that second stream.  A net whose convolutions add up to
+ * less than 0.5 GFLOP per forward pass runs on batch->stream alone.  The step allocates no
+ * memory, issues no memset and no synchronisation, so once the second stream exists (after
+ * the first call on the device) a caller may capture a step in a HIP graph of its own:
+ * the second stream is forked from batch->stream and joined back into it inside the call. */
 int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_batch* batch, float lr);
 
 /* ---- measurement hook -------------------------------------------------------------------

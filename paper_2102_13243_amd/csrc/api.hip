@@ -222,6 +222,10 @@ struct NetPlan {
   std::vector<int> branch_of, start_after, needs;
   std::vector<int> branch_conv;         // per pair: its convolution's op index
   size_t sscratch_off;                  // scratch of the side branches (as large as the main scratch)
+  // A step whose convolutions add up to little arithmetic is a chain of kernels of a few microseconds each:
+  // there a hand-over between streams (5-10 us) costs more than the overlap can return, and the whole step
+  // runs on the caller's stream.
+  bool one_stream;
 };
 
 static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
@@ -367,6 +371,13 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
       pl.wpad_off[i] = off; off += align_up((size_t)op.r * op.s * pl.pad_c[i] * op.k * es, 256);
       pl.dwpad_off[i] = off; off += align_up((size_t)op.r * op.s * pl.pad_c[i] * op.k * sizeof(float), 256);
     }
+  double conv_flops = 0.0;  // forward pass
+  for (int i = 0; i < nops; ++i)
+    if (net->ops[i].kind == S4TF_OP_CONV) {
+      const s4tf_op& op = net->ops[i];
+      conv_flops += 2.0 * (double)pl.t[i + 1].elems * op.r * op.s * pl.t[op.in].c / op.groups;
+    }
+  pl.one_stream = conv_flops < 0.5e9;
   pl.scratch_off = off;
   pl.scratch_bytes = align_up(scratch, 256);
   pl.wscratch_off = pl.scratch_off + pl.scratch_bytes;
@@ -592,6 +603,8 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   void* wscratch = ws + pl.wscratch_off;
   SideStream* side = nullptr;
   CHECK(side_stream(&side));
+  const bool one_stream = pl.one_stream;               // small steps: everything in order on `st`
+  const hipStream_t side_st = one_stream ? st : side->stream;
   // Whatever way this function returns, `st` ends up waiting for what the side stream was given, so
   // that in stream order on `st` the step is over (and its workspace free) when its last kernel is.
   struct Join {
@@ -607,6 +620,7 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   } join{side, st};
   // everything `st` has queued so far (the previous step's optimizer included) precedes the side stream's work
   auto fork = [&]() -> int {
+    if (one_stream) return S4TF_OK;
     join.forked = true;
     if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
       return fail(S4TF_ERR_DEVICE, "train step: stream fork failed");
@@ -633,6 +647,7 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   int back_next = 0;
   std::vector<int> branch_event(pl.branch_conv.size(), -1);
   auto side_done = [&](int& slot) -> int {  // marks what the side stream has been given so far
+    if (one_stream) return S4TF_OK;
     slot = back_next++ % 8;
     if (hipEventRecord(side->back[slot], side->stream) != hipSuccess) return fail(S4TF_ERR_DEVICE, "train step: event record failed");
     return S4TF_OK;
@@ -701,8 +716,8 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
       const int b = pl.start_after[i], j = pl.branch_conv[b];
       CHECK(fork());
       int sr = 0;
-      CHECK(fwd_op(j, side->stream, sscratch, sr));
-      CHECK(fwd_op(j + 1, side->stream, sscratch, sr));
+      CHECK(fwd_op(j, side_st, sscratch, sr));
+      CHECK(fwd_op(j + 1, side_st, sscratch, sr));
       CHECK(side_done(branch_event[b]));
     }
   }
@@ -738,11 +753,11 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
     if (pl.pad_c[j]) {  // the batch has no cotangent; the filter gradient of the padded channels is dropped
       d.c = pl.pad_c[j];
       float* dwp = reinterpret_cast<float*>(ws + pl.dwpad_off[j]);
-      CHECK(conv_param_grads_impl(d, ws + pl.xpad_off[j], dyj, dwp, dbias, wscratch, pl.wscratch_bytes, side->stream));
-      return unpad_channels_f32(dwp, params->grad + pl.poff[2 * j], (long long)cv.r * cv.s, cin.c, pl.pad_c[j], cv.k, side->stream);
+      CHECK(conv_param_grads_impl(d, ws + pl.xpad_off[j], dyj, dwp, dbias, wscratch, pl.wscratch_bytes, side_st));
+      return unpad_channels_f32(dwp, params->grad + pl.poff[2 * j], (long long)cv.r * cv.s, cin.c, pl.pad_c[j], cv.k, side_st);
     }
     return conv_param_grads_impl(d, act_ptr(pl.t[cv.in].root), dyj, params->grad + pl.poff[2 * j], dbias, wscratch,
-                                 pl.wscratch_bytes, side->stream);
+                                 pl.wscratch_bytes, side_st);
   };
   // A hand-over to the second stream costs the first one 5-7 us (measured: an event record between two kernels
   // 2.9 us, more once another stream waits on it), so the filter gradients of the main branch are handed over
@@ -773,7 +788,7 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
     void* dy = grad_ptr(i + 1);
     const int br = pl.branch_of[i];
     const bool on_side = br >= 0;
-    hipStream_t s = on_side ? side->stream : st;
+    hipStream_t s = on_side ? side_st : st;
     void* scr = on_side ? sscratch : scratch;
     if (on_side) {
       if (!branch_forked[br]) {  // everything queued on `st` so far (its cotangent's producer included) comes first

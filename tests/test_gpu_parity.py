@@ -513,3 +513,90 @@ def test_config4_resnet50_bf16():
                                 need_dx=False)[0]
     print("resnet50 bf16 loss: gpu %.6f oracle %.6f" % (gpu["loss"], ref_loss))
     assert abs(gpu["loss"] - ref_loss) <= 5e-3 * abs(ref_loss)
+
+
+# ---- the same step dispatched op by op (the paper's eager mode, Section 3.3) ---------------------------
+def run_eager_steps(net, wl, sync, steps=1):
+    from paper_2102_13243_amd.eager import EagerState
+    st = EagerState(net, wl["params"], DEV, sync=sync)
+    xd, ld = st.upload_batch(wl["x"], wl["labels"])
+    losses = []
+    for _ in range(steps):
+        st.step(xd, ld)
+        torch.cuda.synchronize()
+        losses.append(float(st.loss[0].item()))
+    out = st.results()
+    out["losses"] = losses
+    out["state"] = st
+    return out
+
+
+@pytest.mark.parametrize("name,kw,sync", [(n, kw, i % 2 == 0) for i, (n, kw) in enumerate(SMALL_NETS)],
+                         ids=[n for n, _ in SMALL_NETS])
+def test_eager_step_small_fp32(name, kw, sync):
+    """One entry point per op, pullbacks in reverse order with the accumulate flags doing the gradient
+    fan-in, one SGD call per parameter tensor: the result is the oracle's step, to the fused step's bar,
+    and the two ways of running the step agree on the loss."""
+    net = nets.CONFIGS[name](**kw)
+    wl = nets.make_workload(net, perturb=True)
+    ref = oracle_step_with_conditioning(net, wl)
+    eager = run_eager_steps(net, wl, sync)
+    compare_step(net, eager, ref, 1e-4, 1e-3, 1e-3)
+    fused = run_gpu_steps(net, wl)
+    assert abs(eager["loss"] - fused["loss"]) <= 2e-5 * abs(fused["loss"]), (eager["loss"], fused["loss"])
+
+
+def test_eager_lenet_ten_steps_and_bf16_loss():
+    net = nets.lenet5(batch=16)
+    wl = nets.make_workload(net)
+    eager = run_eager_steps(net, wl, sync=False, steps=10)
+    fused = run_gpu_steps(net, wl, steps=10)
+    np.testing.assert_allclose(eager["losses"], fused["losses"], rtol=1e-4)
+    # bf16 storage: the working copy of the parameters is refreshed by the per-tensor SGD calls
+    net = dict(nets.resnet50(batch=8, hw=64, stages=(2, 2, 1, 1), classes=40), dtype="bf16")
+    wl = nets.make_workload(net, perturb=True)
+    wl["x"] = nets.to_bf16_grid(wl["x"])
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+    eager = run_eager_steps(net, wl, sync=True, steps=2)
+    assert abs(eager["losses"][0] - ref["loss"]) <= 5e-2 * abs(ref["loss"]), (eager["losses"], ref["loss"])
+    assert np.isfinite(eager["losses"][1])
+    st = eager["state"]
+    np.testing.assert_array_equal(st.lowp.float().cpu().numpy(), st.master.to(torch.bfloat16).float().cpu().numpy())
+
+
+@pytest.mark.parametrize("name,kw", [("lenet5", dict(batch=16)),
+                                     ("resnet50", dict(batch=4, hw=64, stages=(2, 1, 1, 1), classes=24, dtype="f32"))],
+                         ids=["one_stream", "two_streams"])
+def test_train_step_captured_in_a_graph_replays_like_direct_calls(name, kw):
+    """The step allocates nothing, clears nothing with memset calls and synchronises nothing, and its second
+    stream is forked from and joined back into the caller's: a caller may capture it in a HIP graph.  Every
+    replay (with other work and a synchronisation between replays) must give the loss of the same step
+    made by a direct call, bit for bit, since each replay trains the parameters one step further."""
+    net = nets.CONFIGS[name](**kw)
+    wl = nets.make_workload(net, perturb=True)
+    ref = B.TrainState(net, wl["params"], DEV)
+    xr, lr_ = ref.upload_batch(wl["x"], wl["labels"])
+    want = []
+    for _ in range(5):
+        ref.step(xr, lr_)
+        torch.cuda.synchronize()
+        want.append(float(ref.loss[0].item()))
+    st = B.TrainState(net, wl["params"], DEV)
+    xd, ld = st.upload_batch(wl["x"], wl["labels"])
+    st.step(xd, ld)   # the first call on a device creates the library's second stream: not under capture
+    torch.cuda.synchronize()
+    got = [float(st.loss[0].item())]
+    graph, stream = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=stream):
+        st.step(xd, ld)
+    torch.cuda.synchronize()
+    for _ in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        got.append(float(st.loss[0].item()))
+        assert float(xd.float().abs().sum().item()) > 0   # unrelated work on the default stream in between
+    assert got == want, (got, want)
+    a, b = st.results(), ref.results()
+    for pa, pb in zip(a["params"], b["params"]):
+        for x, y in zip(pa, pb):
+            np.testing.assert_array_equal(x, y)
