@@ -774,7 +774,9 @@ void igemm_dma_tile(int pass, int Mg, int Ng, int splits, int& BM, int& BN) {
   BN = Ng <= 64 ? 64 : 128;
   if (BN == 64) return;  // (128x64)
   if (pass == PASS_WGRAD) {
-    if (Mg <= 64) BM = 64;
+    // 64-row tiles: twice the tiles, so half the splits of the reduction axis fill the chip, and half the
+    // fp32 partial sums are written and read back (measured over a ResNet-50 step: -1.8 %)
+    BM = 64;
   } else if ((long long)((Mg + 127) / 128) * ((Ng + 127) / 128) * splits < 512) {
     BM = 64;
     // still fewer workgroups than CUs (the 7x7 layers): 64x64, twice as many again
