@@ -777,7 +777,9 @@ void igemm_dma_tile(int pass, int Mg, int Ng, int splits, int& BM, int& BN) {
     // 64-row tiles: twice the tiles, so half the splits of the reduction axis fill the chip, and half the
     // fp32 partial sums are written and read back (measured over a ResNet-50 step: -1.8 %)
     BM = 64;
-  } else if ((long long)((Mg + 127) / 128) * ((Ng + 127) / 128) * splits < 512) {
+  } else if ((long long)((Mg + 127) / 128) * ((Ng + 127) / 128) * splits < 384) {
+    // fewer than 1.5 workgroups of 128x128 per CU: 64-row tiles (inside a training step, where the filter
+    // gradients of the second stream share the CUs, 384 measured 0.7 % better than 512 and like 256)
     BM = 64;
     // still fewer workgroups than CUs (the 7x7 layers): 64x64, twice as many again
     if ((long long)((Mg + 63) / 64) * ((Ng + 127) / 128) * splits < 256) BN = 64;
