@@ -835,7 +835,9 @@ void wgrad_split(const ConvGeom& g, int dtype, int& splits, int& nk_per_split) {
     int BM, BN;
     igemm_dma_tile(PASS_WGRAD, Mg, g.K, 1, BM, BN);
     const long long tiles = (long long)((Mg + BM - 1) / BM) * ((g.K + BN - 1) / BN);
-    want = 320 / tiles;
+    // (at most four tiles: the first layers, whose filter gradients are the tail of a step with nothing
+    // left beside them; there more workgroups are simply faster)
+    want = (tiles <= 4 ? 512 : 320) / tiles;
   } else {
     int BM = 128, BN = 128;
     if (dtype != S4TF_BF16) f32_tile(Mg, g.K, Kg, true, BM, BN);
