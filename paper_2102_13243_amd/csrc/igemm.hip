@@ -842,7 +842,7 @@ void wgrad_split(const ConvGeom& g, int dtype, int& splits, int& nk_per_split) {
     int BM = 128, BN = 128;
     if (dtype != S4TF_BF16) f32_tile(Mg, g.K, Kg, true, BM, BN);
     const long long tiles = (long long)((Mg + BM - 1) / BM) * ((g.K + BN - 1) / BN);
-    want = (1024 + tiles - 1) / tiles;
+    want = (512 + tiles - 1) / tiles;  // measured inside the fp32 training steps: 1024 +1.8 %, 768 +0.8 %, 416 +2 %
   }
   if (want > nk) want = nk;
   if (want < 1) want = 1;
