@@ -818,7 +818,14 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
           pending.push_back(i);
           // (the last few of the pass one by one: whatever is still queued when the main stream runs out of work
           // is the tail of the step)
-          if ((int)pending.size() >= FORK_EVERY || convs_before[i] < 6) CHECK(flush_pending());
+          // A big filter gradient (gigaflops, contracted over tens of thousands of pixels: 50-130 us on the second
+          // stream, behind main-stream kernels that are as long) is worth a hand-over of its own: started as early
+          // as possible, the second stream is not what the end of the step waits for (ResNet-50: -1 %; the small
+          // layers of the fp32 nets lose 1-2 % when handed over singly).
+          const TensorPlan& ot = pl.t[i + 1];
+          const double wflops = 2.0 * (double)ot.elems * op.r * op.s * in.c / op.groups;
+          const bool big = wflops >= 5e9 && (double)ot.n * ot.h * ot.w >= 40000.0;
+          if ((int)pending.size() >= FORK_EVERY || convs_before[i] < 6 || big) CHECK(flush_pending());
         }
         break;
       }
