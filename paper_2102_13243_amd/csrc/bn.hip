@@ -248,13 +248,14 @@ template <typename T, int V>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        const float* __restrict__ mean, const float* __restrict__ invstd,
-                                                       T* __restrict__ y, long long M, int C, int cvb, long long per,
-                                                       int act) {
+                                                       T* __restrict__ y, unsigned char* __restrict__ bits, long long M,
+                                                       int C, int cvb, long long per, int act) {
   const int CV = C / V, pl_count = blockDim.x / cvb;
   const int cvl = threadIdx.x % cvb, pl = threadIdx.x / cvb;
   const int cv = blockIdx.x * cvb + cvl;
   if (cv >= CV) return;
   const int c = cv * V;
+  const float mhi = remask_hi<T>(act);
   float mu[V], sc[V], be[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) {
@@ -273,13 +274,17 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
               },
               [&](long long m, int u) {
                 float o[V];
+                unsigned b = 0;
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                   float z = bn_z(xv[u].get(e), mu[e], sc[e], be[e]);
                   if (res) z += rv[u].get(e);
                   o[e] = fminf(fmaxf(z, act_lo), act_hi);  // the activation as a clamp: no branch per element
+                  b |= (z > 0.f && z < mhi) ? (1u << e) : 0u;
                 }
                 stp<T, V>(y + m * C + c, pack_of<T, V>(o));
+                // act'(y) of this thread's V outputs, one bit each (see remask_hi), for the pullback
+                if (bits) bits[m * CV + cv] = (unsigned char)b;
               });
 }
 
@@ -291,12 +296,13 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
 // that double accumulators would hold through the loop are what lets a fourth wavefront share a SIMD
 // (the kernel is bound by how many loads it keeps in flight: 898 -> 750 us over the BatchNorms of a
 // ResNet-50).
-template <typename T, int V, bool REMASK>
+template <typename T, int V, bool REMASK, bool BITS = false>
 __device__ __forceinline__ void bn_vjp_reduce_body(const T* __restrict__ x, const T* __restrict__ y,
                                                    const T* __restrict__ dy, const float* __restrict__ mean,
                                                    const float* __restrict__ invstd, const float* __restrict__ gamma,
                                                    const float* __restrict__ beta, double* __restrict__ part,
-                                                   long long M, int C, int cvb, long long per, int act) {
+                                                   long long M, int C, int cvb, long long per, int act,
+                                                   const unsigned char* __restrict__ bits = nullptr) {
   extern __shared__ double redd[];
   const int CV = C / V, pl_count = blockDim.x / cvb;
   const int cvl = threadIdx.x % cvb, pl = threadIdx.x / cvb;
@@ -322,17 +328,21 @@ __device__ __forceinline__ void bn_vjp_reduce_body(const T* __restrict__ x, cons
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
   if (live) {
     Pack<T, V> xv[UNROLL], dv[UNROLL], yv[UNROLL];
+    unsigned char bv[UNROLL];
     walk_pixels(p0 + pl, p1, pl_count,
                 [&](long long m, int u) {
                   xv[u] = ldp<T, V>(x + m * C + c);
                   dv[u] = ldp<T, V>(dy + m * C + c);
-                  if (act != S4TF_ACT_NONE && !remask) yv[u] = ldp<T, V>(y + m * C + c);
+                  if (BITS) bv[u] = bits[m * CV + cv];
+                  else if (act != S4TF_ACT_NONE && !remask) yv[u] = ldp<T, V>(y + m * C + c);
                 },
                 [&](long long, int u) {
 #pragma unroll
                   for (int e = 0; e < V; ++e) {
                     float dz = dv[u].get(e);
-                    if (remask) {
+                    if (BITS) {
+                      dz = ((bv[u] >> e) & 1) ? dz : 0.f;
+                    } else if (remask) {
                       const float z = bn_z(xv[u].get(e), mu[e], sc[e], be[e]);
                       dz = (z > 0.f && z < mhi) ? dz : 0.f;
                     } else if (act != S4TF_ACT_NONE) {
@@ -373,6 +383,11 @@ template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_reduc
 template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_reduce_remask_kernel(BN_VJP_REDUCE_ARGS) {
   bn_vjp_reduce_body<T, V, true>(x, y, dy, mean, invstd, gamma, beta, part, M, C, cvb, per, act);
 }
+// act'(y) from the bits the forward pass left (here `y` points at them): one byte per thread and pixel instead of V outputs
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_reduce_bits_kernel(BN_VJP_REDUCE_ARGS) {
+  bn_vjp_reduce_body<T, V, false, true>(x, nullptr, dy, mean, invstd, gamma, beta, part, M, C, cvb, per, act,
+                                        reinterpret_cast<const unsigned char*>(y));
+}
 
 __global__ __launch_bounds__(FIN_THREADS) void bn_vjp_finalize_kernel(const double* __restrict__ part, int chunks, int C,
                                                                       float* __restrict__ dgamma, float* __restrict__ dbeta) {
@@ -385,14 +400,15 @@ __global__ __launch_bounds__(FIN_THREADS) void bn_vjp_finalize_kernel(const doub
   dgamma[c] = (float)s2;
 }
 
-template <typename T, int V, bool REMASK>
+template <typename T, int V, bool REMASK, bool BITS = false>
 __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const T* __restrict__ y,
                                                            const T* __restrict__ dy, const float* __restrict__ gamma,
                                                            const float* __restrict__ mean, const float* __restrict__ invstd,
                                                            const float* __restrict__ beta,
                                                            const float* __restrict__ dgamma, const float* __restrict__ dbeta,
                                                            T* __restrict__ dx, T* dres, int acc_dres, long long M, int C,
-                                                           int cvb, long long per, int act) {
+                                                           int cvb, long long per, int act,
+                                                           const unsigned char* __restrict__ bits = nullptr) {
   const int CV = C / V, pl_count = blockDim.x / cvb;
   const int cvl = threadIdx.x % cvb, pl = threadIdx.x / cvb;
   const int cv = blockIdx.x * cvb + cvl;
@@ -416,11 +432,13 @@ __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const
   }
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
   Pack<T, V> xv[UNROLL], dv[UNROLL], yv[UNROLL], ov[UNROLL];
+  unsigned char bv[UNROLL];
   walk_pixels(p0 + pl, p1, pl_count,
               [&](long long m, int u) {
                 xv[u] = ldp<T, V>(x + m * C + c);
                 dv[u] = ldp<T, V>(dy + m * C + c);
-                if (act != S4TF_ACT_NONE && !remask) yv[u] = ldp<T, V>(y + m * C + c);
+                if (BITS) bv[u] = bits[m * CV + cv];
+                else if (act != S4TF_ACT_NONE && !remask) yv[u] = ldp<T, V>(y + m * C + c);
                 if (dres && acc_dres) ov[u] = ldp<T, V>(dres + m * C + c);
               },
               [&](long long m, int u) {
@@ -429,7 +447,9 @@ __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const
                 for (int e = 0; e < V; ++e) {
                   float dz = dv[u].get(e);
                   const float xc = xv[u].get(e) - mu[e];
-                  if (remask) {
+                  if (BITS) {
+                    dz = ((bv[u] >> e) & 1) ? dz : 0.f;
+                  } else if (remask) {
                     const float z = fmaf(xc, gs[e], be[e]);  // bn_z, sharing the subtraction
                     dz = (z > 0.f && z < mhi) ? dz : 0.f;
                   } else if (act != S4TF_ACT_NONE) {
@@ -454,8 +474,21 @@ template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply
 template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply_remask_kernel(BN_VJP_APPLY_ARGS) {
   bn_vjp_apply_body<T, V, true>(x, y, dy, gamma, mean, invstd, beta, dgamma, dbeta, dx, dres, acc_dres, M, C, cvb, per, act);
 }
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply_bits_kernel(BN_VJP_APPLY_ARGS) {
+  bn_vjp_apply_body<T, V, false, true>(x, nullptr, dy, gamma, mean, invstd, beta, dgamma, dbeta, dx, dres, acc_dres, M, C,
+                                       cvb, per, act, reinterpret_cast<const unsigned char*>(y));
+}
 
 }  // namespace
+
+// Bytes of the activation bits of an (M, C) tensor: one byte per channel vector and pixel.  The reduction and
+// the apply plans of one tensor use the same vector width, so the byte a forward thread wrote is the byte a
+// pullback thread reads.
+size_t bn_mask_bytes(size_t M, int C, int dtype) {
+  int V = dtype == S4TF_BF16 ? 8 : 4;
+  if (C % V) V = 1;
+  return M * (size_t)(C / V);
+}
 
 size_t bn_workspace(size_t M, int C) {
   (void)M;
@@ -478,7 +511,8 @@ size_t bn_workspace(size_t M, int C) {
   } while (0)
 
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
-           void* y, float* mean, float* invstd, void* ws, hipStream_t st, const float* stats_part, int stats_rows) {
+           void* y, float* mean, float* invstd, void* ws, hipStream_t st, const float* stats_part, int stats_rows,
+           unsigned char* maskbits) {
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
   const Plan pr = make_plan((size_t)M, C, d.dtype, 1024, 16);  // reduction: fewer, longer blocks
@@ -506,23 +540,29 @@ int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* g
     if ((rc = launch_status("bn_stats_finalize")) != S4TF_OK) return rc;
   }
   ProfScope ps(PC_BN_APPLY, st);
-  BN_LAUNCH(bn_apply_kernel, pa, 0, (const T*)x, (const T*)res, gamma, beta, mean, invstd, (T*)y, M, C, pa.cvb, pa.per, d.act);
+  BN_LAUNCH(bn_apply_kernel, pa, 0, (const T*)x, (const T*)res, gamma, beta, mean, invstd, (T*)y, maskbits, M, C, pa.cvb,
+            pa.per, d.act);
   return launch_status("bn_apply");
 }
 
 int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* beta, const float* mean,
            const float* invstd, const void* dy, void* dx, void* dres, float* dgamma, float* dbeta,
-           void* ws, hipStream_t st) {
+           void* ws, hipStream_t st, const unsigned char* maskbits) {
   const long long M = (long long)d.n * d.h * d.w;
   const int C = d.c;
   if (dres || d.act == S4TF_ACT_NONE) beta = nullptr;  // with a residual z cannot be rebuilt from x alone
+  if (beta || d.act == S4TF_ACT_NONE) maskbits = nullptr;
+  if (maskbits) y = maskbits;  // the bits kernels take them through the y argument
   const Plan pr = make_plan((size_t)M, C, d.dtype, 512, UNROLL);  // measured over the ResNet-50 shapes: 512 blocks beat 1024 and 256
   const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, UNROLL);
   double* part = static_cast<double*>(ws);
   int rc;
   {
     ProfScope ps(PC_BN_VJP_REDUCE, st);
-    if (beta)
+    if (maskbits)
+      BN_LAUNCH(bn_vjp_reduce_bits_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(double), (const T*)x, (const T*)y,
+                (const T*)dy, mean, invstd, gamma, beta, part, M, C, pr.cvb, pr.per, d.act);
+    else if (beta)
       BN_LAUNCH(bn_vjp_reduce_remask_kernel, pr, (size_t)4 * pr.cvb * 2 * pr.V * sizeof(double), (const T*)x, (const T*)y,
                 (const T*)dy, mean, invstd, gamma, beta, part, M, C, pr.cvb, pr.per, d.act);
     else
@@ -533,7 +573,10 @@ int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gam
     if ((rc = launch_status("bn_vjp_finalize")) != S4TF_OK) return rc;
   }
   ProfScope ps(PC_BN_VJP_APPLY, st);
-  if (beta)
+  if (maskbits)
+    BN_LAUNCH(bn_vjp_apply_bits_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, beta, dgamma, dbeta,
+              (T*)dx, (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);
+  else if (beta)
     BN_LAUNCH(bn_vjp_apply_remask_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, beta, dgamma, dbeta,
               (T*)dx, (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);
   else

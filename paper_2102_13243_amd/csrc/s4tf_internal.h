@@ -119,14 +119,18 @@ int unpad_channels_f32(const float* src, float* dst, long long outer, int C, int
 
 // batch norm
 size_t bn_workspace(size_t M, int C);
+size_t bn_mask_bytes(size_t M, int C, int dtype);
 // stats_part / stats_rows: per-channel partial sums that the producing convolution left (see igemm_fwd);
-// NULL / 0: the statistics are computed here from x
+// NULL / 0: the statistics are computed here from x.
+// maskbits (optional, bn_mask_bytes bytes): the forward pass leaves act'(y) there, one bit per output, and a
+// pullback that is given them reads these instead of y (a BatchNorm with a residual cannot rebuild its
+// activation mask from x; the bits are a sixteenth of y in bf16).
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
            void* y, float* mean, float* invstd, void* ws, hipStream_t st, const float* stats_part = nullptr,
-           int stats_rows = 0);
+           int stats_rows = 0, unsigned char* maskbits = nullptr);
 int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* beta, const float* mean,
            const float* invstd, const void* dy, void* dx, void* dres, float* dgamma, float* dbeta,
-           void* ws, hipStream_t st);
+           void* ws, hipStream_t st, const unsigned char* maskbits = nullptr);
 
 // pools
 // idx (optional, max pool with a channel count that the 16-byte kernels take: pool_saves_positions): one byte per
