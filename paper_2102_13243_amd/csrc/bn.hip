@@ -20,6 +20,16 @@ namespace {
 constexpr int MAX_CHUNKS = 2048;
 constexpr int UNROLL = 4;
 
+// The finalize kernels give a block a few adjacent channels and have it walk the rows of a table of partial
+// sums, a few bytes per row.  Workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own:
+// with channel block = workgroup id, every XCD ends up fetching every line of the table.  Dealt as below, an
+// XCD's blocks cover one contiguous range of channels, and a line is fetched by one L2 only (measured over a
+// ResNet-50 step: the statistics finalize kernels fetch 155 MB instead of 480, the pullback's 125 instead of 241).
+__device__ inline int xcd_channel_block() {
+  const int n = gridDim.x, b = blockIdx.x;
+  return n % 8 == 0 ? (b % 8) * (n / 8) + b / 8 : b;
+}
+
 struct Plan {
   int V, cvb, cblocks, pl, chunks;
   long long per;  // pixels per chunk
@@ -177,7 +187,7 @@ __global__ __launch_bounds__(FIN_THREADS) void bn_stats_finalize_kernel(const T*
                                                                         int chunks, long long M, int C, float eps,
                                                                         float* __restrict__ mean, float* __restrict__ invstd) {
   __shared__ double sh[FIN_THREADS / 64][2][8];
-  const int c = blockIdx.x * 8 + (threadIdx.x & 7);
+  const int c = xcd_channel_block() * 8 + (threadIdx.x & 7);
   double s1, s2;
   sum_chunks<float>(part, chunks, C, c, sh, s1, s2);
   if (threadIdx.x >= 8 || c >= C) return;
@@ -201,7 +211,7 @@ __global__ __launch_bounds__(1024) void bn_stats_from_runs_kernel(const float* _
                                                                   float* __restrict__ invstd) {
   constexpr int ZL = 1024 / CPB;
   __shared__ double sh[16][3][CPB];
-  const int cl = threadIdx.x % CPB, c = blockIdx.x * CPB + cl, zl = threadIdx.x / CPB;
+  const int cl = threadIdx.x % CPB, c = xcd_channel_block() * CPB + cl, zl = threadIdx.x / CPB;
   const double inv_rows = 1.0 / (double)rows;
   const double inv_last = 1.0 / (double)(M - (long long)(runs - 1) * rows);
   double v[3] = {0.0, 0.0, 0.0};
@@ -392,7 +402,7 @@ template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_reduc
 __global__ __launch_bounds__(FIN_THREADS) void bn_vjp_finalize_kernel(const double* __restrict__ part, int chunks, int C,
                                                                       float* __restrict__ dgamma, float* __restrict__ dbeta) {
   __shared__ double sh[FIN_THREADS / 64][2][8];
-  const int c = blockIdx.x * 8 + (threadIdx.x & 7);
+  const int c = xcd_channel_block() * 8 + (threadIdx.x & 7);
   double s1, s2;
   sum_chunks<double>(part, chunks, C, c, sh, s1, s2);
   if (threadIdx.x >= 8 || c >= C) return;
