@@ -142,9 +142,10 @@ static int conv_fwd_impl(const s4tf_conv_desc& d, const void* x, const void* w, 
 }
 // dz: cotangent after the activation pullback
 // The pullback's two halves are independent given dz: the input cotangent, and the parameter gradients.
-static int conv_dgrad_impl(const s4tf_conv_desc& d, const void* w, const void* dz, void* dx, hipStream_t st) {
+static int conv_dgrad_impl(const s4tf_conv_desc& d, const void* w, const void* dz, void* dx, hipStream_t st,
+                           const void* acc_src = nullptr, const unsigned char* acc_bits = nullptr) {
   ConvGeom g = conv_geom(d);
-  if (d.groups == 1) return igemm_dgrad(g, d.dtype, dz, w, dx, d.accumulate_dx, st);
+  if (d.groups == 1) return igemm_dgrad(g, d.dtype, dz, w, dx, d.accumulate_dx, st, acc_src, acc_bits);
   return dwconv_dgrad(g, d.dtype, dz, w, dx, d.accumulate_dx, st);
 }
 static int conv_param_grads_impl(const s4tf_conv_desc& d, const void* x, const void* dz, float* dw, float* dbias,
@@ -206,6 +207,11 @@ struct TensorPlan {
 struct NetPlan {
   std::vector<TensorPlan> t;
   std::vector<int64_t> poff, psize;  // 2 per op
+  // per BatchNorm op with activation bits whose residual input has one other consumer, a plain convolution of
+  // the main branch (an identity shortcut): that convolution's op index, else -1.  The pullback of such a
+  // BatchNorm need not write its residual cotangent dz = act'(y) dy: the convolution's dgrad adds it from dy
+  // and the bits in its epilogue (same values, one tensor less written).
+  std::vector<int> defer_conv;
   std::vector<size_t> mask_off;      // per op: activation bits of a BatchNorm with residual and activation (0: none)
   std::vector<size_t> stat_off;      // per op: save_mean/invstd (BN); max pool: the saved window positions (one byte per output)
   // a convolution on the batch itself whose channel count is not a multiple of 8 (bf16) or 4 (fp32) runs
@@ -241,6 +247,7 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
   pl.psize.assign(2 * nops, 0);
   pl.stat_off.assign(nops, 0);
   pl.mask_off.assign(nops, 0);
+  pl.defer_conv.assign(nops, -1);
   pl.pad_c.assign(nops, 0);
   pl.xpad_off.assign(nops, 0);
   pl.wpad_off.assign(nops, 0);
@@ -415,6 +422,22 @@ static int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
     pl.branch_of[j] = pl.branch_of[j + 1] = id;
     pl.start_after[X - 1] = id;
     pl.needs[user] = id;
+  }
+  // identity shortcuts whose residual cotangent the consuming convolution's dgrad can add by itself
+  for (int i = 0; i < nops; ++i) {
+    const s4tf_op& bn = net->ops[i];
+    if (bn.kind != S4TF_OP_BN || bn.res <= 0 || !pl.mask_off[i] || pl.branch_of[i] >= 0) continue;
+    const int R = bn.res;
+    if (pl.t[R].root != R || pl.t[R].consumers != 2) continue;
+    int conv = -1;
+    for (int j = 0; j < i; ++j)
+      if (net->ops[j].in == R && j != i) { conv = j; break; }
+    if (conv < 0) continue;
+    const s4tf_op& cv = net->ops[conv];
+    if (cv.kind != S4TF_OP_CONV || cv.groups != 1 || cv.stride != 1 || cv.act != S4TF_ACT_NONE || pl.pad_c[conv] ||
+        pl.branch_of[conv] >= 0)
+      continue;
+    pl.defer_conv[i] = conv;
   }
   pl.param_count = pcount;
   return S4TF_OK;
@@ -752,6 +775,7 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
   // Ops of a side branch run on the side stream (after the op that feeds them their cotangent, which
   // the fork orders); a cotangent they write is waited for where the main stream first touches it.
   std::vector<int> grad_event(nops + 1, -1);   // per tensor: pending side-stream write of its cotangent
+  std::vector<int> deferred(nops + 1, -1);     // per tensor: the BatchNorm whose residual cotangent its consumer's dgrad adds
   std::vector<char> branch_forked(pl.branch_conv.size(), 0);
   int early_join = -1;  // event slot: everything the side stream got before the first op's filter gradient
   // Filter (and bias) gradient of convolution j, on the second stream.
@@ -818,7 +842,14 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         // dz is final.  The input cotangent is computed first; the parameter gradients go to the side
         // stream and start when it is done, so that they run beside the bandwidth-bound BatchNorm pullback
         // of the layer before rather than beside this layer's other matrix kernel (measured: 2 % of the step).
-        if (want_dx && !pl.pad_c[i]) {
+        if (want_dx && !pl.pad_c[i] && deferred[src] >= 0) {
+          const int b = deferred[src];  // dx = dgrad + the residual cotangent of BatchNorm b, from its dy and bits
+          if (written[src]) return fail(S4TF_ERR_UNSUPPORTED, "train step: deferred residual cotangent of tensor %d already written", src);
+          CHECK(conv_dgrad_impl(d, conv_w(i), dy, grad_ptr(src), s, grad_ptr(b + 1),
+                                reinterpret_cast<const unsigned char*>(ws + pl.mask_off[b])));
+          deferred[src] = -1;
+          written[src] = 1;
+        } else if (want_dx && !pl.pad_c[i]) {
           CHECK(conv_dgrad_impl(d, conv_w(i), dy, grad_ptr(src), s));
           written[src] = 1;
           if (on_side) CHECK(side_done(grad_event[src]));
@@ -847,13 +878,22 @@ int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_ba
         float* stats = reinterpret_cast<float*>(ws + pl.stat_off[i]);
         void* dxb = grad_ptr(src);  // src != 0: checked when the net was planned
         void* dres = rsrc > 0 ? grad_ptr(rsrc) : nullptr;
+        if (pl.defer_conv[i] >= 0 && !on_side && !written[rsrc]) {
+          // identity shortcut: the dgrad of the block's first convolution will add dz = act'(y) dy itself
+          const int j = pl.defer_conv[i];
+          s4tf_conv_desc cd = conv_desc(j, 0);
+          if (igemm_dgrad_adds_other(conv_geom(cd), dt, grad_ptr(j + 1), conv_w(j), dres, dy)) {
+            deferred[rsrc] = i;
+            dres = nullptr;
+          }
+        }
         // no residual in the forward pass: the pullback rebuilds the activation mask from x and skips y
         const float* beta = op.res < 0 ? params->master + pl.poff[2 * i + 1] : nullptr;
         CHECK(bn_vjp(d, act_ptr(src), out_ptr(i + 1), params->master + pl.poff[2 * i], beta, stats, stats + in.c, dy, dxb,
                      dres, params->grad + pl.poff[2 * i], params->grad + pl.poff[2 * i + 1], scr, s,
                      pl.mask_off[i] ? reinterpret_cast<const unsigned char*>(ws + pl.mask_off[i]) : nullptr));
         written[src] = 1;
-        if (rsrc > 0) written[rsrc] = 1;
+        if (rsrc > 0 && dres) written[rsrc] = 1;
         break;
       }
       case S4TF_OP_AVGPOOL2:

@@ -884,10 +884,27 @@ size_t igemm_fwd_stats_bytes(const ConvGeom& g) {  // the finest runs any tile u
   return (M + 31) / 32 * 2 * g.K * sizeof(float);
 }
 
+// Can igemm_dgrad add a (masked) tensor other than the old contents of dx?  Only the stride-1 case of the
+// fast bf16 kernel does.
+bool igemm_dgrad_adds_other(const ConvGeom& g, int dtype, const void* dy, const void* w, const void* dx,
+                            const void* acc_src) {
+  if (dtype != S4TF_BF16 || g.stride != 1 || !aligned16(acc_src) || g.C % 8) return false;
+  Args a = {};
+  a.g = g; a.a = dy; a.b = w; a.out = const_cast<void*>(dx);
+  return igemm_dma_ok(PASS_DGRAD, g, a);
+}
+
 int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,
-                hipStream_t st) {
+                hipStream_t st, const void* acc_src, const unsigned char* acc_bits) {
   Args a = {};
   a.g = g; a.a = dy; a.b = w; a.out = dx; a.accumulate = accumulate;
+  if (acc_src) {
+    if (!igemm_dgrad_adds_other(g, dtype, dy, w, dx, acc_src))
+      return fail(S4TF_ERR_UNSUPPORTED, "dgrad: this shape cannot add another tensor");
+    a.accumulate = 1;
+    a.acc_src = acc_src;
+    a.acc_bits = acc_bits;
+  }
   a.Mg = g.N * g.H * g.W; a.Ng = g.C; a.Kg = g.R * g.S * g.K;
   a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
   fill_sizes(a, PASS_DGRAD, dtype);

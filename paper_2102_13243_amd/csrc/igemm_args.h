@@ -18,6 +18,11 @@ struct Args {
   int stats_rows;     // set by the launcher: output rows per partial sum
   int Mg, Ng, Kg;
   int act, accumulate, simple;
+  // dgrad with accumulate, fast bf16 path only: what is added to the result, if not the old contents of out.
+  // acc_src: a tensor shaped like out; acc_bits (optional): one byte per 16-byte chunk of it, bit e set = element
+  // e of the chunk counts (the activation bits a BatchNorm's forward pass leaves, see bn_fwd), else it adds 0.
+  const void* acc_src;
+  const unsigned char* acc_bits;
   int scatter2;                     // dgrad of a 1x1 / stride 2 / no padding layer run over the pixels of dy
   // dgrad of a strided layer with a filter wider than its stride, one launch per parity class (ph, pw):
   // rows are the input pixels (stride*hc + ph, stride*wc + pw), 0 <= hc < Hc, 0 <= wc < Wc, and k runs over

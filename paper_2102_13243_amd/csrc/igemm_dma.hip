@@ -655,6 +655,7 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
       // pixels of dy and scatters row (n,p,q) to pixel (n,2p,2q) of dx
       long long dsto[ITERS];
       uint4 old[ITERS];
+      unsigned obits[ITERS];
 #pragma unroll
       for (int it = 0; it < ITERS; ++it) {
         const int chunk = lane + it * 64;
@@ -673,7 +674,11 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
             orow = ((long long)n * a.g.H + 2 * p) * a.g.W + 2 * q;
           }
           dsto[it] = orow * a.Ng + col;
-          if (PASS == PASS_DGRAD && a.accumulate) old[it] = *reinterpret_cast<const uint4*>(out + dsto[it]);
+          if (PASS == PASS_DGRAD && a.accumulate) {
+            const bf16_t* src = a.acc_src ? static_cast<const bf16_t*>(a.acc_src) : out;
+            old[it] = *reinterpret_cast<const uint4*>(src + dsto[it]);
+            obits[it] = a.acc_bits ? a.acc_bits[dsto[it] >> 3] : 0xffu;
+          }
         }
       }
 #pragma unroll
@@ -707,7 +712,7 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
           }
           if (PASS == PASS_DGRAD && a.accumulate) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v8[e] += bf16_to_f32((bf16_t)half_of(old[it], e));
+            for (int e = 0; e < 8; ++e) v8[e] += ((obits[it] >> e) & 1) ? bf16_to_f32((bf16_t)half_of(old[it], e)) : 0.f;
           }
           uint4 o;
           o.x = (uint32_t)f32_to_bf16(v8[0]) | ((uint32_t)f32_to_bf16(v8[1]) << 16);

@@ -91,8 +91,13 @@ inline ConvGeom conv_geom(const s4tf_conv_desc& d) {
 int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, int act,
               void* y, hipStream_t st, float* stats_part = nullptr, int* stats_rows = nullptr);
 size_t igemm_fwd_stats_bytes(const ConvGeom& g);  // upper bound on the size of stats_part
+// acc_src (optional; only where igemm_dgrad_adds_other says so): the result is dgrad + acc_src instead of
+// dgrad (+ old dx); acc_bits (optional): activation bits as bn_fwd leaves them, one per element of acc_src,
+// elements whose bit is clear add nothing.
 int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,
-                hipStream_t st);
+                hipStream_t st, const void* acc_src = nullptr, const unsigned char* acc_bits = nullptr);
+bool igemm_dgrad_adds_other(const ConvGeom& g, int dtype, const void* dy, const void* w, const void* dx,
+                            const void* acc_src);
 size_t igemm_wgrad_workspace(const ConvGeom& g, int dtype);
 int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, float* dw, void* ws,
                 size_t ws_bytes, hipStream_t st);
