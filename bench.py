@@ -64,25 +64,48 @@ def conv_flops(net, shapes):
 def class_bytes(net, shapes, n_params):
     """Algorithmic HBM bytes of one step for the classes that no contraction bounds: every operand a
     kernel class must read or write once, at the storage width (es) of activations; fp32 elsewhere.
-      bn_apply       x -> y (+ residual read)                       (2 + res) * numel * es
-      bn_vjp_reduce  x, dy (+ y for the activation mask, read only    (2 + act*res) * numel * es
-                     when there is a residual: without one the
-                     mask is rebuilt from x)
-      bn_vjp_apply   x, dy (+ y) -> dx (+ residual cotangent)       (3 + act*res + res) * numel * es
+      bn_apply       x -> y (+ residual read) (+ activation bits)   (2 + res) * numel * es + bits
+      bn_vjp_reduce  x, dy + the activation mask: rebuilt from x      2 * numel * es + mask
+                     without a residual (nothing read); with one,
+                     the forward pass's bits where the library
+                     keeps them (rows of at least 32 bytes of bits
+                     per pixel, one bit per element), else y
+      bn_vjp_apply   x, dy, mask -> dx (+ residual cotangent, unless  (3 + dres) * numel * es + mask
+                     the consuming convolution's dgrad adds it: an
+                     identity shortcut in a bf16 net)
       dwconv_fwd     x -> y;  dwconv_dgrad  dy -> dx;  dwconv_wgrad  x, dy      (in + out) * es each
       sgd            p, v, g read, p, v written (fp32) (+ the bf16 working copy written)
     """
     es = 2 if net["dtype"] == "bf16" else 4
     out = {"bn_apply": 0.0, "bn_vjp_reduce": 0.0, "bn_vjp_apply": 0.0, "dwconv_fwd": 0.0, "dwconv_dgrad": 0.0,
            "dwconv_wgrad": 0.0, "sgd": n_params * (20.0 + (2.0 if es == 2 else 0.0))}
+    users = {}
+    for j, o in enumerate(net["ops"]):
+        for t in {o["in"], o.get("res", -1)}:
+            if t >= 0:
+                users.setdefault(t, []).append(j)
     for i, op in enumerate(net["ops"]):
         numel = float(np.prod(shapes[op["in"]]))
         if op["kind"] == "bn":
             res = 1 if op["res"] >= 0 else 0
             act = 0 if op["act"] == "none" else 1
-            out["bn_apply"] += (2 + res) * numel * es
-            out["bn_vjp_reduce"] += (2 + act * res) * numel * es
-            out["bn_vjp_apply"] += (3 + act * res + res) * numel * es
+            c = shapes[op["in"]][3]
+            v = 8 if es == 2 else 4
+            if c % v:
+                v = 1
+            bits = numel / v if (res and act and c // v >= 32) else 0.0
+            mask = bits if bits else act * res * numel * es
+            dres = res
+            if bits and es == 2:
+                others = [j for j in users.get(op["res"], []) if j != i]
+                if len(others) == 1:
+                    o = net["ops"][others[0]]
+                    if (o["kind"] == "conv" and o["in"] == op["res"] and o["groups"] == 1 and o["stride"] == 1
+                            and o["act"] == "none" and shapes[o["in"]][3] % 8 == 0):
+                        dres = 0
+            out["bn_apply"] += (2 + res) * numel * es + bits
+            out["bn_vjp_reduce"] += 2 * numel * es + mask
+            out["bn_vjp_apply"] += (3 + dres) * numel * es + mask
         elif op["kind"] == "conv" and op["groups"] > 1:
             io = (numel + float(np.prod(shapes[i + 1]))) * es
             out["dwconv_fwd"] += io
