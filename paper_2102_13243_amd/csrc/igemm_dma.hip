@@ -592,20 +592,19 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
       });
     }
   }
+  // Optional by-product (forward) for a BatchNorm that follows: per channel (column), over the workgroup's BM
+  // output rows, the sum of the values as stored (rounded to bf16) and the sum of their squared deviations from
+  // that run's own mean.  Each wavefront sums its own FM*32 rows (lanes l and l^32 hold the two halves of a
+  // column); the wavefronts of the lower row block then hand their sums to the upper ones through LDS.
+  float ssum[FN], sqsum[FN];
   if constexpr (PASS == PASS_FWD) {
-    // Optional by-product for a BatchNorm that follows: per channel (column), over this wavefront's
-    // FM*32 output rows, the sum of the values as stored (rounded to bf16) and the sum of their squared
-    // deviations from that run's own mean.  Lanes l and l^32 hold the two halves of a column.
     if (a.stats) {
       const int rbase = m0 + arow;
-      const int cnt = min(max(a.Mg - rbase, 0), FM * 32);
-      float* part = a.stats + (long long)(rbase / (FM * 32)) * 2 * a.Ng;
-      const bool full = rbase + FM * 32 <= a.Mg;  // every row of the run exists
-      const float inv_cnt = cnt > 0 ? 1.f / (float)cnt : 0.f;
+      const bool full = rbase + FM * 32 <= a.Mg;  // every row of this wavefront exists
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
         // One pass: sum and sum of squares of the rounded values, four independent chains each, then the
-        // other half of the column from lane ^ 32.  A run is at most 64 values, so taking the squared
+        // other half of the column from lane ^ 32.  A run is at most 128 values, so taking the squared
         // deviations as sum(r^2) - sum(r)^2/n in fp32 loses about 1e-7 * (1 + mean^2/variance) of them.
         float s4[4] = {0.f, 0.f, 0.f, 0.f}, q4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -619,19 +618,44 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
           }
         float s1 = (s4[0] + s4[1]) + (s4[2] + s4[3]);
         float q1 = (q4[0] + q4[1]) + (q4[2] + q4[3]);
-        s1 += other_half(s1);
-        q1 += other_half(q1);
-        const float m2 = fmaxf(q1 - s1 * s1 * inv_cnt, 0.f);
-        const int col = n0 + brow + j * 32 + (lane & 31);
-        if (lane < 32 && col < a.Ng && cnt > 0) {  // a run with no valid row has no slot
-          part[col] = s1;
-          part[a.Ng + col] = m2;
-        }
+        ssum[j] = s1 + other_half(s1);
+        sqsum[j] = q1 + other_half(q1);
       }
     }
   }
   wait_vmcnt<0>();
   __syncthreads();  // the LDS tiles are idle: reuse them for the output tile
+  if constexpr (PASS == PASS_FWD) {
+    if (a.stats) {  // uniform over the workgroup: every wavefront meets the barrier below
+      static_assert(WM == 2, "two row blocks of wavefronts");
+      // the exchange area of a column block lies in the output patch of its upper wavefront, which reads it
+      // before it overwrites it; nobody else touches that patch
+      float* ex = reinterpret_cast<float*>(smem + (wave % WN) * Patch<FN>::BYTES);
+      if (wave / WN == 1 && lane < 32) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          ex[(j * 32 + lane) * 2] = ssum[j];
+          ex[(j * 32 + lane) * 2 + 1] = sqsum[j];
+        }
+      }
+      __syncthreads();
+      if (wave / WN == 0 && lane < 32) {
+        const int cnt = min(max(a.Mg - m0, 0), BM);
+        const float inv_cnt = cnt > 0 ? 1.f / (float)cnt : 0.f;
+        float* part = a.stats + (long long)(m0 / BM) * 2 * a.Ng;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const float s1 = ssum[j] + ex[(j * 32 + lane) * 2];
+          const float q1 = sqsum[j] + ex[(j * 32 + lane) * 2 + 1];
+          const int col = n0 + brow + j * 32 + lane;
+          if (col < a.Ng && cnt > 0) {  // a run with no valid row has no slot
+            part[col] = s1;
+            part[a.Ng + col] = fmaxf(q1 - s1 * s1 * inv_cnt, 0.f);
+          }
+        }
+      }
+    }
+  }
 
   // epilogue.  A 32x32 accumulator block: lane holds column (lane & 31) and, in register v,
   // row 8*(v/4) + 4*(lane >> 5) + (v % 4).
@@ -799,7 +823,7 @@ static void launch_tile(Args& a, int splits, hipStream_t st) {
   a.tiles_m = (a.Mg + BM - 1) / BM;
   a.tiles_n = (a.Ng + BN - 1) / BN;
   a.splits = splits;
-  a.stats_rows = FM * 32;
+  a.stats_rows = BM;
   unsigned blocks_all = grid_blocks(a);
   if (PASS == PASS_DGRAD && a.cls) {  // the four classes side by side, each dealt to the XCDs like a launch of its own
     blocks_all = 0;
