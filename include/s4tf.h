@@ -172,6 +172,13 @@ int s4tf_pool_dense_xent_fwd_vjp(const s4tf_head_desc* d, const void* x, const f
 int s4tf_sgd_momentum(size_t count, float* param, float* velocity, const float* grad, void* param_lowp,
                       float lr, float momentum, void* stream);
 
+/* ---- storage-type conversion --------------------------------------------------------------
+ * dst[i] = bfloat16(src[i]), round to nearest even (NaN stays NaN): how a caller that holds fp32 data
+ * produces the bf16 tensors this library reads (a batch, the initial working copy of the parameters),
+ * with the same rounding the library applies to everything it stores in bf16.  src: count floats,
+ * dst: count bf16 values, both device memory; count may be 0. */
+int s4tf_round_to_bf16(size_t count, const float* src, void* dst, void* stream);
+
 /* ---- whole step -------------------------------------------------------------------------
  * A network is a static list of ops in topological order; op i produces tensor i+1,
  * tensor 0 is the batch.  `in`/`res` name earlier tensors.  The last op must be the head

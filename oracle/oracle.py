@@ -232,10 +232,12 @@ def forward(net, x, params, keep=True):
     return tensors, saved
 
 
-def train_step(net, x, labels, params, velocity=None, lr=None, momentum=None):
+def train_step(net, x, labels, params, velocity=None, lr=None, momentum=None, keep_cotangents=False):
     """One differentiated training step.  `params` is the nested list of arrays from the
     workload generator (any float dtype); nothing is modified in place.  Returns a dict:
-    loss, logits, grads, params (updated), velocity (updated), tensors, cotangents."""
+    loss, logits, grads, params (updated), velocity (updated), tensors and, when
+    keep_cotangents is set, cotangents: {tensor id: the finished cotangent its producer's
+    pullback received} (otherwise each is dropped once it has been used)."""
     lr = net["lr"] if lr is None else lr
     momentum = net["momentum"] if momentum is None else momentum
     rnd = (lambda a: round_bf16(a, inplace=True)) if net["dtype"] == "bf16" else (lambda a: a)
@@ -244,6 +246,7 @@ def train_step(net, x, labels, params, velocity=None, lr=None, momentum=None):
     tensors, saved = forward(net, x, params)
     grads = [[None] * len(p) for p in params]
     cot = {}
+    kept = {}
 
     def contribute(t, g):
         if t == 0 or g is None:
@@ -262,6 +265,8 @@ def train_step(net, x, labels, params, velocity=None, lr=None, momentum=None):
         dy = cot.pop(i + 1, None)
         if dy is None:
             raise ValueError("op %d output has no consumer" % i)
+        if keep_cotangents:
+            kept[i + 1] = dy
         xin, y = tensors[tin], tensors[i + 1]
         if kind == "conv":
             dz, dbias = dy, None
@@ -299,4 +304,4 @@ def train_step(net, x, labels, params, velocity=None, lr=None, momentum=None):
         new_params.append(np_)
         new_vel.append(nv_)
     return {"loss": loss, "logits": logits, "grads": grads, "params": new_params,
-            "velocity": new_vel, "tensors": tensors}
+            "velocity": new_vel, "tensors": tensors, "cotangents": kept}

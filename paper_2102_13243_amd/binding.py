@@ -92,6 +92,8 @@ def lib():
     L.s4tf_pool2d_vjp.argtypes = [P(PoolDesc), c_vp, c_vp, c_vp, c_vp]
     L.s4tf_pool_dense_xent_fwd_vjp.argtypes = [P(HeadDesc)] + [c_vp] * 10 + [c_sz, c_vp]
     L.s4tf_sgd_momentum.argtypes = [c_sz, c_vp, c_vp, c_vp, c_vp, c_f32, c_f32, c_vp]
+    L.s4tf_round_to_bf16.argtypes = [c_sz, c_vp, c_vp, c_vp]
+    L.s4tf_round_to_bf16.restype = ctypes.c_int
     L.s4tf_net_param_count.restype = c_sz
     L.s4tf_net_param_count.argtypes = [P(NetDesc)]
     L.s4tf_net_param_layout.argtypes = [P(NetDesc), P(ctypes.c_int64), P(ctypes.c_int64)]
@@ -202,6 +204,20 @@ def s4tf_sgd_momentum(count, param, velocity, grad, param_lowp, lr, momentum, st
                                    _stream(stream)))
 
 
+def s4tf_round_to_bf16(count, src, dst, stream=None):
+    _check(lib().s4tf_round_to_bf16(count, _p(src), _p(dst), _stream(stream)))
+
+
+def to_bf16_device(t):
+    """A bf16 device tensor with the values of the fp32 device tensor t, rounded by the library's kernel
+    (torch only allocates the destination)."""
+    import torch
+    src = t.contiguous()
+    dst = torch.empty(src.shape, dtype=torch.bfloat16, device=src.device)
+    s4tf_round_to_bf16(src.numel(), src, dst)
+    return dst
+
+
 def s4tf_net_param_count(net_desc):
     return int(lib().s4tf_net_param_count(ctypes.byref(net_desc)))
 
@@ -305,7 +321,7 @@ class TrainState:
         self.grad = torch.zeros(self.count, dtype=torch.float32, device=device)
         self.lowp = None
         if net["dtype"] == "bf16":
-            self.lowp = torch.from_numpy(arena).to(torch.bfloat16).to(device)
+            self.lowp = to_bf16_device(self.master)
         self.ws_bytes = s4tf_train_step_workspace_bytes(self.desc)
         self.workspace = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=device)
         self.loss = torch.zeros(4, dtype=torch.float32, device=device)
@@ -329,10 +345,10 @@ class TrainState:
 
     def upload_batch(self, x, labels):
         torch = self.torch
-        xt = torch.from_numpy(np.ascontiguousarray(x, np.float32))
+        xt = torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(self.device)
         if self.net["dtype"] == "bf16":
-            xt = xt.to(torch.bfloat16)
-        return xt.to(self.device), torch.from_numpy(np.ascontiguousarray(labels, np.int32)).to(self.device)
+            xt = to_bf16_device(xt)
+        return xt, torch.from_numpy(np.ascontiguousarray(labels, np.int32)).to(self.device)
 
     def step(self, x_dev, labels_dev, lr=None, stream=None):
         lr = self.net["lr"] if lr is None else lr

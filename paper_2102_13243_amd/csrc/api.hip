@@ -574,6 +574,13 @@ int s4tf_sgd_momentum(size_t count, float* param, float* velocity, const float* 
   return sgd(count, param, velocity, grad, param_lowp, lr, momentum, (hipStream_t)stream);
 }
 
+int s4tf_round_to_bf16(size_t count, const float* src, void* dst, void* stream) {
+  clear_error();
+  if (count == 0) return S4TF_OK;
+  CHECK(need(src, "src")); CHECK(need(dst, "dst"));
+  return round_to_bf16(count, src, dst, (hipStream_t)stream);
+}
+
 // ---- whole step ---------------------------------------------------------------------------------------------------
 size_t s4tf_net_param_count(const s4tf_net_desc* net) {
   clear_error();

@@ -583,6 +583,9 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
     // Optional by-product for a BatchNorm that follows (no bias, no activation here): per channel
     // (column) and run of 32 output rows, the sum of the outputs and the sum of their squared deviations
     // from the run's own mean.  Lanes l and l ^ 32 hold the two halves of a column of a 32x32 block.
+    // The sums are taken of the deviations from a pivot, the run's first value (which lane l < 32 holds in
+    // register 0): sum = s + n*pivot, squared deviations = q - s^2/n with s and q of the size of the
+    // channel's spread, so a channel mean of many standard deviations costs no digits.
     if (a.stats) {
 #pragma unroll
       for (int i = 0; i < FM; ++i) {
@@ -592,13 +595,14 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
         const float inv_cnt = cnt > 0 ? 1.f / (float)cnt : 0.f;
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
+          const float pivot = __shfl(acc[i][j][0], lane & 31, 64);
           float s2[2] = {0.f, 0.f}, q2[2] = {0.f, 0.f};
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int row = rbase + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-            const float val = row < a.Mg ? acc[i][j][v] : 0.f;
-            s2[v & 1] += val;
-            q2[v & 1] = fmaf(val, val, q2[v & 1]);
+            const float dev = row < a.Mg ? acc[i][j][v] - pivot : 0.f;
+            s2[v & 1] += dev;
+            q2[v & 1] = fmaf(dev, dev, q2[v & 1]);
           }
           float s1 = s2[0] + s2[1], q1 = q2[0] + q2[1];
           s1 += __shfl_xor(s1, 32, 64);
@@ -606,7 +610,7 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
           const float m2 = fmaxf(q1 - s1 * s1 * inv_cnt, 0.f);
           const int col = n0 + brow + j * 32 + (lane & 31);
           if (lane < 32 && col < a.Ng && cnt > 0) {  // a run with no valid row has no slot
-            part[col] = s1;
+            part[col] = fmaf((float)cnt, pivot, s1);
             part[a.Ng + col] = m2;
           }
         }

@@ -596,30 +596,39 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
   // output rows, the sum of the values as stored (rounded to bf16) and the sum of their squared deviations from
   // that run's own mean.  Each wavefront sums its own FM*32 rows (lanes l and l^32 hold the two halves of a
   // column); the wavefronts of the lower row block then hand their sums to the upper ones through LDS.
+  // A wavefront sums deviations from a pivot, the first value of its row block (register 0 of lane l < 32):
+  // sum = s + n*pivot and squared deviations = q - s^2/n, with s and q of the size of the channel's spread
+  // whatever its mean, so a channel whose mean is many standard deviations loses no digits in the fp32 sums.
   float ssum[FN], sqsum[FN];
+  int wcnt = 0;  // valid rows of this wavefront's row block
   if constexpr (PASS == PASS_FWD) {
     if (a.stats) {
       const int rbase = m0 + arow;
-      const bool full = rbase + FM * 32 <= a.Mg;  // every row of this wavefront exists
+      wcnt = min(max(a.Mg - rbase, 0), FM * 32);
+      const bool full = wcnt == FM * 32;  // every row of this wavefront exists
+      const float inv_cnt = wcnt > 0 ? 1.f / (float)wcnt : 0.f;
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
-        // One pass: sum and sum of squares of the rounded values, four independent chains each, then the
-        // other half of the column from lane ^ 32.  A run is at most 128 values, so taking the squared
-        // deviations as sum(r^2) - sum(r)^2/n in fp32 loses about 1e-7 * (1 + mean^2/variance) of them.
+        const float p0 = bf16_to_f32(f32_to_bf16(acc[0][j][0]));
+        const float p1 = other_half(p0);
+        const float pivot = (lane & 32) ? p1 : p0;
+        // four independent chains each, then the other half of the column from lane ^ 32
         float s4[4] = {0.f, 0.f, 0.f, 0.f}, q4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            float rv = bf16_to_f32(f32_to_bf16(acc[i][j][v]));
-            if (!full) rv = (rbase + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4) < a.Mg) ? rv : 0.f;
-            s4[v % 4] += rv;
-            q4[v % 4] = fmaf(rv, rv, q4[v % 4]);
+            float dev = bf16_to_f32(f32_to_bf16(acc[i][j][v])) - pivot;
+            if (!full) dev = (rbase + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4) < a.Mg) ? dev : 0.f;
+            s4[v % 4] += dev;
+            q4[v % 4] = fmaf(dev, dev, q4[v % 4]);
           }
         float s1 = (s4[0] + s4[1]) + (s4[2] + s4[3]);
         float q1 = (q4[0] + q4[1]) + (q4[2] + q4[3]);
-        ssum[j] = s1 + other_half(s1);
-        sqsum[j] = q1 + other_half(q1);
+        s1 += other_half(s1);
+        q1 += other_half(q1);
+        ssum[j] = fmaf((float)wcnt, pivot, s1);             // the row block's sum
+        sqsum[j] = fmaxf(q1 - s1 * s1 * inv_cnt, 0.f);      // ... and squared deviations from its own mean
       }
     }
   }
@@ -640,17 +649,22 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
       }
       __syncthreads();
       if (wave / WN == 0 && lane < 32) {
+        // two row blocks (n_a and n_b rows, sums s, squared deviations q from their own means) joined:
+        // q = q_a + q_b + (s_a/n_a - s_b/n_b)^2 n_a n_b / (n_a + n_b)
         const int cnt = min(max(a.Mg - m0, 0), BM);
-        const float inv_cnt = cnt > 0 ? 1.f / (float)cnt : 0.f;
+        const int nb = cnt - wcnt;  // valid rows of the other row block
+        const float fa = (float)wcnt, fb = (float)nb;
+        const float inv_a = wcnt > 0 ? 1.f / fa : 0.f, inv_b = nb > 0 ? 1.f / fb : 0.f;
+        const float wgt = nb > 0 ? fa * fb / (fa + fb) : 0.f;
         float* part = a.stats + (long long)(m0 / BM) * 2 * a.Ng;
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
-          const float s1 = ssum[j] + ex[(j * 32 + lane) * 2];
-          const float q1 = sqsum[j] + ex[(j * 32 + lane) * 2 + 1];
+          const float sb = ex[(j * 32 + lane) * 2], qb = ex[(j * 32 + lane) * 2 + 1];
+          const float dm = ssum[j] * inv_a - sb * inv_b;
           const int col = n0 + brow + j * 32 + lane;
           if (col < a.Ng && cnt > 0) {  // a run with no valid row has no slot
-            part[col] = s1;
-            part[a.Ng + col] = fmaxf(q1 - s1 * s1 * inv_cnt, 0.f);
+            part[col] = ssum[j] + sb;
+            part[a.Ng + col] = sqsum[j] + qb + dm * dm * wgt;
           }
         }
       }

@@ -397,7 +397,32 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ param, flo
   }
 }
 
+// dst[i] = bf16(src[i]), round to nearest even
+__global__ __launch_bounds__(256) void round_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst,
+                                                         long long n4, long long n) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (; i < n4; i += stride) {
+    const float4 p = reinterpret_cast<const float4*>(src)[i];
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16(p.x) | ((uint32_t)f32_to_bf16(p.y) << 16);
+    o.y = (uint32_t)f32_to_bf16(p.z) | ((uint32_t)f32_to_bf16(p.w) << 16);
+    reinterpret_cast<uint2*>(dst)[i] = o;
+  }
+  for (long long j = n4 * 4 + (long long)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += stride) dst[j] = f32_to_bf16(src[j]);
+}
+
 }  // namespace
+
+int round_to_bf16(size_t count, const float* src, void* dst, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  const long long n4 = (long long)(count / 4);
+  long long blocks = (n4 + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(round_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, src, (bf16_t*)dst, n4, (long long)count);
+  return launch_status("round_to_bf16");
+}
 
 bool pool_saves_positions(const s4tf_pool_desc& d) {
   return d.kind == S4TF_POOL_MAX3S2 && d.c % (d.dtype == S4TF_BF16 ? 8 : 4) == 0;

@@ -150,6 +150,9 @@ int head_fwd_vjp(const s4tf_head_desc& d, const void* x, const float* W, const f
                  const int32_t* labels, float* loss, void* dx, float* dW, float* db, float* logits,
                  void* ws, hipStream_t st);
 
+// storage-type conversion: dst[i] = bf16(src[i]), round to nearest even
+int round_to_bf16(size_t count, const float* src, void* dst, hipStream_t st);
+
 // optimizer
 int sgd(size_t count, float* param, float* vel, const float* grad, void* lowp, float lr, float mu,
         hipStream_t st);

@@ -8,19 +8,17 @@ on its own: the op's INPUTS are the tensors the GPU itself produced (read back f
 workspace), its expected OUTPUT is the oracle's op applied to those inputs, and that is compared
 with what the GPU stored.  A chain of steps that are each correct is correct as a whole, and each
 comparison is as tight as a single-op test.  Big convolutions are checked on sampled output
-pixels / filter slices, each computed from the plain definition; everything else in full.
+pixels / filter slices, each computed from the plain definition; everything else in full
+(`full_flops=float("inf")` checks every convolution in full: the full-size headline workload does).
+Every comparison is norm-wise (relative L2, the gate; relative max-norm reported) and element by
+element (parity_metrics.py), so that a wrong row inside a large tensor cannot hide in the norm.
 """
 import numpy as np
 
 from oracle import oracle as orc
+from parity_metrics import rel_l2, rel_inf, check_tensor, elementwise_f32
 
 FULL_FLOPS = 3e9   # convolutions cheaper than this are checked on every output element
-
-
-def rel_l2(a, b):
-    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
-    den = np.linalg.norm(b)
-    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
 
 
 def _act(z, act):
@@ -83,8 +81,10 @@ def conv_rows_dgrad(dz, w, op, xshape, pos):
 
 
 class LocalChecker:
-    def __init__(self, net, wl, state, samples=192, seed=0):
+    def __init__(self, net, wl, state, samples=192, seed=0, full_flops=None, progress=None):
         self.net, self.wl, self.st = net, wl, state
+        self.full_flops = full_flops
+        self.progress = progress or (lambda msg: None)
         self.ops = net["ops"]
         self.bf16 = net["dtype"] == "bf16"
         self.rnd = (lambda a: orc.round_bf16(a)) if self.bf16 else (lambda a: a)
@@ -94,6 +94,7 @@ class LocalChecker:
         self.rng = np.random.default_rng(seed)
         self.x = np.asarray(wl["x"], np.float64)
         self.report = []
+        self.detail = []   # (what, rel-L2, bound, rel-inf, element-wise summary) of every tensor comparison
         # resolve flatten aliases
         self.root = [0]
         for i, op in enumerate(self.ops):
@@ -112,8 +113,16 @@ class LocalChecker:
         return self.st.tensor(self.root[t], cotangent=True)
 
     def note(self, what, err, tol):
+        """A scalar measure against its bound."""
         self.report.append((what, err, tol))
-        assert err <= tol, "%s: rel-L2 %.3g > %.3g" % (what, err, tol)
+        assert err <= tol, "%s: %.3g > %.3g" % (what, err, tol)
+
+    def tensor_check(self, what, got, ref, tol, lowp=None, atol=None):
+        """A tensor against the oracle's: relative L2 against tol, and every element (lowp: the tensor is
+        stored in bf16, ref is already rounded; default: the net's storage type)."""
+        rec = check_tensor(what, got, ref, self.bf16 if lowp is None else lowp, tol, atol)
+        self.report.append((rec[0], rec[1], rec[2]))
+        self.detail.append(rec)
 
     def conv_w(self, i):
         w = np.asarray(self.wl["params"][i][0], np.float64)
@@ -121,7 +130,7 @@ class LocalChecker:
 
     def conv_is_small(self, op, xshape, yshape):
         flops = 2.0 * yshape[0] * yshape[1] * yshape[2] * yshape[3] * op["r"] * op["s"] * xshape[3] / op["groups"]
-        return flops <= FULL_FLOPS or op["groups"] > 1
+        return flops <= (FULL_FLOPS if self.full_flops is None else self.full_flops) or op["groups"] > 1
 
     # -- forward -----------------------------------------------------------------------------------
     def check_forward(self):
@@ -129,6 +138,7 @@ class LocalChecker:
             kind = op["kind"]
             if kind == "flatten":
                 continue
+            self.progress("%s: checking the forward pass, op %d of %d" % (self.net["name"], i, len(self.ops)))
             x = self.act(op["in"])
             y = self.act(i + 1)
             p = self.wl["params"][i]
@@ -137,7 +147,7 @@ class LocalChecker:
                 bias = np.asarray(p[1], np.float64) if op["bias"] else None
                 if self.conv_is_small(op, x.shape, y.shape):
                     ref = self.rnd(_act(orc.conv2d_fwd(x, w, bias, op["stride"], op["pad"], op["groups"]), op["act"]))
-                    self.note("op %d conv fwd" % i, rel_l2(y, ref), self.tol_act)
+                    self.tensor_check("op %d conv fwd" % i, y, ref, self.tol_act)
                 else:
                     n_, p_, q_, _ = y.shape
                     pos = np.stack([self.rng.integers(0, n_, self.samples), self.rng.integers(0, p_, self.samples),
@@ -146,7 +156,7 @@ class LocalChecker:
                     pos[1] = (n_ - 1, p_ - 1, q_ - 1)
                     ref = self.rnd(_act(conv_rows_fwd(x, w, bias, op, pos), op["act"]))
                     got = y[pos[:, 0], pos[:, 1], pos[:, 2]]
-                    self.note("op %d conv fwd (sampled)" % i, rel_l2(got, ref), self.tol_act)
+                    self.tensor_check("op %d conv fwd (sampled)" % i, got, ref, self.tol_act)
             elif kind == "bn":
                 res = self.act(op["res"]) if op["res"] >= 0 else None
                 ref, mean, invstd = orc.bn_act_fwd(x, res, p[0], p[1], op["eps"], op["act"])
@@ -154,12 +164,13 @@ class LocalChecker:
                 # in units of the channel's standard deviation (a mean can be exactly zero: BatchNorm
                 # without activation followed by a 1x1 convolution)
                 self.note("op %d bn mean" % i, float(np.max(np.abs(gm - mean) * invstd)), 2e-5)
-                self.note("op %d bn invstd" % i, rel_l2(gi, invstd), 5e-5)
-                self.note("op %d bn fwd" % i, rel_l2(y, self.rnd(ref)), self.tol_act)
+                self.note("op %d bn invstd" % i, float(np.max(np.abs(gi - invstd) / invstd)), 5e-5)
+                self.tensor_check("op %d bn fwd" % i, y, self.rnd(ref), self.tol_act)
             elif kind == "avgpool2":
-                self.note("op %d avgpool fwd" % i, rel_l2(y, self.rnd(orc.avgpool2_fwd(x))), self.tol_act)
+                self.tensor_check("op %d avgpool fwd" % i, y, self.rnd(orc.avgpool2_fwd(x)), self.tol_act)
             elif kind == "maxpool3s2":
-                self.note("op %d maxpool fwd" % i, rel_l2(y, orc.maxpool3s2_fwd(x)), 0.0)
+                assert np.array_equal(y, orc.maxpool3s2_fwd(x)), "op %d maxpool fwd: not bit-exact" % i
+                self.report.append(("op %d maxpool fwd" % i, 0.0, 0.0))
 
     # -- head + backward ------------------------------------------------------------------------------
     def check_backward(self, results):
@@ -194,8 +205,8 @@ class LocalChecker:
         Wh, bh = self.wl["params"][-1]
         l_ref, dx_ref, dW_ref, db_ref, _ = orc.head_fwd_vjp(xh, Wh, bh, self.wl["labels"])
         self.note("head loss", abs(results["loss"] - l_ref) / abs(l_ref), 2e-5)
-        self.note("head dW", rel_l2(grads[-1][0], dW_ref), 1e-4)
-        self.note("head db", rel_l2(grads[-1][1], db_ref), 1e-4)
+        self.tensor_check("head dW", grads[-1][0], dW_ref, 1e-4, lowp=False)
+        self.tensor_check("head db", grads[-1][1], db_ref, 1e-4, lowp=False)
         rt = self.root[hop["in"]]
         if rt != 0:
             add(rt, pick(rt, dx_ref))
@@ -204,6 +215,7 @@ class LocalChecker:
             kind = op["kind"]
             if kind == "flatten":
                 continue
+            self.progress("%s: checking the backward pass, op %d of %d" % (self.net["name"], i, len(self.ops)))
             t_in = self.root[op["in"]]
             x = self.act(op["in"])
             y = self.act(i + 1)
@@ -221,9 +233,9 @@ class LocalChecker:
                 if self.conv_is_small(op, x.shape, y.shape):
                     dxr, dwr, dbr = orc.conv2d_vjp(x, w, dz, op["stride"], op["pad"], op["groups"], need_dx=want_dx,
                                                    need_db=op["bias"])
-                    self.note("op %d conv dw" % i, rel_l2(grads[i][0], dwr), self.tol_par)
+                    self.tensor_check("op %d conv dw" % i, grads[i][0], dwr, self.tol_par, lowp=False)
                     if op["bias"]:
-                        self.note("op %d conv db" % i, self._rel_or_abs(grads[i][1], dbr, dz), self.tol_par)
+                        self.sum_check("op %d conv db" % i, grads[i][1], dbr, np.abs(dz), self.tol_par)
                     if want_dx:
                         add(t_in, pick(t_in, dxr))
                 else:
@@ -231,7 +243,7 @@ class LocalChecker:
                     cs = np.sort(self.rng.choice(c_, size=min(4, c_), replace=False))
                     _, dwr, _ = orc.conv2d_vjp(np.ascontiguousarray(x[..., cs]), np.ascontiguousarray(w[:, :, cs, :]), dz,
                                                op["stride"], op["pad"], 1, need_dx=False)
-                    self.note("op %d conv dw (channel slice)" % i, rel_l2(grads[i][0][:, :, cs, :], dwr), self.tol_par)
+                    self.tensor_check("op %d conv dw (channel slice)" % i, grads[i][0][:, :, cs, :], dwr, self.tol_par, lowp=False)
                     if want_dx and pos_of.get(t_in) is not None:
                         add(t_in, conv_rows_dgrad(dz, w, op, x.shape, pos_of[t_in]))
                     elif want_dx:   # a reinterpreted (flattened) input: small, checked in full
@@ -240,8 +252,12 @@ class LocalChecker:
                 _, mean, invstd = orc.bn_act_fwd(x, self.act(op["res"]) if op["res"] >= 0 else None, p[0], p[1], op["eps"],
                                                  op["act"])
                 dxr, dres, dg, db = orc.bn_act_vjp(x, y, p[0], mean, invstd, dy, op["act"], op["res"] >= 0)
-                self.note("op %d bn dgamma" % i, self._rel_or_abs(grads[i][0], dg, dy), 2e-4)
-                self.note("op %d bn dbeta" % i, self._rel_or_abs(grads[i][1], db, dy), 2e-4)
+                dza = np.abs(dy) if op["act"] == "none" else np.abs(dy) * _mask(y, op["act"])
+                self.sum_check("op %d bn dbeta" % i, grads[i][1], db, dza, 2e-4)
+                dza *= np.abs(x - mean)
+                dza *= invstd
+                self.sum_check("op %d bn dgamma" % i, grads[i][0], dg, dza, 2e-4)
+                del dza
                 if op["res"] >= 0:
                     add(self.root[op["res"]], pick(self.root[op["res"]], dres))
                 add(t_in, pick(t_in, dxr))
@@ -250,12 +266,19 @@ class LocalChecker:
             elif kind == "maxpool3s2":
                 add(t_in, pick(t_in, orc.maxpool3s2_vjp(x, dy)))
 
-    def _rel_or_abs(self, got, ref, dy):
-        """Relative L2 error, or 0 when both are rounding noise around an exactly-zero sum."""
-        scale = float(np.abs(dy).sum(axis=(0, 1, 2)).max())
-        if float(np.abs(got - ref).max()) <= 1e-6 * scale:
-            return 0.0
-        return rel_l2(got, ref)
+    def sum_check(self, what, got, ref, terms_abs, tol):
+        """A per-channel sum of cotangent terms (bias gradient, dbeta, dgamma) whose terms may cancel, even
+        exactly (the beta of a BatchNorm that feeds a convolution followed by BatchNorm has gradient zero).
+        Its error is measured against the sum of the magnitudes of its terms S[c] = sum |term|:
+        norm-wise, relative L2 <= tol unless the whole difference is below 1e-6 max S (both sides are then
+        rounding noise around a sum that cancels); element-wise, |got - ref| <= 1e-4 |ref| + 2e-6 S[c]."""
+        S = terms_abs.reshape(-1, terms_abs.shape[-1]).sum(axis=0)
+        d = np.abs(np.asarray(got, np.float64) - ref)
+        e2 = 0.0 if float(d.max()) <= 1e-6 * float(S.max()) else rel_l2(got, ref)
+        self.note(what, e2, tol)
+        worst = float((d / (1e-4 * np.abs(ref) + 2e-6 * S + 1e-300)).max())
+        assert worst <= 1.0, "%s: element-wise check failed (worst element %.3g of its bound)" % (what, worst)
+        self.detail.append((what, e2, tol, rel_inf(got, ref), "worst element %.3g of its bound" % worst))
 
     def _check_cotangent(self, t, contrib, pos_of, dy_gpu, post=None):
         t = self.root[t]
@@ -270,9 +293,9 @@ class LocalChecker:
         if post is not None:
             exp = exp * sel(post)
         tol = self.tol_act * (1.0 + 0.5 * (len(parts) - 1))
-        self.note("tensor %d cotangent (%d contribution%s%s)" % (t, len(parts), "s" if len(parts) > 1 else "",
-                                                                "" if pos is None else ", sampled"),
-                  rel_l2(got, exp), tol)
+        self.tensor_check("tensor %d cotangent (%d contribution%s%s)" % (t, len(parts), "s" if len(parts) > 1 else "",
+                                                                        "" if pos is None else ", sampled"),
+                          got, exp, tol)
 
     def check_update(self, results, lr, momentum):
         """velocity = momentum*0 + grad and param = param0 - lr*velocity for a first step."""

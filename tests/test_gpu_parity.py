@@ -1,16 +1,30 @@
 """GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
 
-Tolerances.  Relative L2 error per tensor, ||gpu - oracle||_2 / ||oracle||_2.
- fp32 storage: the GPU accumulates in fp32, the oracle in fp64; per-op outputs agree to ~1e-6,
-   the bound used is 2e-5 (1e-4 for long reductions).  Whole steps use the workload's stated
-   bounds: 1e-4 on the loss, 1e-3 on every gradient and updated parameter.
- bf16 storage: both sides round the same tensors to bf16 (ties to even) but accumulate in
-   different precisions, so a few outputs land on the other side of a rounding boundary
-   (one bf16 ulp = 2^-8 relative).  Per-op bound 4e-3 for bf16 outputs, 2e-3 for fp32
-   outputs computed from bf16 inputs; whole steps 5e-3 on the loss, 2e-2 on gradients.
- A gradient that is exactly zero in exact arithmetic (the beta of a BatchNorm that feeds a
- 1x1 convolution followed by BatchNorm) is compared on an absolute scale instead.
+Every tensor is compared norm-wise AND element by element (parity_metrics.py).
+ Norm-wise, relative L2 error ||gpu - oracle||_2 / ||oracle||_2 (relative max-norm reported beside it):
+  fp32 storage: the GPU accumulates in fp32, the oracle in fp64; per-op outputs agree to ~1e-6, the bound
+    used is 2e-5 (1e-4 for long reductions).  Whole steps use the workload's stated bounds: 1e-4 on the
+    loss, 1e-3 on every gradient and updated parameter.
+  bf16 storage: both sides round the same tensors to bf16 (ties to even) but accumulate in different
+    precisions, so a few outputs land on the other side of a rounding boundary (one bf16 ulp = 2^-8
+    relative).  Per-op bound 4e-3 for bf16 outputs, 2e-3 for fp32 outputs computed from bf16 inputs;
+    whole steps 5e-3 on the loss, 2e-2 on gradients.
+ Element-wise: fp32 results |gpu - oracle| <= 1e-4 |oracle| + 1e-4 rms(oracle); bf16 results within one
+  bf16 ulp of the oracle's rounded value on at least 99.9 % of the elements and within two everywhere
+  (after an absolute allowance of 3e-5 rms for elements that cancellation leaves near zero).
+Output buffers of the per-op sweeps are allocated with guard regions before and after, pre-filled with
+NaN (every element must be written) and the guards are verified after each test (nothing else written).
+
+End-to-end gradient comparisons (see compare_step_strict / compare_step_full_size): small fp32 nets run
+on workloads made kink free (kink_free.py; margins asserted on the CPU), where every gradient and
+parameter must meet the stated bounds with no exception; full-size nets have tens of millions of
+pre-activations, some of which sit within rounding distance of a ReLU kink whatever the seed, so there
+the number of differing activation decisions is bounded and the median per-tensor gradient error is held
+to the stated bound, beside the per-op checks of the same finished step (local_check.py), which hold
+every tensor of the step to the per-op bounds.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -20,9 +34,17 @@ from workloads import nets
 torch = pytest.importorskip("torch")
 from paper_2102_13243_amd import binding as B  # noqa: E402
 from local_check import LocalChecker  # noqa: E402
+from parity_metrics import rel_l2, rel_inf, check_tensor  # noqa: E402
+import kink_free as KF  # noqa: E402
+import step_compare  # noqa: E402
+from conftest import progress  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+GUARD = 256          # guard elements before and after every output buffer
+GUARD_VALUE = -7.0   # exactly representable in bf16 and fp32
+_guarded = []
+_REPORT = []
 
 
 def to_dev(a, bf16=False, dtype=None):
@@ -30,7 +52,7 @@ def to_dev(a, bf16=False, dtype=None):
         return None
     t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32 if dtype is None else dtype))
     if bf16:
-        t = t.to(torch.bfloat16)
+        t = t.to(torch.bfloat16)   # values are on the bf16 grid already: exact
     return t.to(DEV)
 
 
@@ -40,17 +62,57 @@ def to_host(t):
 
 
 def empty(shape, bf16=False):
-    return torch.full(tuple(shape), float("nan"), dtype=torch.bfloat16 if bf16 else torch.float32, device=DEV)
+    """An output buffer: NaN-filled, with guard regions on both sides that no kernel may touch."""
+    n = int(np.prod(shape))
+    buf = torch.full((n + 2 * GUARD,), GUARD_VALUE, dtype=torch.bfloat16 if bf16 else torch.float32, device=DEV)
+    view = buf[GUARD:GUARD + n].view(*shape)
+    view.fill_(float("nan"))
+    _guarded.append((buf, n))
+    return view
 
 
 def ws(nbytes):
-    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=DEV)
+    n = max(int(nbytes), 16)
+    n = (n + 15) // 16 * 16
+    buf = torch.full((n + 2 * GUARD,), 0xA5, dtype=torch.uint8, device=DEV)
+    _guarded.append((buf, n))
+    return buf[GUARD:GUARD + n]
 
 
-def rel_l2(a, b):
-    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
-    den = np.linalg.norm(b)
-    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
+@pytest.fixture(autouse=True)
+def canaries():
+    """After every test: the guard regions of every buffer handed out by empty() / ws() are intact."""
+    _guarded.clear()
+    yield
+    torch.cuda.synchronize()
+    for buf, n in _guarded:
+        want = 0xA5 if buf.dtype == torch.uint8 else GUARD_VALUE
+        assert bool((buf[:GUARD] == want).all()) and bool((buf[GUARD + n:] == want).all()), \
+            "a kernel wrote outside an output buffer of %d elements" % n
+    _guarded.clear()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def report_file():
+    """The measured errors of every comparison, for the record (gpurun_out/ is where GPU runs leave files)."""
+    yield
+    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(out) and _REPORT:
+        with open(os.path.join(out, "parity_report.txt"), "w") as f:
+            f.write("\n".join(_REPORT) + "\n")
+
+
+def say(line):
+    print(line)
+    _REPORT.append(line)
+
+
+def check(what, got, ref, bf16, l2_tol, atol=None):
+    """got: device tensor or host array; ref: the oracle's value (rounded here when bf16)."""
+    g = to_host(got) if isinstance(got, torch.Tensor) else np.asarray(got, np.float64)
+    r = orc.round_bf16(ref) if bf16 else np.asarray(ref, np.float64)
+    rec = check_tensor(what, g, r, bf16, l2_tol, atol)
+    say("%-40s rel-L2 %.3g (bound %.3g) rel-inf %.3g; %s" % (rec[0], rec[1], rec[2], rec[3], rec[4]))
 
 
 def grid(a, bf16):
@@ -59,9 +121,17 @@ def grid(a, bf16):
     return nets.to_bf16_grid(a) if bf16 else a
 
 
+def compare_step_strict(net, wl, gpu, ref, **kw):
+    step_compare.compare_step_strict(net, wl, gpu, ref, say=say, **kw)
+
+
+def compare_step_full_size(net, gpu, ref, loss_tol, median_tol):
+    step_compare.compare_step_full_size(net, gpu, ref, loss_tol, median_tol, say=say)
+
+
 RNG = np.random.default_rng(11)
 
-# n h w c k r stride pad
+# n h w c k r stride pad [s]   (s: filter width when it differs from the height r)
 CONV_SHAPES = [
     (2, 9, 9, 8, 16, 3, 1, 1),        # single tile, vector path
     (3, 17, 13, 16, 24, 3, 1, 1),     # ragged M, N < tile
@@ -87,52 +157,54 @@ CONV_SHAPES = [
     (1, 11, 11, 64, 64, 5, 2, 2),     # ... 5x5: two or three taps per axis and class
     (2, 14, 14, 64, 64, 3, 2, 0),     # ... no padding: the last input row and column meet no output pixel
     (2, 64, 64, 32, 64, 3, 1, 1),     # fp32: enough work and few enough tiles for the 64x32 and 32x32 tiles
+    (2, 12, 14, 16, 24, 1, 1, 1, 3),  # filters that are not square: 1x3 (pad 1 also pads the height)
+    (2, 13, 12, 64, 64, 3, 1, 1, 1),  # 3x1, fast path
+    (2, 14, 15, 64, 128, 5, 2, 2, 3), # 5x3 with stride 2: parity classes with different tap counts per axis
+    (2, 10, 11, 3, 8, 3, 1, 1, 5),    # 3x5, element-wise loader
 ]
 
 
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
 @pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_conv2d_fwd_and_vjp(shape, bf16):
-    n, h, w, c, k, r, stride, pad = shape
+    n, h, w, c, k, r, stride, pad = shape[:8]
+    s = shape[8] if len(shape) > 8 else r
     x = grid(RNG.standard_normal((n, h, w, c)), bf16)
-    wt = grid(RNG.standard_normal((r, r, c, k)) * np.sqrt(2.0 / (r * r * c)), bf16)
+    wt = grid(RNG.standard_normal((r, s, c, k)) * np.sqrt(2.0 / (r * s * c)), bf16)
     bias = RNG.standard_normal(k).astype(np.float32)
-    d = B.ConvDesc(n, h, w, c, k, r, r, stride, pad, 1, B.S4TF_BF16 if bf16 else B.S4TF_F32, B.ACT["relu"], 0)
+    d = B.ConvDesc(n, h, w, c, k, r, s, stride, pad, 1, B.S4TF_BF16 if bf16 else B.S4TF_F32, B.ACT["relu"], 0)
     p = (h + 2 * pad - r) // stride + 1
-    q = (w + 2 * pad - r) // stride + 1
+    q = (w + 2 * pad - s) // stride + 1
     xd, wd, bd = to_dev(x, bf16), to_dev(wt, bf16), to_dev(bias)
     y = empty((n, p, q, k), bf16)
     B.s4tf_conv2d_fwd(d, xd, wd, bd, y)
     y_ref = orc.bias_act_fwd(orc.conv2d_fwd(x, wt, bias, stride, pad), None, "relu")
     if bf16:
         y_ref = orc.round_bf16(y_ref)
-    y_gpu = to_host(y)
-    assert np.isfinite(y_gpu).all()
-    assert rel_l2(y_gpu, y_ref) < (4e-3 if bf16 else 2e-5)
+    tol_act = 4e-3 if bf16 else 2e-5
+    tol_par = 2e-3 if bf16 else 1e-4
+    check("conv y", y, y_ref, bf16, tol_act)
     # pullback, from the oracle's y so that both sides use the same activation mask
     dy = grid(RNG.standard_normal((n, p, q, k)), bf16)
     dz_ref, _ = orc.bias_act_vjp(y_ref, dy, "relu", need_db=False)
     dx_ref, dw_ref, db_ref = orc.conv2d_vjp(x, wt, dz_ref, stride, pad, need_dx=True, need_db=True)
-    dx = empty((n, h, w, c), bf16)
-    dx.fill_(float("nan"))   # every element must be written, also those no output pixel reads
-    dw, db = empty((r, r, c, k)), empty((k,))
+    dx = empty((n, h, w, c), bf16)   # NaN-filled: every element must be written, also those no output pixel reads
+    dw, db = empty((r, s, c, k)), empty((k,))
     wsp = ws(B.s4tf_conv2d_vjp_workspace_bytes(d))
     B.s4tf_conv2d_vjp(d, xd, wd, to_dev(y_ref, bf16), to_dev(dy, bf16), dx, dw, db, wsp)
-    tol_act = 4e-3 if bf16 else 2e-5
-    tol_par = 2e-3 if bf16 else 1e-4
-    assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < tol_act
-    assert rel_l2(to_host(dw), dw_ref) < tol_par
-    assert rel_l2(to_host(db), db_ref) < tol_par
+    check("conv dx", dx, dx_ref, bf16, tol_act)
+    check("conv dw", dw, dw_ref, False, tol_par)
+    check("conv db", db, db_ref, False, tol_par)
     # accumulate into an existing cotangent, no bias gradient, no dx
     d.accumulate_dx = 1
     base = grid(RNG.standard_normal((n, h, w, c)), bf16)
-    dx2 = to_dev(base, bf16)
+    dx2 = empty((n, h, w, c), bf16)
+    dx2.copy_(to_dev(base, bf16))
     B.s4tf_conv2d_vjp(d, xd, wd, to_dev(y_ref, bf16), to_dev(dy, bf16), dx2, dw, None, wsp)
-    want = base + dx_ref
-    assert rel_l2(to_host(dx2), orc.round_bf16(want) if bf16 else want) < tol_act
+    check("conv dx accumulated", dx2, base + dx_ref, bf16, tol_act)
     dw.fill_(float("nan"))
     B.s4tf_conv2d_vjp(d, xd, wd, to_dev(y_ref, bf16), to_dev(dy, bf16), None, dw, None, wsp)
-    assert rel_l2(to_host(dw), dw_ref) < tol_par
+    check("conv dw alone", dw, dw_ref, False, tol_par)
 
 
 # n h w c r stride pad
@@ -160,14 +232,15 @@ def test_depthwise_conv(shape, bf16):
     y = empty((n, p, q, c), bf16)
     B.s4tf_conv2d_fwd(d, xd, wd, None, y)
     y_ref = orc.conv2d_fwd(x, wt, None, stride, pad, groups=c)
-    assert rel_l2(to_host(y), orc.round_bf16(y_ref) if bf16 else y_ref) < (4e-3 if bf16 else 2e-5)
+    tol_act = 4e-3 if bf16 else 2e-5
+    check("dw y", y, y_ref, bf16, tol_act)
     dy = grid(RNG.standard_normal((n, p, q, c)), bf16)
     dx_ref, dw_ref, _ = orc.conv2d_vjp(x, wt, dy, stride, pad, groups=c)
     dx, dw = empty((n, h, w, c), bf16), empty((r, r, 1, c))
     wsp = ws(B.s4tf_conv2d_vjp_workspace_bytes(d))
     B.s4tf_conv2d_vjp(d, xd, wd, None, to_dev(dy, bf16), dx, dw, None, wsp)
-    assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < (4e-3 if bf16 else 2e-5)
-    assert rel_l2(to_host(dw), dw_ref) < (2e-3 if bf16 else 1e-4)
+    check("dw dx", dx, dx_ref, bf16, tol_act)
+    check("dw dw", dw, dw_ref, False, 2e-3 if bf16 else 1e-4)
     if n * h * w * c > 4_000_000:
         return
     # bias and activation in the forward pass; the pullback accumulating into an existing cotangent
@@ -175,13 +248,13 @@ def test_depthwise_conv(shape, bf16):
     d2 = B.ConvDesc(n, h, w, c, c, r, r, stride, pad, c, B.S4TF_BF16 if bf16 else B.S4TF_F32, B.ACT["relu6"], 0)
     B.s4tf_conv2d_fwd(d2, xd, wd, to_dev(bias), y)
     y2_ref = orc.bias_act_fwd(orc.conv2d_fwd(x, wt, bias, stride, pad, groups=c), None, "relu6")
-    assert rel_l2(to_host(y), orc.round_bf16(y2_ref) if bf16 else y2_ref) < (4e-3 if bf16 else 2e-5)
+    check("dw y relu6", y, y2_ref, bf16, tol_act)
     base = grid(RNG.standard_normal((n, h, w, c)), bf16)
     d3 = B.ConvDesc(n, h, w, c, c, r, r, stride, pad, c, B.S4TF_BF16 if bf16 else B.S4TF_F32, B.ACT["none"], 1)
-    dx2 = to_dev(base, bf16)
+    dx2 = empty((n, h, w, c), bf16)
+    dx2.copy_(to_dev(base, bf16))
     B.s4tf_conv2d_vjp(d3, xd, wd, None, to_dev(dy, bf16), dx2, dw, None, wsp)
-    want = base + dx_ref
-    assert rel_l2(to_host(dx2), orc.round_bf16(want) if bf16 else want) < (4e-3 if bf16 else 2e-5)
+    check("dw dx accumulated", dx2, base + dx_ref, bf16, tol_act)
 
 
 BN_SHAPES = [(2, 5, 7, 16), (4, 16, 16, 64), (3, 9, 9, 6), (2, 7, 7, 960), (64, 8, 8, 32), (1, 1, 3, 8)]
@@ -202,38 +275,41 @@ def test_bn_relu_fwd_and_vjp(shape, act, use_res, bf16):
     y, mean, invstd = empty(shape, bf16), empty((c,)), empty((c,))
     B.s4tf_bn_relu_fwd(d, xd, rd, gd, bd, y, mean, invstd, wsp)
     y_ref, mean_ref, invstd_ref = orc.bn_act_fwd(x, res, gamma, beta, 1e-5, act)
+    # statistics element by element: the mean in units of the channel's standard deviation
+    assert float(np.max(np.abs(to_host(mean) - mean_ref) * invstd_ref)) < 5e-6
+    assert float(np.max(np.abs(to_host(invstd) - invstd_ref) / invstd_ref)) < 2e-5
+    tol_act = 4e-3 if bf16 else 2e-5
+    check("bn y", y, y_ref, bf16, tol_act)
     if bf16:
         y_ref = orc.round_bf16(y_ref)
-    assert rel_l2(to_host(mean), mean_ref) < 2e-6
-    assert rel_l2(to_host(invstd), invstd_ref) < 2e-5
-    assert rel_l2(to_host(y), y_ref) < (4e-3 if bf16 else 2e-5)
     dy = grid(RNG.standard_normal(shape), bf16)
     dx_ref, dres_ref, dg_ref, db_ref = orc.bn_act_vjp(x, y_ref, gamma, mean_ref, invstd_ref, dy, act, use_res)
     dx, dres = empty(shape, bf16), (empty(shape, bf16) if use_res else None)
     dg, db = empty((c,)), empty((c,))
     B.s4tf_bn_relu_vjp(d, xd, to_dev(y_ref, bf16), gd, None, to_dev(mean_ref), to_dev(invstd_ref), to_dev(dy, bf16), dx,
                        dres, dg, db, wsp)
-    assert rel_l2(to_host(dg), dg_ref) < 1e-4
-    assert rel_l2(to_host(db), db_ref) < 1e-4
-    assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < (6e-3 if bf16 else 5e-5)
+    tol_dx = 6e-3 if bf16 else 5e-5
+    check("bn dgamma", dg, dg_ref, False, 1e-4)
+    check("bn dbeta", db, db_ref, False, 1e-4)
+    check("bn dx", dx, dx_ref, bf16, tol_dx)
     if not use_res and act != "none":
         # beta given, no residual: the activation mask is rebuilt from x with the statistics the GPU's own
         # forward pass saved, y is not read (NULL).  An element whose z rounds to the other side of 0 (or 6)
-        # than the oracle's may differ; the tolerances are those of the first call.
+        # than the oracle's may differ; the norm-wise tolerances are those of the first call.
         dx.fill_(float("nan"))
         B.s4tf_bn_relu_vjp(d, xd, None, gd, bd, mean, invstd, to_dev(dy, bf16), dx, None, dg, db, wsp)
         assert rel_l2(to_host(dg), dg_ref) < 1e-4
         assert rel_l2(to_host(db), db_ref) < 1e-4
-        assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < (6e-3 if bf16 else 5e-5)
+        assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < tol_dx
     if use_res:
-        assert rel_l2(to_host(dres), dres_ref) == 0.0
+        assert np.array_equal(to_host(dres), dres_ref)   # dz = dy * act'(y): exact
         d.accumulate_dres = 1
         base = grid(RNG.standard_normal(shape), bf16)
-        dres2 = to_dev(base, bf16)
+        dres2 = empty(shape, bf16)
+        dres2.copy_(to_dev(base, bf16))
         B.s4tf_bn_relu_vjp(d, xd, to_dev(y_ref, bf16), gd, None, to_dev(mean_ref), to_dev(invstd_ref), to_dev(dy, bf16), dx,
                            dres2, dg, db, wsp)
-        want = base + dres_ref
-        assert rel_l2(to_host(dres2), orc.round_bf16(want) if bf16 else want) < (4e-3 if bf16 else 1e-6)
+        check("bn dres accumulated", dres2, base + dres_ref, bf16, 4e-3 if bf16 else 1e-6)
 
 
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
@@ -250,21 +326,22 @@ def test_pool2d(kind, shape, bf16):
     xd = to_dev(x, bf16)
     y = empty(y_ref.shape, bf16)
     B.s4tf_pool2d_fwd(d, xd, y)
+    tol = 4e-3 if bf16 else 1e-6
     if kind == B.POOL_MAX3S2:
         np.testing.assert_array_equal(to_host(y), y_ref)
     else:
-        assert rel_l2(to_host(y), orc.round_bf16(y_ref) if bf16 else y_ref) < (4e-3 if bf16 else 1e-6)
+        check("avgpool y", y, y_ref, bf16, tol)
     dy = grid(RNG.standard_normal(y_ref.shape), bf16)
     dx_ref = orc.avgpool2_vjp(dy, x.shape) if kind == B.POOL_AVG2 else orc.maxpool3s2_vjp(x, dy)
     dx = empty(shape, bf16)
     B.s4tf_pool2d_vjp(d, xd, to_dev(dy, bf16), dx)
-    assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < (4e-3 if bf16 else 1e-6)
+    check("pool dx", dx, dx_ref, bf16, tol)
     d.accumulate_dx = 1
     base = grid(RNG.standard_normal(shape), bf16)
-    dx2 = to_dev(base, bf16)
+    dx2 = empty(shape, bf16)
+    dx2.copy_(to_dev(base, bf16))
     B.s4tf_pool2d_vjp(d, xd, to_dev(dy, bf16), dx2)
-    want = base + dx_ref
-    assert rel_l2(to_host(dx2), orc.round_bf16(want) if bf16 else want) < (4e-3 if bf16 else 1e-6)
+    check("pool dx accumulated", dx2, base + dx_ref, bf16, tol)
 
 
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
@@ -282,11 +359,11 @@ def test_head(shape, bf16):
     B.s4tf_pool_dense_xent_fwd_vjp(d, to_dev(x, bf16), to_dev(W), to_dev(b), to_dev(labels, dtype=np.int32), loss, dx, dW,
                                    db, logits, wsp)
     l_ref, dx_ref, dW_ref, db_ref, z_ref = orc.head_fwd_vjp(x, W, b, labels)
-    assert rel_l2(to_host(logits), z_ref) < 2e-5
+    check("head logits", logits, z_ref, False, 2e-5)
     assert abs(to_host(loss)[0] - l_ref) < 1e-5 * abs(l_ref)
-    assert rel_l2(to_host(dW), dW_ref) < 5e-5
-    assert rel_l2(to_host(db), db_ref) < 5e-5
-    assert rel_l2(to_host(dx), orc.round_bf16(dx_ref) if bf16 else dx_ref) < (4e-3 if bf16 else 5e-5)
+    check("head dW", dW, dW_ref, False, 5e-5)
+    check("head db", db, db_ref, False, 5e-5)
+    check("head dx", dx, dx_ref, bf16, 4e-3 if bf16 else 5e-5)
     # W = 0, b = 0: loss = ln(classes)
     B.s4tf_pool_dense_xent_fwd_vjp(d, to_dev(x, bf16), to_dev(np.zeros_like(W)), to_dev(np.zeros_like(b)),
                                    to_dev(labels, dtype=np.int32), loss, None, dW, db, None, wsp)
@@ -298,12 +375,15 @@ def test_sgd_momentum(count):
     p = RNG.standard_normal(count).astype(np.float32)
     v = RNG.standard_normal(count).astype(np.float32)
     g = RNG.standard_normal(count).astype(np.float32)
-    pd, vd, gd = to_dev(p), to_dev(v), to_dev(g)
+    pd, vd, gd = empty((count,)), empty((count,)), to_dev(g)
+    pd.copy_(to_dev(p))
+    vd.copy_(to_dev(v))
     low = torch.zeros(count + 8, dtype=torch.bfloat16, device=DEV)
     B.s4tf_sgd_momentum(count, pd, vd, gd, low, 0.1, 0.9)
     p64, v64 = p.astype(np.float64), v.astype(np.float64)
     orc.sgd_momentum(p64, v64, g, 0.1, 0.9)
-    assert rel_l2(to_host(vd), v64) < 1e-6 and rel_l2(to_host(pd), p64) < 1e-6
+    check("sgd velocity", vd, v64, False, 1e-6, atol=1e-6)
+    check("sgd param", pd, p64, False, 1e-6, atol=1e-6)
     # the bf16 working copy is the rounded fp32 master (same precision on both sides)
     np.testing.assert_array_equal(to_host(low)[:count], orc.round_bf16(to_host(pd)))
     assert float(low[count:].abs().max()) == 0.0
@@ -317,71 +397,7 @@ def test_sgd_momentum(count):
 # ---------------------------------------------------------------------------------------------------
 # whole steps
 # ---------------------------------------------------------------------------------------------------
-def oracle_step_with_conditioning(net, wl, jitter=1e-7):
-    """The oracle's step, plus for every parameter gradient how far it moves (relative L2) when the
-    oracle's own convolution outputs are perturbed by a relative `jitter` at the fp32 rounding level.
-    Gradients that are sums of almost cancelling terms (the beta of a BatchNorm whose consumer is a
-    convolution followed by another BatchNorm) move by orders of magnitude more than the jitter;
-    no two implementations can agree on them end to end more closely than that."""
-    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
-    rng = np.random.default_rng(99)
-    fwd0 = orc.conv2d_fwd
-    try:
-        orc.conv2d_fwd = lambda *a, **k: (lambda y: y * (1.0 + jitter * rng.standard_normal(y.shape)))(fwd0(*a, **k))
-        jit = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
-    finally:
-        orc.conv2d_fwd = fwd0
-    ref["sensitivity"] = [[rel_l2(x, y) for x, y in zip(p, q)] for p, q in zip(jit["grads"], ref["grads"])]
-    return ref
-
-
-def compare_step(net, gpu, ref, loss_tol, grad_tol, param_tol):
-    """End-to-end comparison.  Bound per gradient tensor: grad_tol, widened to 100x the tensor's own
-    sensitivity to a 1e-7 jitter where that is larger (see oracle_step_with_conditioning).  When a
-    ReLU decision differs between the two forward passes the gradients are only reported: the two
-    runs then differentiate different piecewise-linear functions, and the step has already been
-    verified op by op by the local checks."""
-    assert abs(gpu["loss"] - ref["loss"]) <= loss_tol * abs(ref["loss"]), (gpu["loss"], ref["loss"])
-    flips = count_mask_flips(net, gpu, ref) if "state" in gpu and "tensors" in ref else 0
-    elems = sum(t.size for t in ref["tensors"][1:-1]) if "tensors" in ref else 1
-    assert flips <= max(3, 2e-6 * elems), ("activation decisions differ in too many places", flips, elems)
-    if flips:
-        errs = [rel_l2(a, b) for pg, pr in zip(gpu["grads"], ref["grads"]) for a, b in zip(pg, pr)]
-        print("\n%s: loss gpu %.7g oracle %.7g; %d of %d activation decisions differ, gradients not compared end to "
-              "end (median rel-L2 %.2g, max %.2g)" % (net["name"], gpu["loss"], ref["loss"], flips, elems,
-                                                      float(np.median(errs)), max(errs)))
-        return
-    gmax = max(float(np.abs(g).max()) for p in ref["grads"] for g in p)
-    sens = ref.get("sensitivity")
-    worst = {"grad": (0.0, None), "param": (0.0, None)}
-    widened, total = 0, 0
-    for i, (pg, pr) in enumerate(zip(gpu["grads"], ref["grads"])):
-        for j, (a, b) in enumerate(zip(pg, pr)):
-            assert np.isfinite(a).all(), (i, j)
-            total += 1
-            e = rel_l2(a, b)
-            if e > grad_tol and (float(np.abs(a - b).max()) <= 1e-6 * gmax or (sens is not None and sens[i][j] > 0.5)):
-                # a gradient that is exactly zero in exact arithmetic (the oracle's own value is rounding
-                # noise): both sides must be negligible on the scale of the net's gradients
-                assert float(np.abs(a).max()) <= 1e-4 * gmax and float(np.abs(b).max()) <= 1e-4 * gmax, (i, j)
-                continue
-            bound = grad_tol
-            if sens is not None and 100.0 * sens[i][j] > grad_tol:
-                bound = 100.0 * sens[i][j]
-                widened += 1
-            assert e <= bound, ("gradient", i, j, net["ops"][i]["kind"], e, bound)
-            assert rel_l2(gpu["velocity"][i][j], ref["velocity"][i][j]) <= bound, ("velocity", i, j)
-            if bound == grad_tol and e > worst["grad"][0]:
-                worst["grad"] = (e, (i, j, net["ops"][i]["kind"]))
-            ep = rel_l2(gpu["params"][i][j], ref["params"][i][j])
-            if ep > worst["param"][0]:
-                worst["param"] = (ep, (i, j))
-            assert ep <= max(param_tol, bound), ("param", i, j, ep)
-    print("\n%s: loss gpu %.7g oracle %.7g; worst rel-L2 grad %.3g at %s, param %.3g; %d of %d gradient tensors compared with a bound widened by their conditioning"
-          % (net["name"], gpu["loss"], ref["loss"], worst["grad"][0], worst["grad"][1], worst["param"][0], widened, total))
-
-
-def run_gpu_steps(net, wl, steps=1, local=False):
+def run_gpu_steps(net, wl, steps=1, local=False, full_flops=None):
     st = B.TrainState(net, wl["params"], DEV)
     xd, ld = st.upload_batch(wl["x"], wl["labels"])
     losses = []
@@ -390,30 +406,17 @@ def run_gpu_steps(net, wl, steps=1, local=False):
         torch.cuda.synchronize()
         losses.append(float(st.loss[0].item()))
     if local:   # every op of the finished step against the oracle op applied to the GPU's own inputs
-        ck = LocalChecker(net, wl, st)
+        ck = LocalChecker(net, wl, st, full_flops=full_flops, progress=progress)
         out, worst = ck.run()
-        print("\n%s: %d local checks passed; closest to their bounds: %s"
-              % (net["name"], len(ck.report), "; ".join("%s %.2g/%.2g" % w for w in worst)))
+        say("%s: %d local checks passed; closest to their bounds: %s"
+            % (net["name"], len(ck.report), "; ".join("%s %.2g/%.2g" % w for w in worst)))
+        for rec in ck.detail:
+            _REPORT.append("   %-52s rel-L2 %.3g (bound %.3g) rel-inf %.3g; %s" % rec)
     else:
         out = st.results()
     out["losses"] = losses
     out["state"] = st
     return out
-
-
-def count_mask_flips(net, gpu, ref):
-    """Elements whose ReLU / ReLU6 / max-pool decision differs between the GPU's and the oracle's
-    forward pass (one side sits at a kink, the other a rounding error away from it).  A single such
-    element changes the gradients downstream by about 1/sqrt(elements of its tensor)."""
-    st, flips = gpu["state"], 0
-    for i, op in enumerate(net["ops"][:-1]):
-        act = op.get("act", "none")
-        if op["kind"] in ("conv", "bn") and act != "none":
-            a, b = st.tensor(i + 1), ref["tensors"][i + 1]
-            flips += int(((a > 0) != (b > 0)).sum())
-            if act == "relu6":
-                flips += int(((a < 6) != (b < 6)).sum())
-    return flips
 
 
 SMALL_NETS = [
@@ -423,37 +426,73 @@ SMALL_NETS = [
     ("resnet50", dict(batch=4, hw=64, stages=(2, 1, 1, 1), classes=24, dtype="f32")),
     ("mobilenetv2", dict(batch=4, hw=64, classes=16)),
 ]
+KINK_MARGIN = 1e-4      # of a pre-activation's standard deviation; a hundred times the fp32/fp64 difference
+MAXPOOL_MARGIN = 1e-5   # gap between the two largest entries of a max-pool window, same units
+
+
+def kink_free_workload(net, perturb):
+    """Seeded workload whose pre-activations all keep KINK_MARGIN from every kink (asserted here, on the
+    CPU, with the oracle), so that the end-to-end comparison has exactly one right answer."""
+    wl, report = KF.make_kink_free(net, nets.make_workload(net, perturb=perturb), KINK_MARGIN)
+    for op, what, margin, _ in report:
+        assert margin >= (MAXPOOL_MARGIN if what == "maxpool" else KINK_MARGIN), (op, what, margin)
+    return wl
 
 
 @pytest.mark.parametrize("perturb", [False, True], ids=["init", "perturbed"])
 @pytest.mark.parametrize("name,kw", SMALL_NETS, ids=[n for n, _ in SMALL_NETS])
 def test_train_step_small_fp32(name, kw, perturb):
     net = nets.CONFIGS[name](**kw)
-    wl = nets.make_workload(net, perturb=perturb)
-    ref = oracle_step_with_conditioning(net, wl)
+    wl = kink_free_workload(net, perturb)
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"], keep_cotangents=True)
     gpu = run_gpu_steps(net, wl, local=True)
-    compare_step(net, gpu, ref, 1e-4, 1e-3, 1e-3)
+    compare_step_strict(net, wl, gpu, ref)
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("name,kw", [("resnet56", dict(batch=8, blocks_per_stage=2, hw=16)),
+                                     ("resnet50", dict(batch=8, hw=64, stages=(2, 2, 1, 1), classes=40)),
+                                     ("mobilenetv2", dict(batch=4, hw=64, classes=16))],
+                         ids=["resnet56", "resnet50", "mobilenetv2"])
+def test_train_step_with_large_channel_means(name, kw, bf16):
+    """Convolution outputs whose per-channel mean is several (up to tens of) standard deviations: the case in
+    which the BatchNorm statistics that the convolution kernels emit as a by-product (one pass over a run of
+    output rows) could lose digits.  The local checks hold mean and 1/std of every BatchNorm to 2e-5 std and
+    5e-5 against the oracle's two-pass float64 statistics of the same tensor."""
+    net = dict(nets.CONFIGS[name](**kw), dtype="bf16" if bf16 else "f32")
+    wl = nets.make_workload(net, perturb="shifted")
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+    big = 0.0
+    for i, op in enumerate(net["ops"][:-1]):
+        if op["kind"] == "conv" and op["groups"] == 1:
+            t = ref["tensors"][i + 1].reshape(-1, ref["tensors"][i + 1].shape[-1])
+            big = max(big, float(np.max(np.abs(t.mean(axis=0)) / (t.std(axis=0) + 1e-30))))
+    assert big >= 10.0, big
+    gpu = run_gpu_steps(net, wl, local=True)
+    say("%s %s shifted: largest |mean|/std of a convolution output channel %.1f; loss gpu %.6g oracle %.6g"
+        % (name, net["dtype"], big, gpu["loss"], ref["loss"]))
+    assert abs(gpu["loss"] - ref["loss"]) <= (5e-3 if bf16 else 1e-4) * abs(ref["loss"]), (gpu["loss"], ref["loss"])
 
 
 @pytest.mark.parametrize("name,kw", [("resnet50", dict(batch=8, hw=64, stages=(2, 2, 1, 1), classes=40)),
                                      ("mobilenetv2", dict(batch=4, hw=64, classes=16)),
                                      ("lenet5", dict(batch=16))], ids=["resnet50", "mobilenetv2", "lenet5"])
 def test_train_step_small_bf16(name, kw):
-    """bf16 storage.  Every op is checked locally; end to end only the loss is compared, and loosely:
-    these nets are tiny (BatchNorm over as few as 16 samples in the last stage), so two
-    differently-rounded runs drift apart by percents (see test_local_check_cpu.py).  The full-size
-    workload, whose statistics average over thousands of samples, is held to 5e-3."""
+    """bf16 storage.  Every op is checked locally, element by element; end to end the loss is held to the
+    workload's stated 5e-3."""
     net = dict(nets.CONFIGS[name](**kw), dtype="bf16")
     wl = nets.make_workload(net, perturb=True)
     wl["x"] = nets.to_bf16_grid(wl["x"])
     ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
     gpu = run_gpu_steps(net, wl, local=True)
-    assert abs(gpu["loss"] - ref["loss"]) <= 5e-2 * abs(ref["loss"]), (gpu["loss"], ref["loss"])
+    say("%s bf16 small: loss gpu %.7g oracle %.7g (rel %.2g)" % (name, gpu["loss"], ref["loss"],
+                                                                abs(gpu["loss"] - ref["loss"]) / abs(ref["loss"])))
+    assert abs(gpu["loss"] - ref["loss"]) <= 5e-3 * abs(ref["loss"]), (gpu["loss"], ref["loss"])
 
 
 def test_train_step_is_deterministic_and_in_place_equals_functional():
     net = nets.resnet56(batch=8, blocks_per_stage=1, hw=16)
-    wl = nets.make_workload(net)
+    wl = kink_free_workload(net, False)
     a = run_gpu_steps(net, wl)
     b = run_gpu_steps(net, wl)
     assert a["loss"] == b["loss"]
@@ -462,15 +501,17 @@ def test_train_step_is_deterministic_and_in_place_equals_functional():
             np.testing.assert_array_equal(x, y)
     # the caller's host copies of the parameters were not touched; the step updated the device
     # arena in place and its result equals the oracle's pure-function step
-    ref = oracle_step_with_conditioning(net, wl)
-    compare_step(net, a, ref, 1e-4, 1e-3, 1e-3)
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"], keep_cotangents=True)
+    compare_step_strict(net, wl, a, ref)
 
 
 def test_config1_tiny_block():
     net = nets.tiny_block()
     wl = nets.make_workload(net)
-    ref = oracle_step_with_conditioning(net, wl)
-    compare_step(net, run_gpu_steps(net, wl, local=True), ref, 1e-4, 1e-3, 1e-3)
+    margin = min(m for _, _, m, _ in KF.kink_margins(net, wl))
+    assert margin >= 1e-5, margin   # the configuration's own seed: no pre-activation near a kink
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"], keep_cotangents=True)
+    compare_step_strict(net, wl, run_gpu_steps(net, wl, local=True), ref)
 
 
 def test_config2_lenet_ten_steps():
@@ -485,34 +526,36 @@ def test_config2_lenet_ten_steps():
     assert gpu["losses"][-1] < gpu["losses"][0]
     np.testing.assert_allclose(gpu["losses"], ref_losses, rtol=1e-4)
     gpu["loss"] = gpu["losses"][-1]
-    compare_step(net, gpu, ref, 1e-4, 1e-3, 1e-3)
-    run_gpu_steps(net, wl, steps=1, local=True)
+    # after ten steps: eight million pre-activations have been through a ReLU on the way
+    compare_step_full_size(net, gpu, ref, 1e-4, 1e-3)
+    # the first step of the configuration, every op checked, and end to end
+    one = run_gpu_steps(net, wl, steps=1, local=True)
+    compare_step_full_size(net, one, orc.train_step(net, wl["x"], wl["labels"], wl["params"]), 1e-4, 1e-3)
 
 
 def test_config3_resnet56():
     net = nets.resnet56()
     wl = nets.make_workload(net)
-    ref = oracle_step_with_conditioning(net, wl)
-    compare_step(net, run_gpu_steps(net, wl, local=True), ref, 1e-4, 1e-3, 1e-3)
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+    compare_step_full_size(net, run_gpu_steps(net, wl, local=True), ref, 1e-4, 1e-3)
 
 
 def test_config5_mobilenetv2():
     net = nets.mobilenetv2()
     wl = nets.make_workload(net)
-    ref = oracle_step_with_conditioning(net, wl)
-    compare_step(net, run_gpu_steps(net, wl, local=True), ref, 1e-4, 1e-3, 1e-3)
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+    compare_step_full_size(net, run_gpu_steps(net, wl, local=True), ref, 1e-4, 1e-3)
 
 
 def test_config4_resnet50_bf16():
-    """Full size (batch 64, 224x224), the launch configuration the benchmark times."""
+    """Full size (batch 64, 224x224), the launch configuration the benchmark times.  Every convolution
+    forward, input gradient and filter gradient of the step is checked in full (no sampling), element by
+    element, like every other tensor of the step; then the step is compared end to end."""
     net = nets.resnet50()
     wl = nets.make_workload(net)
-    gpu = run_gpu_steps(net, wl, local=True)
-    tensors, _ = orc.forward(net, wl["x"], wl["params"])
-    ref_loss = orc.head_fwd_vjp(tensors[net["ops"][-1]["in"]], wl["params"][-1][0], wl["params"][-1][1], wl["labels"],
-                                need_dx=False)[0]
-    print("resnet50 bf16 loss: gpu %.6f oracle %.6f" % (gpu["loss"], ref_loss))
-    assert abs(gpu["loss"] - ref_loss) <= 5e-3 * abs(ref_loss)
+    gpu = run_gpu_steps(net, wl, local=True, full_flops=float("inf"))
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+    compare_step_full_size(net, gpu, ref, 5e-3, 2e-2)
 
 
 # ---- the same step dispatched op by op (the paper's eager mode, Section 3.3) ---------------------------
@@ -538,10 +581,10 @@ def test_eager_step_small_fp32(name, kw, sync):
     fan-in, one SGD call per parameter tensor: the result is the oracle's step, to the fused step's bar,
     and the two ways of running the step agree on the loss."""
     net = nets.CONFIGS[name](**kw)
-    wl = nets.make_workload(net, perturb=True)
-    ref = oracle_step_with_conditioning(net, wl)
+    wl = kink_free_workload(net, True)
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"], keep_cotangents=True)
     eager = run_eager_steps(net, wl, sync)
-    compare_step(net, eager, ref, 1e-4, 1e-3, 1e-3)
+    compare_step_strict(net, wl, eager, ref)
     fused = run_gpu_steps(net, wl)
     assert abs(eager["loss"] - fused["loss"]) <= 2e-5 * abs(fused["loss"]), (eager["loss"], fused["loss"])
 
@@ -558,10 +601,11 @@ def test_eager_lenet_ten_steps_and_bf16_loss():
     wl["x"] = nets.to_bf16_grid(wl["x"])
     ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
     eager = run_eager_steps(net, wl, sync=True, steps=2)
-    assert abs(eager["losses"][0] - ref["loss"]) <= 5e-2 * abs(ref["loss"]), (eager["losses"], ref["loss"])
+    assert abs(eager["losses"][0] - ref["loss"]) <= 5e-3 * abs(ref["loss"]), (eager["losses"], ref["loss"])
     assert np.isfinite(eager["losses"][1])
     st = eager["state"]
-    np.testing.assert_array_equal(st.lowp.float().cpu().numpy(), st.master.to(torch.bfloat16).float().cpu().numpy())
+    np.testing.assert_array_equal(st.lowp.view(torch.int16).cpu().numpy().view(np.uint16).astype(np.uint32) << 16,
+                                  nets.to_bf16_grid(st.master.cpu().numpy()).view(np.uint32))
 
 
 @pytest.mark.parametrize("name,kw", [("lenet5", dict(batch=16)),

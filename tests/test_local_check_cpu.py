@@ -13,6 +13,7 @@ import pytest
 from oracle import oracle as orc
 from workloads import nets
 import local_check as LC
+from parity_metrics import rel_l2
 
 
 class OracleBackedState:
@@ -104,6 +105,16 @@ def test_checker_accepts_the_oracle_and_rejects_planted_mistakes(name, kw, sampl
         b.out["tensors"][i + 1] = b.out["tensors"][i + 1] * 1.05
     expect_failure(scale_activation)
 
+    def one_wrong_row(b):          # one pixel's channels of a forward output off by 2 %: invisible in the tensor's norm
+        t = b.out["tensors"][i + 1]
+        t[0, 0, 0, :] = t[0, 0, 0, :] * 1.02 + 0.02 * np.abs(t).max()
+    expect_failure(one_wrong_row)
+
+    def one_wrong_filter_entry(b):
+        g = b.out["grads"][i][0]
+        g.reshape(-1)[0] += 1e-2 * np.sqrt(np.mean(g * g))
+    expect_failure(one_wrong_filter_entry)
+
     def wrong_wgrad(b):            # a transposed / dropped term shows up as a wrong filter gradient
         g = b.out["grads"][i][0]
         b.out["grads"][i][0] = g + 0.05 * np.abs(g).max() * rng.standard_normal(g.shape)
@@ -140,7 +151,7 @@ def test_whole_step_gradients_amplify_a_1e6_jitter(dtype, monkeypatch):
     wl = nets.make_workload(net)
     a = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
     b = _jittered_step(net, wl, 1e-6, monkeypatch)
-    errs = sorted(LC.rel_l2(x, y) for p, q in zip(b["grads"], a["grads"]) for x, y in zip(p, q))
+    errs = sorted(rel_l2(x, y) for p, q in zip(b["grads"], a["grads"]) for x, y in zip(p, q))
     median, worst = errs[len(errs) // 2], errs[-1]
     loss_err = abs(a["loss"] - b["loss"]) / abs(a["loss"])
     print("%s: jitter 1e-6 -> loss %.2e, median gradient rel-L2 %.2e, worst %.2e" % (dtype, loss_err, median, worst))

@@ -420,3 +420,52 @@ def test_bf16_step_rounds_stored_tensors_only():
     g = out["grads"][0][0]
     assert not np.array_equal(g, orc.round_bf16(g))
     assert np.isfinite(out["loss"])
+
+
+@pytest.mark.parametrize("act", ["none", "relu", "relu6"])
+def test_bn_forward_output_closed_form_with_every_input_nontrivial(act):
+    """y = act(gamma (x - mean)/sqrt(var + eps) + beta + residual), written out with NumPy: gamma, beta, the
+    residual and the clamp all enter (a dropped or doubled term, a residual added after the activation or a
+    gamma applied to the residual would each fail)."""
+    x = RNG.standard_normal((3, 5, 4, 7)) * 1.7 - 0.8
+    res = RNG.standard_normal(x.shape) * 2.0 + 1.0
+    gamma = 1.0 + 0.5 * RNG.standard_normal(7)
+    beta = RNG.standard_normal(7) + 2.5
+    eps = 1e-3
+    xf = x.reshape(-1, 7)
+    z = gamma * (x - xf.mean(0)) / np.sqrt(((xf - xf.mean(0)) ** 2).mean(0) + eps) + beta + res
+    want = z if act == "none" else np.maximum(z, 0.0) if act == "relu" else np.minimum(np.maximum(z, 0.0), 6.0)
+    if act == "relu6":
+        assert (z > 6).any() and (z < 0).any()   # both clamps are exercised
+    y, _, _ = orc.bn_act_fwd(x, res, gamma, beta, eps, act)
+    np.testing.assert_allclose(y, want, rtol=1e-12, atol=1e-12)
+    y_nores, _, _ = orc.bn_act_fwd(x, None, gamma, beta, eps, "none")
+    np.testing.assert_allclose(y_nores, z - res, rtol=1e-12, atol=1e-12)
+
+
+def test_bf16_fan_in_sums_cotangents_in_reverse_consumer_order_rounding_after_each_addition():
+    """A tensor with two consumers (a convolution and, later, the residual input of a BatchNorm): in a bf16
+    workload its cotangent is round(round(residual cotangent) + convolution's input cotangent), i.e. the later
+    consumer contributes first and the sum is rounded to bf16 after every addition.  Rebuilt here from the
+    oracle's per-op pullbacks and an independent rounding routine (the workload generator's, NumPy integer
+    arithmetic); the other order gives different bits."""
+    ops = [dict(kind="conv", **{"in": 0}, k=8, r=3, s=3, stride=1, pad=1, groups=1, bias=False, act="none"),
+           dict(kind="bn", **{"in": 1}, res=-1, act="relu", eps=1e-5),                    # tensor 2: two consumers
+           dict(kind="conv", **{"in": 2}, k=8, r=3, s=3, stride=1, pad=1, groups=1, bias=False, act="none"),
+           dict(kind="bn", **{"in": 3}, res=2, act="relu", eps=1e-5),
+           dict(kind="head", **{"in": 4}, classes=5)]
+    net = dict(name="fanin", dtype="bf16", input=(4, 6, 6, 8), classes=5, lr=0.1, momentum=0.9, seed=77, init="he",
+               x_dist="normal", ops=ops)
+    wl = nets.make_workload(net, perturb=True)
+    out = orc.train_step(net, wl["x"], wl["labels"], wl["params"], keep_cotangents=True)
+    t, cot = out["tensors"], out["cotangents"]
+    r32 = lambda a: nets.to_bf16_grid(np.asarray(a, np.float32)).astype(np.float64)   # noqa: E731
+    # pullback of the second BatchNorm (op 3) from the cotangent the oracle fed it
+    _, mean, invstd = orc.bn_act_fwd(t[3], t[2], wl["params"][3][0], wl["params"][3][1], 1e-5, "relu")
+    dx3, dres, _, _ = orc.bn_act_vjp(t[3], t[4], wl["params"][3][0], mean, invstd, cot[4], "relu", True)
+    np.testing.assert_array_equal(cot[3], r32(dx3))
+    w2 = r32(wl["params"][2][0])
+    dconv, _, _ = orc.conv2d_vjp(t[2], w2, cot[3], 1, 1)
+    in_order = r32(r32(dres) + dconv)          # the later consumer (the residual input) first
+    np.testing.assert_array_equal(cot[2], in_order)
+    assert not np.array_equal(in_order, r32(r32(dconv) + dres))

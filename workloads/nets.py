@@ -197,6 +197,10 @@ def make_workload(net, perturb=False):
     perturb=True additionally draws non-trivial BatchNorm gamma/beta and biases (after
     everything else, so the default stream is unchanged); used by parity tests so that
     a mistake in how those enter the arithmetic cannot hide behind gamma=1, beta=0.
+    perturb="shifted": inputs and activations far from zero mean, so that every convolution output
+    has a per-channel mean of several standard deviations (x ~ N(12,1) resp. U[0,1)+12; BatchNorms
+    with an activation get gamma ~ 0.25, beta ~ 4, i.e. outputs of mean 4 and spread 0.25): the
+    workload on which one-pass variance formulas lose digits.
     """
     rng = np.random.default_rng(net["seed"])
     n, h, w, c = net["input"]
@@ -239,10 +243,18 @@ def make_workload(net, perturb=False):
         else:
             params.append([])
     if perturb:
+        shifted = perturb == "shifted"
+        if shifted:
+            x = x + np.float32(12.0)
+            if net["dtype"] == "bf16":
+                x = to_bf16_grid(x)
         for op, p in zip(net["ops"], params):
             if op["kind"] == "bn":
                 p[0] = (1.0 + 0.3 * rng.standard_normal(p[0].shape)).astype(np.float32)
                 p[1] = (0.2 * rng.standard_normal(p[1].shape)).astype(np.float32)
+                if shifted and op["act"] != "none":
+                    p[0] = (0.25 * p[0]).astype(np.float32)
+                    p[1] = (p[1] + 4.0).astype(np.float32)
             elif op["kind"] in ("conv", "head") and len(p) == 2:
                 p[1] = (0.1 * rng.standard_normal(p[1].shape)).astype(np.float32)
     return {"x": x, "labels": labels, "params": params}
