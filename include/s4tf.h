@@ -28,9 +28,12 @@
  *    library keeps no pointer after the work it enqueued has completed.
  *  - Execution: all work is enqueued on `stream` (a hipStream_t passed as void*, NULL is
  *    the default stream).  No entry point synchronises the host.
- *  - Errors: every entry point returns an s4tf_status.  Arguments are validated before
- *    anything is launched, so a non-OK return means nothing was written.  A message is
- *    available from s4tf_last_error() (thread-local).  No exception crosses the ABI.
+ *  - Errors: every entry point returns an s4tf_status.  Arguments, shapes and everything a
+ *    network's plan decides are validated before anything is launched: after any status but
+ *    S4TF_ERR_DEVICE nothing was written.  S4TF_ERR_DEVICE (a launch, event or stream call
+ *    failed half way) leaves the outputs, and for a train step the workspace, gradients and
+ *    parameters, undefined.  A message is available from s4tf_last_error() (thread-local).
+ *    No exception crosses the ABI.
  *  - Alignment: device pointers must be 16-byte aligned.  Outputs must not alias inputs
  *    except where documented (param/velocity of s4tf_sgd_momentum, the in-place update
  *    of s4tf_train_step).
@@ -256,12 +259,36 @@ int s4tf_net_tensor_layout(const s4tf_net_desc* net, int64_t* act_off, int64_t* 
  * step orders it after the work already queued on batch->stream and makes batch->stream
  * wait for it before the update, also when the step fails half way, so in stream order on
  * batch->stream the step is complete (and its workspace reusable) when its last kernel is.
- * Steps on the same device share that second stream.  A net whose convolutions add up to
+ * Steps on the same device share that second stream (and take turns enqueuing).  A net whose convolutions add up to
  * less than 0.5 GFLOP per forward pass runs on batch->stream alone.  The step allocates no
  * memory, issues no memset and no synchronisation, so once the second stream exists (after
  * the first call on the device) a caller may capture a step in a HIP graph of its own:
  * the second stream is forked from batch->stream and joined back into it inside the call. */
 int s4tf_train_step(const s4tf_net_desc* net, s4tf_params* params, const s4tf_batch* batch, float lr);
+
+/* ---- planned networks ---------------------------------------------------------------------
+ * A network is planned once: shapes, the parameter and workspace layout, which ops run beside
+ * each other on the second stream, which cotangent accumulates into which, and the flat list
+ * of launches and stream operations (the schedule) that a step then replays with the caller's
+ * pointers.  The descriptor form of the calls above keeps its plans in a cache inside the
+ * library, keyed by a hash of the descriptor (scalar fields and op records; the 32 most
+ * recently planned nets are kept): the role the cache of compiled traces, keyed by a hash of
+ * the trace, plays in the paper's Section 3.4, so that only the first step of a net pays for
+ * planning.  s4tf_net_create gives a caller a plan of its own: *out (host pointer) is valid
+ * until s4tf_net_destroy, independent of the cache and of the descriptor's memory, and may
+ * be used by several threads at once (a step does not modify it).  s4tf_net_train_step is
+ * s4tf_train_step on such a plan: same arguments, same kernels in the same order, bit-identical
+ * results.  Every reason a net cannot be run (S4TF_ERR_SHAPE / _UNSUPPORTED / _DTYPE) is
+ * reported by s4tf_net_create, respectively by the first descriptor call, before any launch.
+ * Two-stream steps on one device are serialised by a lock held while a step is enqueued, so
+ * several host threads may step (different workspaces) on one device.
+ * s4tf_net_schedule_length: commands in the schedule; s4tf_net_hash: the cache key. */
+typedef struct s4tf_net s4tf_net;
+int s4tf_net_create(const s4tf_net_desc* desc, s4tf_net** out);
+void s4tf_net_destroy(s4tf_net* net); /* NULL is allowed */
+int s4tf_net_train_step(const s4tf_net* net, s4tf_params* params, const s4tf_batch* batch, float lr);
+size_t s4tf_net_schedule_length(const s4tf_net* net);
+uint64_t s4tf_net_hash(const s4tf_net* net);
 
 /* ---- measurement hook -------------------------------------------------------------------
  * While enabled, every kernel launch made by this thread's calls is bracketed by a pair of

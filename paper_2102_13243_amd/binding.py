@@ -102,6 +102,16 @@ def lib():
     L.s4tf_train_step_workspace_bytes.restype = c_sz
     L.s4tf_train_step_workspace_bytes.argtypes = [P(NetDesc)]
     L.s4tf_train_step.argtypes = [P(NetDesc), P(Params), P(Batch), c_f32]
+    L.s4tf_net_create.argtypes = [P(NetDesc), P(c_vp)]
+    L.s4tf_net_create.restype = ctypes.c_int
+    L.s4tf_net_destroy.argtypes = [c_vp]
+    L.s4tf_net_destroy.restype = None
+    L.s4tf_net_train_step.argtypes = [c_vp, P(Params), P(Batch), c_f32]
+    L.s4tf_net_train_step.restype = ctypes.c_int
+    L.s4tf_net_schedule_length.argtypes = [c_vp]
+    L.s4tf_net_schedule_length.restype = c_sz
+    L.s4tf_net_hash.argtypes = [c_vp]
+    L.s4tf_net_hash.restype = ctypes.c_uint64
     L.s4tf_profile_enable.argtypes = [ctypes.c_int]
     L.s4tf_profile_collect.argtypes = [P(ctypes.c_double), P(ctypes.c_int64)]
     L.s4tf_profile_bracket_overhead.argtypes = [ctypes.c_void_p, ctypes.c_int, P(ctypes.c_double)]
@@ -246,6 +256,29 @@ def s4tf_train_step(net_desc, params, batch, lr):
     _check(lib().s4tf_train_step(ctypes.byref(net_desc), ctypes.byref(params), ctypes.byref(batch), lr))
 
 
+def s4tf_net_create(net_desc):
+    """Returns the handle (an integer address) of a plan of the net."""
+    out = c_vp()
+    _check(lib().s4tf_net_create(ctypes.byref(net_desc), ctypes.byref(out)))
+    return out.value
+
+
+def s4tf_net_destroy(handle):
+    lib().s4tf_net_destroy(handle)
+
+
+def s4tf_net_train_step(handle, params, batch, lr):
+    _check(lib().s4tf_net_train_step(handle, ctypes.byref(params), ctypes.byref(batch), lr))
+
+
+def s4tf_net_schedule_length(handle):
+    return int(lib().s4tf_net_schedule_length(handle))
+
+
+def s4tf_net_hash(handle):
+    return int(lib().s4tf_net_hash(handle))
+
+
 def s4tf_profile_enable(on):
     _check(lib().s4tf_profile_enable(1 if on else 0))
 
@@ -350,11 +383,15 @@ class TrainState:
             xt = to_bf16_device(xt)
         return xt, torch.from_numpy(np.ascontiguousarray(labels, np.int32)).to(self.device)
 
-    def step(self, x_dev, labels_dev, lr=None, stream=None):
+    def step(self, x_dev, labels_dev, lr=None, stream=None, handle=None):
+        """One training step; with `handle` (from s4tf_net_create) through the planned-network entry point."""
         lr = self.net["lr"] if lr is None else lr
         p = Params(_p(self.master), _p(self.velocity), _p(self.grad), _p(self.lowp), self.count)
         b = Batch(_p(x_dev), _p(labels_dev), _p(self.loss), _p(self.workspace), self.ws_bytes, _stream(stream))
-        s4tf_train_step(self.desc, p, b, lr)
+        if handle is not None:
+            s4tf_net_train_step(handle, p, b, lr)
+        else:
+            s4tf_train_step(self.desc, p, b, lr)
 
     def _view(self, off, shape, dtype):
         torch = self.torch

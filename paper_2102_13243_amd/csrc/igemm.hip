@@ -898,6 +898,10 @@ bool igemm_dgrad_adds_other(const ConvGeom& g, int dtype, const void* dy, const 
   return igemm_dma_ok(PASS_DGRAD, g, a);
 }
 
+bool igemm_dgrad_can_add_other(const ConvGeom& g, int dtype) {
+  return dtype == S4TF_BF16 && g.stride == 1 && g.C % 8 == 0 && igemm_dma_geom_ok(PASS_DGRAD, g);
+}
+
 int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,
                 hipStream_t st, const void* acc_src, const unsigned char* acc_bits) {
   Args a = {};

@@ -98,6 +98,7 @@ int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, voi
                 hipStream_t st, const void* acc_src = nullptr, const unsigned char* acc_bits = nullptr);
 bool igemm_dgrad_adds_other(const ConvGeom& g, int dtype, const void* dy, const void* w, const void* dx,
                             const void* acc_src);
+bool igemm_dgrad_can_add_other(const ConvGeom& g, int dtype);  // the same question for 16-byte aligned operands
 size_t igemm_wgrad_workspace(const ConvGeom& g, int dtype);
 int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, float* dw, void* ws,
                 size_t ws_bytes, hipStream_t st);
@@ -162,6 +163,24 @@ int check_conv_desc(const s4tf_conv_desc* d);
 int check_bn_desc(const s4tf_bn_desc* d);
 int check_pool_desc(const s4tf_pool_desc* d);
 int check_head_desc(const s4tf_head_desc* d);
+
+// argument checks shared by the entry points (api.hip) and the whole-step scheduler (step.hip)
+int need(const void* p, const char* name);   // not NULL and 16-byte aligned
+int opt(const void* p, const char* name);    // NULL or 16-byte aligned
+int check_ws(const void* ws, size_t have, size_t want);
+#define CHECK(expr)                 \
+  do {                              \
+    int rc_ = (expr);               \
+    if (rc_ != S4TF_OK) return rc_; \
+  } while (0)
+
+// a convolution's three passes, dense or depthwise by the descriptor's groups (api.hip)
+int conv_fwd_impl(const s4tf_conv_desc& d, const void* x, const void* w, const float* bias, void* y, hipStream_t st,
+                  float* stats_part = nullptr, int* stats_rows = nullptr);
+int conv_dgrad_impl(const s4tf_conv_desc& d, const void* w, const void* dz, void* dx, hipStream_t st,
+                    const void* acc_src = nullptr, const unsigned char* acc_bits = nullptr);
+int conv_param_grads_impl(const s4tf_conv_desc& d, const void* x, const void* dz, float* dw, float* dbias,
+                          void* wg_ws, size_t wg_bytes, hipStream_t st);
 
 inline int launch_status(const char* what) {
   hipError_t e = hipGetLastError();

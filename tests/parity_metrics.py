@@ -47,14 +47,18 @@ def bf16_ulp(b):
     return np.ldexp(1.0, e - 8)
 
 
-def elementwise_f32(a, b, rtol=F32_RTOL, atol=None, atol_rms=F32_ATOL_RMS):
-    """Returns (ok, worst) where worst = max |a-b| / (atol + rtol |b|) (<= 1 passes)."""
+def elementwise_f32(a, b, rtol=F32_RTOL, atol=None, atol_rms=F32_ATOL_RMS, atol_extra=None):
+    """Returns (ok, worst) where worst = max |a-b| / (atol + rtol |b|) (<= 1 passes).  atol defaults to
+    atol_rms * rms(b); atol_extra (scalar or array that broadcasts against b) is added to it: the
+    accumulation-error allowance of a contraction whose terms are large against its result."""
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
     if b.size == 0:
         return True, 0.0
     if atol is None:
         atol = atol_rms * _rms(b)
-    if atol == 0.0 and not np.any(b):
+    if atol_extra is not None:
+        atol = atol + np.asarray(atol_extra, np.float64)
+    if np.ndim(atol) == 0 and atol == 0.0 and not np.any(b):
         return bool(not np.any(a)), float(np.abs(a).max())
     d = np.abs(a - b)
     np.divide(d, atol + rtol * np.abs(b), out=d)
@@ -62,8 +66,11 @@ def elementwise_f32(a, b, rtol=F32_RTOL, atol=None, atol_rms=F32_ATOL_RMS):
     return bool(np.isfinite(worst) and worst <= 1.0), worst
 
 
-def elementwise_bf16(a, b_rounded, atol=None, atol_rms=BF16_ATOL_RMS):
+def elementwise_bf16(a, b_rounded, atol=None, atol_rms=BF16_ATOL_RMS, operand_scale=None):
     """a: GPU values (on the bf16 grid), b_rounded: the oracle's values rounded to the bf16 grid.
+    operand_scale (optional, same shape): for a value that is a rounded SUM of bf16 operands, the largest
+    operand magnitude; the grid spacing is then taken at max(|b|, operand_scale), because one rounding
+    flip of an operand moves the sum by the operand's spacing however far the operands cancel.
     Returns (ok, frac_within_1, max_ulps)."""
     a, b = np.asarray(a, np.float64), np.asarray(b_rounded, np.float64)
     if b.size == 0:
@@ -73,14 +80,14 @@ def elementwise_bf16(a, b_rounded, atol=None, atol_rms=BF16_ATOL_RMS):
     d = np.abs(a - b)
     d -= atol
     np.maximum(d, 0.0, out=d)
-    d /= bf16_ulp(b)
+    d /= bf16_ulp(b if operand_scale is None else np.maximum(np.abs(b), operand_scale))
     mx = float(d.max())
     frac = float(np.count_nonzero(d <= 1.0)) / d.size
     ok = np.isfinite(mx) and mx <= BF16_MAX_ULPS and frac >= BF16_FRAC_WITHIN_1
     return bool(ok), frac, mx
 
 
-def check_tensor(what, got, ref, bf16, l2_tol, atol=None):
+def check_tensor(what, got, ref, bf16, l2_tol, atol=None, atol_extra=None, operand_scale=None):
     """Norm-wise and element-wise comparison of one tensor.  `ref` is the oracle's value, already rounded
     to the bf16 grid when bf16 is set.  Returns a record (what, rel_l2, l2_tol, rel_inf, detail) and
     raises AssertionError on a violation."""
@@ -88,10 +95,10 @@ def check_tensor(what, got, ref, bf16, l2_tol, atol=None):
     assert np.isfinite(e2), "%s: not finite" % what
     assert e2 <= l2_tol, "%s: rel-L2 %.3g > %.3g (rel-inf %.3g)" % (what, e2, l2_tol, ei)
     if bf16:
-        ok, frac, mx = elementwise_bf16(got, ref, atol)
+        ok, frac, mx = elementwise_bf16(got, ref, atol, operand_scale=operand_scale)
         detail = "within 1 ulp %.5f, max %.2f ulp" % (frac, mx)
     else:
-        ok, worst = elementwise_f32(got, ref, atol=atol)
+        ok, worst = elementwise_f32(got, ref, atol=atol, atol_extra=atol_extra)
         detail = "worst element %.3g of its bound" % worst
     assert ok, "%s: element-wise check failed (%s; rel-L2 %.3g, rel-inf %.3g)" % (what, detail, e2, ei)
     return (what, e2, l2_tol, ei, detail)

@@ -112,3 +112,63 @@ def test_bad_networks_are_rejected():
     p = B.Params(16, 16, 16, None, 3)
     b = B.Batch(16, 16, 16, 16, 1 << 30, None)
     assert B.lib().s4tf_train_step(ctypes.byref(desc), ctypes.byref(p), ctypes.byref(b), 0.1) == -2
+
+
+def test_planned_networks_and_the_plan_cache():
+    """s4tf_net_create plans a net once (Section 3.4's cache of compiled traces, keyed by a hash, is the
+    model): equal descriptors hash alike, different ones differently; the schedule is a flat list whose
+    length grows with the net; whatever makes a net impossible is reported at creation, before any launch;
+    argument errors of a step on a plan are those of the descriptor form."""
+    handles = {}
+    for name in ("tiny", "lenet5", "resnet56", "resnet50", "mobilenetv2"):
+        net = nets.CONFIGS[name]()
+        desc, keep = B.make_net_desc(net)
+        h = B.s4tf_net_create(desc)
+        handles[name] = h
+        assert h and B.s4tf_net_schedule_length(h) >= len([o for o in net["ops"] if o["kind"] != "flatten"])
+        desc2, keep2 = B.make_net_desc(nets.CONFIGS[name]())     # an equal descriptor in other memory
+        h2 = B.s4tf_net_create(desc2)
+        assert h2 != h and B.s4tf_net_hash(h2) == B.s4tf_net_hash(h)
+        assert B.s4tf_net_schedule_length(h2) == B.s4tf_net_schedule_length(h)
+        B.s4tf_net_destroy(h2)
+    assert len({B.s4tf_net_hash(h) for h in handles.values()}) == len(handles)
+    other, keep = B.make_net_desc(nets.resnet56(batch=64))
+    h3 = B.s4tf_net_create(other)
+    assert B.s4tf_net_hash(h3) != B.s4tf_net_hash(handles["resnet56"])
+    B.s4tf_net_destroy(h3)
+    # the two small nets run on the caller's stream alone (no stream operations in their schedules):
+    # conv, bn, head, bn pullback, filter gradient, optimizer = 6 commands
+    assert B.s4tf_net_schedule_length(handles["tiny"]) == 6
+    # a step on a plan validates its arguments like the descriptor form
+    p = B.Params(16, 16, 16, None, 3)
+    b = B.Batch(16, 16, 16, 16, 1 << 30, None)
+    assert B.lib().s4tf_net_train_step(handles["tiny"], ctypes.byref(p), ctypes.byref(b), 0.1) == -2
+    assert "params.count" in B.last_error()
+    assert B.lib().s4tf_net_train_step(None, ctypes.byref(p), ctypes.byref(b), 0.1) == -1
+    for h in handles.values():
+        B.s4tf_net_destroy(h)
+    B.s4tf_net_destroy(None)
+    # impossible nets fail at creation
+    net = nets.tiny_block()
+    desc, keep = B.make_net_desc(dict(net, ops=net["ops"][::-1]))
+    with pytest.raises(B.S4tfError):
+        B.s4tf_net_create(desc)
+    out = ctypes.c_void_p(123)
+    assert B.lib().s4tf_net_create(None, ctypes.byref(out)) == -1 and out.value is None
+
+
+def test_descriptor_calls_reuse_their_plan():
+    """The descriptor form plans on first sight and looks the plan up afterwards: a query on a net of over a
+    hundred ops costs microseconds once planned, and more plans than the cache holds are simply re-made."""
+    import time
+    net = nets.resnet50()
+    desc, keep = B.make_net_desc(net)
+    want = B.s4tf_train_step_workspace_bytes(desc)
+    t0 = time.perf_counter()
+    for _ in range(200):
+        assert B.lib().s4tf_train_step_workspace_bytes(ctypes.byref(desc)) == want
+    assert (time.perf_counter() - t0) / 200 < 2e-4
+    for batch in range(1, 40):   # 39 different nets push the first plan out of the 32-entry cache
+        d, k = B.make_net_desc(nets.lenet5(batch=batch))
+        assert B.s4tf_net_param_count(d) == 61720   # 61 706 parameters, each tensor padded to a multiple of 8
+    assert B.s4tf_train_step_workspace_bytes(desc) == want

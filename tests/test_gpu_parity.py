@@ -125,8 +125,8 @@ def compare_step_strict(net, wl, gpu, ref, **kw):
     step_compare.compare_step_strict(net, wl, gpu, ref, say=say, **kw)
 
 
-def compare_step_full_size(net, gpu, ref, loss_tol, median_tol):
-    step_compare.compare_step_full_size(net, gpu, ref, loss_tol, median_tol, say=say)
+def compare_step_full_size(net, gpu, ref, loss_tol, grad_tol, **kw):
+    return step_compare.compare_step_full_size(net, gpu, ref, loss_tol, grad_tol, say=say, **kw)
 
 
 RNG = np.random.default_rng(11)
@@ -536,14 +536,26 @@ def test_config2_lenet_ten_steps():
 def test_config3_resnet56():
     net = nets.resnet56()
     wl = nets.make_workload(net)
-    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"], keep_cotangents=True)
     compare_step_full_size(net, run_gpu_steps(net, wl, local=True), ref, 1e-4, 1e-3)
+
+
+def test_config3_resnet56_full_size_on_kink_free_shifts():
+    """The same net at full size (batch 128, 32x32) with every BatchNorm beta moved by at most a few 1e-5
+    standard deviations so that none of its 139 million pre-activations lies within 1e-5 std of a kink
+    (asserted on the CPU): then not one activation decision may differ and EVERY gradient and parameter
+    tensor must meet the stated 1e-3, with no allowance."""
+    net = nets.resnet56()
+    wl, report = KF.make_kink_free(net, nets.make_workload(net), 1e-5)
+    assert min(m for _, _, m, _ in report) >= 1e-5
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"], keep_cotangents=True)
+    compare_step_strict(net, wl, run_gpu_steps(net, wl), ref)
 
 
 def test_config5_mobilenetv2():
     net = nets.mobilenetv2()
     wl = nets.make_workload(net)
-    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"], keep_cotangents=True)
     compare_step_full_size(net, run_gpu_steps(net, wl, local=True), ref, 1e-4, 1e-3)
 
 
@@ -555,7 +567,10 @@ def test_config4_resnet50_bf16():
     wl = nets.make_workload(net)
     gpu = run_gpu_steps(net, wl, local=True, full_flops=float("inf"))
     ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
-    compare_step_full_size(net, gpu, ref, 5e-3, 2e-2)
+    # bf16 storage: two correct runs round about one stored value in a thousand differently, after a few layers
+    # every pre-activation differs by ~1e-3 of its spread, and so does about one activation decision in a
+    # thousand: the flip allowance is 5e-3 of the activations instead of the 2e-6 of an fp32 run
+    compare_step_full_size(net, gpu, ref, 5e-3, 2e-2, flip_frac=5e-3)
 
 
 # ---- the same step dispatched op by op (the paper's eager mode, Section 3.3) ---------------------------
@@ -644,3 +659,32 @@ def test_train_step_captured_in_a_graph_replays_like_direct_calls(name, kw):
     for pa, pb in zip(a["params"], b["params"]):
         for x, y in zip(pa, pb):
             np.testing.assert_array_equal(x, y)
+
+
+@pytest.mark.parametrize("name,kw", [("lenet5", dict(batch=16)),
+                                     ("resnet50", dict(batch=4, hw=64, stages=(2, 1, 1, 1), classes=24, dtype="f32")),
+                                     ("resnet50", dict(batch=8, hw=64, stages=(2, 2, 1, 1), classes=40)),
+                                     ("mobilenetv2", dict(batch=4, hw=64, classes=16))],
+                         ids=["lenet5", "resnet50_f32", "resnet50_bf16", "mobilenetv2"])
+def test_planned_network_step_is_bit_identical_to_the_descriptor_form(name, kw):
+    """A plan made by s4tf_net_create and the plan the descriptor form keeps in the library's cache are the
+    same schedule: three steps each way leave the same losses and the same parameters, bit for bit."""
+    net = nets.CONFIGS[name](**kw)
+    wl = nets.make_workload(net, perturb=True)
+    handle = B.s4tf_net_create(B.make_net_desc(net)[0])
+    try:
+        a, b = B.TrainState(net, wl["params"], DEV), B.TrainState(net, wl["params"], DEV)
+        xa, la = a.upload_batch(wl["x"], wl["labels"])
+        xb, lb = b.upload_batch(wl["x"], wl["labels"])
+        for _ in range(3):
+            a.step(xa, la)
+            b.step(xb, lb, handle=handle)
+            torch.cuda.synchronize()
+            assert float(a.loss[0].item()) == float(b.loss[0].item())
+        ra, rb = a.results(), b.results()
+        for key in ("grads", "params", "velocity"):
+            for pa, pb in zip(ra[key], rb[key]):
+                for x, y in zip(pa, pb):
+                    np.testing.assert_array_equal(x, y)
+    finally:
+        B.s4tf_net_destroy(handle)
