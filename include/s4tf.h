@@ -140,6 +140,19 @@ size_t s4tf_bn_relu_workspace_bytes(const s4tf_bn_desc* d);
 int s4tf_bn_relu_fwd(const s4tf_bn_desc* d, const void* x, const void* residual, const float* gamma,
                      const float* beta, void* y, float* save_mean, float* save_invstd,
                      void* workspace, size_t workspace_bytes, void* stream);
+/* s4tf_bn_relu_fwd for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments without the
+ * workspace, same kernels, same results bit for bit.  The statistics kernels' partial sums live in a
+ * device array that is part of the library itself (1 MiB per GPU, held until the process ends); the call
+ * allocates nothing, frees nothing and clears nothing.  A shape whose partial sums need more than that
+ * (roughly: more than 131 072 channel x pixel-chunk pairs, e.g. 512 channels over 200 000 pixels) is
+ * refused with S4TF_ERR_WORKSPACE before anything is launched; s4tf_bn_relu_fwd_static_limit returns the
+ * capacity in bytes and, through `needed` (host, nullable), what the descriptor's shape needs.  All calls
+ * on one GPU share the array: calls that overlap in time on one GPU (different streams or threads) race;
+ * calls in one stream are ordered and need no care, nothing carries over from one call to the next. */
+int s4tf_bn_relu_fwd_static(const s4tf_bn_desc* d, const void* x, const void* residual, const float* gamma,
+                            const float* beta, void* y, float* save_mean, float* save_invstd, void* stream);
+size_t s4tf_bn_relu_fwd_static_limit(const s4tf_bn_desc* d, size_t* needed);
 int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const float* gamma,
                      const float* beta, const float* save_mean, const float* save_invstd, const void* dy, void* dx,
                      void* dresidual, float* dgamma, float* dbeta, void* workspace,

@@ -88,6 +88,10 @@ def lib():
     L.s4tf_conv2d_vjp.argtypes = [P(ConvDesc), c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     L.s4tf_bn_relu_fwd.argtypes = [P(BnDesc), c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     L.s4tf_bn_relu_vjp.argtypes = [P(BnDesc)] + [c_vp] * 12 + [c_sz, c_vp]
+    L.s4tf_bn_relu_fwd_static.argtypes = [P(BnDesc)] + [c_vp] * 8
+    L.s4tf_bn_relu_fwd_static.restype = ctypes.c_int
+    L.s4tf_bn_relu_fwd_static_limit.argtypes = [P(BnDesc), P(c_sz)]
+    L.s4tf_bn_relu_fwd_static_limit.restype = c_sz
     L.s4tf_pool2d_fwd.argtypes = [P(PoolDesc), c_vp, c_vp, c_vp]
     L.s4tf_pool2d_vjp.argtypes = [P(PoolDesc), c_vp, c_vp, c_vp, c_vp]
     L.s4tf_pool_dense_xent_fwd_vjp.argtypes = [P(HeadDesc)] + [c_vp] * 10 + [c_sz, c_vp]
@@ -182,6 +186,18 @@ def s4tf_bn_relu_workspace_bytes(d):
 def s4tf_bn_relu_fwd(d, x, residual, gamma, beta, y, save_mean, save_invstd, workspace, stream=None):
     _check(lib().s4tf_bn_relu_fwd(ctypes.byref(d), _p(x), _p(residual), _p(gamma), _p(beta), _p(y), _p(save_mean),
                                   _p(save_invstd), _p(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def s4tf_bn_relu_fwd_static(d, x, residual, gamma, beta, y, save_mean, save_invstd, stream=None):
+    _check(lib().s4tf_bn_relu_fwd_static(ctypes.byref(d), _p(x), _p(residual), _p(gamma), _p(beta), _p(y), _p(save_mean),
+                                         _p(save_invstd), _stream(stream)))
+
+
+def s4tf_bn_relu_fwd_static_limit(d):
+    """(capacity of the static scratch in bytes, bytes the descriptor's shape needs)"""
+    needed = c_sz(0)
+    cap = lib().s4tf_bn_relu_fwd_static_limit(ctypes.byref(d), ctypes.byref(needed))
+    return int(cap), int(needed.value)
 
 
 def s4tf_bn_relu_vjp(d, x, y, gamma, beta, save_mean, save_invstd, dy, dx, dresidual, dgamma, dbeta, workspace,

@@ -231,6 +231,20 @@ int s4tf_bn_relu_fwd(const s4tf_bn_desc* d, const void* x, const void* residual,
   CHECK(check_ws(workspace, workspace_bytes, bn_workspace((size_t)d->n * d->h * d->w, d->c)));
   return bn_fwd(*d, x, residual, gamma, beta, y, save_mean, save_invstd, workspace, (hipStream_t)stream);
 }
+int s4tf_bn_relu_fwd_static(const s4tf_bn_desc* d, const void* x, const void* residual, const float* gamma,
+                            const float* beta, void* y, float* save_mean, float* save_invstd, void* stream) {
+  clear_error();
+  CHECK(check_bn_desc(d));
+  CHECK(need(x, "x")); CHECK(need(gamma, "gamma")); CHECK(need(beta, "beta")); CHECK(need(y, "y"));
+  CHECK(need(save_mean, "save_mean")); CHECK(need(save_invstd, "save_invstd")); CHECK(opt(residual, "residual"));
+  return bn_fwd_static(*d, x, residual, gamma, beta, y, save_mean, save_invstd, (hipStream_t)stream);
+}
+size_t s4tf_bn_relu_fwd_static_limit(const s4tf_bn_desc* d, size_t* needed) {
+  clear_error();
+  if (needed) *needed = 0;
+  if (d && check_bn_desc(d) == S4TF_OK && needed) *needed = bn_fwd_scratch_bytes(*d);
+  return bn_static_scratch_capacity();
+}
 int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const float* gamma, const float* beta,
                      const float* save_mean, const float* save_invstd, const void* dy, void* dx, void* dresidual,
                      float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {

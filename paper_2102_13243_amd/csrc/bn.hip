@@ -11,11 +11,37 @@
 //             apply:  y = act(gamma*(x-mean)*invstd + beta (+ residual))
 //   pullback  reduce: dbeta = sum dz, dgamma = sum dz*xhat with dz = dy*act'(y)   (in double)
 //             apply:  dx = gamma*invstd*(dz - dbeta/m - xhat*dgamma/m),  dresidual (+)= dz
+#include <mutex>
+
 #include "s4tf_internal.h"
 #include "pack.h"
 
 namespace s4tf {
 namespace {
+
+// Scratch of the forward entry point that allocates nothing (s4tf_bn_relu_fwd_static): the statistics
+// kernels' per-chunk partial sums, which the plain entry point keeps in the caller's workspace.  Device
+// memory that comes with the library's code object, one copy per GPU, held until the process ends.  The
+// name below is a host-side stand-in, not a device address: host code only ever uses the per-device
+// address that static_scratch() looks up once.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[64] = {};
+
+int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return fail(S4TF_ERR_DEVICE, "cannot tell the current device");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {  // once per device, with that device current: each GPU has its own copy at its own address
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(S4TF_ERR_DEVICE, "cannot locate the static scratch on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return S4TF_OK;
+}
 
 constexpr int MAX_CHUNKS = 2048;
 constexpr int UNROLL = 4;
@@ -553,6 +579,26 @@ int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* g
   BN_LAUNCH(bn_apply_kernel, pa, 0, (const T*)x, (const T*)res, gamma, beta, mean, invstd, (T*)y, maskbits, M, C, pa.cvb,
             pa.per, d.act);
   return launch_status("bn_apply");
+}
+
+size_t bn_fwd_scratch_bytes(const s4tf_bn_desc& d) {
+  const Plan pr = make_plan((size_t)d.n * d.h * d.w, d.c, d.dtype, 1024, 16);  // the reduction plan of bn_fwd
+  return (size_t)pr.chunks * 2 * d.c * sizeof(float);
+}
+size_t bn_static_scratch_capacity() { return STATIC_SCRATCH_BYTES; }
+
+int bn_fwd_static(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
+                  void* y, float* mean, float* invstd, hipStream_t st) {
+  const size_t want = bn_fwd_scratch_bytes(d);
+  if (want > STATIC_SCRATCH_BYTES)
+    return fail(S4TF_ERR_WORKSPACE, "bn: this shape needs %zu bytes of partial sums, the static scratch holds %zu", want,
+                (size_t)STATIC_SCRATCH_BYTES);
+  void* ptr = nullptr;
+  int rc = static_scratch(&ptr);
+  if (rc != S4TF_OK) return rc;
+  // every partial sum the finalize kernel reads is written by the statistics kernel of the same call: nothing
+  // has to start at zero, and what an earlier call left behind is never read
+  return bn_fwd(d, x, res, gamma, beta, y, mean, invstd, ptr, st);
 }
 
 int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* beta, const float* mean,

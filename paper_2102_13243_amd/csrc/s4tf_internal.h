@@ -134,6 +134,12 @@ size_t bn_mask_bytes(size_t M, int C, int dtype);
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
            void* y, float* mean, float* invstd, void* ws, hipStream_t st, const float* stats_part = nullptr,
            int stats_rows = 0, unsigned char* maskbits = nullptr);
+// bn_fwd with its partial sums in a static device array instead of a workspace: allocates nothing; shapes
+// whose partial sums (bn_fwd_scratch_bytes) exceed bn_static_scratch_capacity() are refused
+size_t bn_fwd_scratch_bytes(const s4tf_bn_desc& d);
+size_t bn_static_scratch_capacity();
+int bn_fwd_static(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
+                  void* y, float* mean, float* invstd, hipStream_t st);
 int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gamma, const float* beta, const float* mean,
            const float* invstd, const void* dy, void* dx, void* dres, float* dgamma, float* dbeta,
            void* ws, hipStream_t st, const unsigned char* maskbits = nullptr);
