@@ -158,6 +158,8 @@ def main():
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the other four configurations (other_workloads in the JSON line)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="launch only a plain copy kernel of known size (reads and writes 256 MiB, three times): "
                          "the reference reading for the FETCH_SIZE / WRITE_SIZE counters")
@@ -191,25 +193,102 @@ def main():
     if args.ablation:
         print(json.dumps(ablation(net, wl, args.steps, args.warmup)))
         return
+    m = measure(net, wl, args.steps, args.warmup, args.workload)
+    batch, dtype = net["input"][0], net["dtype"]
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle as it stands on the host's cores, same net, image size and batch as the GPU's step: one
+        # warm-up step, one timed step
+        cpu = oracle_rate(net, wl, warm=True)
+        cpu["sample"] = "one oracle step of the same workload at its full batch %d after one warm-up step (%.1f s)" % (batch, cpu.pop("seconds"))
+
+    others = None
+    if args.workload == "resnet50" and not args.no_other_workloads:
+        # the other four configurations, short runs: ms per step, images/s, the dominant kernel class against its
+        # roofline, and the oracle on the host (all cores; one thread as well for the three small ones)
+        others = {}
+        for name in ("tiny", "lenet5", "resnet56", "mobilenetv2"):
+            onet = nets.CONFIGS[name]()
+            owl = nets.make_workload(onet)
+            om = measure(onet, owl, 10, 3, name)
+            rec = {"ms_per_step": om["ms_per_step"], "images_per_s": om["images_per_s"], "dtype": onet["dtype"],
+                   "batch": onet["input"][0], "host_enqueue_ms_per_step": om["host_enqueue_ms_per_step"],
+                   "roofline": om["roofline"], "mfma_util_convs": om["mfma_util_convs"]}
+            if not args.no_cpu_baseline:
+                c = oracle_rate(onet, owl, warm=True)
+                rec["cpu_oracle_images_per_s"] = c["value"]
+                rec["cpu_cores"] = c["cores"]
+                if name != "mobilenetv2":
+                    rec["cpu_oracle_images_per_s_1_thread"] = oracle_rate(onet, owl, warm=False, threads=1)["value"]
+            others[name] = rec
+
+    out = {
+        "metric": METRIC, "value": m["images_per_s"], "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": m["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": "%s-shaped net, batch %d of %dx%dx%d, %s storage, fp32 accumulate, SGD-momentum; one "
+                               "s4tf_train_step per step" % (net["name"], batch, net["input"][3], net["input"][1],
+                                                              net["input"][2], dtype),
+                   "params": nets.param_count(wl["params"]), "loss_after": m["loss_after"]},
+        "roofline": m["roofline"], "cpu_baseline": cpu,
+        "mfma_util_convs": m["mfma_util_convs"],
+        "host_enqueue_ms_per_step": m["host_enqueue_ms_per_step"],
+        "event_pair_overhead_us": m["event_pair_overhead_us"],
+        "kernel_classes": m["kernel_classes"],
+        "other_workloads": others,
+    }
+    print(json.dumps(out))
+
+
+def oracle_rate(net, wl, warm, threads=None):
+    """images/s of one oracle step on the host (optionally after a warm-up step, optionally on `threads` threads)."""
+    import os
+    import subprocess
+    from oracle import oracle as orc
+    batch = net["input"][0]
+    if threads is not None:
+        # the OpenMP thread count is fixed when the oracle's library starts: a child process with its own setting
+        code = ("import sys, time, json; sys.path.insert(0, %r); from oracle import oracle as orc; from workloads import nets;"
+                "net = nets.CONFIGS[%r](); wl = nets.make_workload(net); t0 = time.perf_counter();"
+                "orc.train_step(net, wl['x'], wl['labels'], wl['params']); print(json.dumps([time.perf_counter() - t0, orc.num_threads()]))"
+                % (os.path.dirname(os.path.abspath(__file__)), net["name"]))
+        env = dict(os.environ, OMP_NUM_THREADS=str(threads))
+        ct, cores = json.loads(subprocess.check_output([sys.executable, "-c", code], env=env).decode().strip().splitlines()[-1])
+    else:
+        if warm:
+            orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+        t0 = time.perf_counter()
+        orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+        ct, cores = time.perf_counter() - t0, orc.num_threads()
+    return {"value": round(batch / ct, 4), "unit": "images/s", "cores": cores, "kind": "oracle", "seconds": ct}
+
+
+def measure(net, wl, steps, warmup, workload):
+    """Times `steps` training steps of the net on cuda:0 (after `warmup`), then the per-class kernel durations."""
+    import torch
+    from paper_2102_13243_amd import binding as B
+    from workloads import nets
     st = B.TrainState(net, wl["params"], "cuda:0")
     xd, ld = st.upload_batch(wl["x"], wl["labels"])
     batch = net["input"][0]
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         st.step(xd, ld)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         st.step(xd, ld)
+    t_enq = time.perf_counter() - t0   # the host is done enqueuing; the device is still running
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    ms_per_step = dt / steps * 1e3
     loss = float(st.loss[0].item())
 
     # Per-kernel-class durations: the same steps again with every launch bracketed by HIP events on
     # the launch stream (kept out of the timed region above so the events do not perturb it).
     B.s4tf_profile_enable(True)
-    prof_steps = max(1, min(args.steps, 10))
+    prof_steps = max(1, min(steps, 10))
     for _ in range(prof_steps):
         st.step(xd, ld)
     torch.cuda.synchronize()
@@ -223,7 +302,7 @@ def main():
     for name, (ms, cnt) in prof.items():
         ms = max(ms - cnt * bracket_ms, 0.0)
         classes[name] = {"ms_per_step": ms / prof_steps, "launches_per_step": cnt / prof_steps}
-        if flops.get(name):
+        if flops.get(name) and ms > 0:
             classes[name]["tflops"] = flops[name] / (ms / prof_steps * 1e-3) / 1e12
     nbytes = class_bytes(net, shapes, nets.param_count(wl["params"]))
     for name, b in nbytes.items():
@@ -233,45 +312,33 @@ def main():
     dom = max(classes, key=lambda k: classes[k]["ms_per_step"])
     dtype = net["dtype"]
     roofline = None
-    if flops.get(dom) and dom.startswith("conv_"):
+    if flops.get(dom) and dom.startswith("conv_") and "tflops" in classes[dom]:
         ach = classes[dom]["tflops"]
         roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": PEAK[dtype], "unit": "TFLOP/s",
-                    "frac": round(ach / PEAK[dtype], 4), "traffic": measured_traffic(args.workload, dom),
+                    "frac": round(ach / PEAK[dtype], 4), "traffic": measured_traffic(workload, dom),
                     "launches_per_step": classes[dom]["launches_per_step"],
                     "avg_launch_ms": classes[dom]["ms_per_step"] / classes[dom]["launches_per_step"],
                     "flops_per_step": flops[dom]}
+    elif "hbm_tbps" in classes[dom]:
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(classes[dom]["hbm_tbps"] * 1e3, 1), "peak": HBM_PEAK_TBPS * 1e3,
+                    "unit": "GB/s", "frac": round(classes[dom]["hbm_frac"], 4), "traffic": None,
+                    "launches_per_step": classes[dom]["launches_per_step"],
+                    "avg_launch_ms": classes[dom]["ms_per_step"] / classes[dom]["launches_per_step"],
+                    "bytes_per_step": nbytes[dom]}
+    else:   # a class with no roofline model of its own (finalize kernels, pools, the head): time only
+        roofline = {"bound": "latency", "kernel": dom, "achieved": None, "peak": None, "unit": None, "frac": None, "traffic": None,
+                    "launches_per_step": classes[dom]["launches_per_step"],
+                    "avg_launch_ms": classes[dom]["ms_per_step"] / classes[dom]["launches_per_step"]}
     conv_ms = sum(classes[k]["ms_per_step"] for k in ("conv_fwd_igemm", "conv_dgrad_igemm", "conv_wgrad_igemm") if k in classes)
     conv_fl = sum(flops[k] for k in ("conv_fwd_igemm", "conv_dgrad_igemm", "conv_wgrad_igemm"))
     mfma_util = conv_fl / (conv_ms * 1e-3) / 1e12 / PEAK[dtype] if conv_ms else None
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import oracle as orc
-        # a bounded sample of the same workload: same net and image size at a small batch, one step
-        sb = {"resnet50": 32, "mobilenetv2": 32, "resnet56": 64}.get(args.workload, batch)
-        sb = min(sb, batch)
-        snet = nets.CONFIGS[args.workload](batch=sb)
-        swl = nets.make_workload(snet)
-        t0 = time.perf_counter()
-        orc.train_step(snet, swl["x"], swl["labels"], swl["params"])
-        ct = time.perf_counter() - t0
-        cpu = {"value": round(sb / ct, 4), "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
-               "sample": "one oracle step of the same net and image size at batch %d (%.1f s)" % (sb, ct)}
-
-    out = {
-        "metric": METRIC, "value": round(batch / (ms_per_step * 1e-3), 1), "unit": "images/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": "%s-shaped net, batch %d of %dx%dx%d, %s storage, fp32 accumulate, SGD-momentum; one "
-                               "s4tf_train_step per step" % (net["name"], batch, net["input"][3], net["input"][1],
-                                                              net["input"][2], dtype),
-                   "params": nets.param_count(wl["params"]), "loss_after": round(loss, 5)},
-        "roofline": roofline, "cpu_baseline": cpu,
-        "mfma_util_convs": None if mfma_util is None else round(mfma_util, 4),
-        "event_pair_overhead_us": round(bracket_ms * 1e3, 3),
-        "kernel_classes": {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in sorted(classes.items())},
-    }
-    print(json.dumps(out))
+    del st
+    torch.cuda.empty_cache()
+    return {"ms_per_step": round(ms_per_step, 4), "images_per_s": round(batch / (ms_per_step * 1e-3), 1),
+            "host_enqueue_ms_per_step": round(t_enq / steps * 1e3, 4), "loss_after": round(loss, 5), "roofline": roofline,
+            "mfma_util_convs": None if mfma_util is None else round(mfma_util, 4),
+            "event_pair_overhead_us": round(bracket_ms * 1e3, 3),
+            "kernel_classes": {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in sorted(classes.items())}}
 
 
 if __name__ == "__main__":
