@@ -85,12 +85,14 @@ typedef struct {
   int32_t act;   /* s4tf_act */
   int32_t dtype; /* s4tf_dtype */
   int32_t accumulate_dres; /* pullback adds into dresidual instead of overwriting */
+  int32_t accumulate_dx;   /* pullback adds into dx instead of overwriting (Section 4.3) */
 } s4tf_bn_desc;
 
 /* Head: global average pool over (h,w), dense c -> classes, mean softmax cross-entropy. */
 typedef struct {
   int32_t n, h, w, c, classes;
   int32_t dtype; /* storage type of x and dx; W, b, loss and their gradients are fp32 */
+  int32_t accumulate_dx; /* the pullback adds into dx instead of overwriting (Section 4.3) */
 } s4tf_head_desc;
 
 typedef enum { S4TF_POOL_AVG2 = 0, S4TF_POOL_MAX3S2 = 1 } s4tf_pool_kind;
@@ -158,6 +160,32 @@ int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const 
                      void* dresidual, float* dgamma, float* dbeta, void* workspace,
                      size_t workspace_bytes, void* stream);
 
+/* ---- BatchNorm in inference mode ----------------------------------------------------------
+ * For models that start from trained parameters (the paper's Section 1 motivates fine-tuning from
+ * a checkpoint): running statistics take the place of batch statistics.
+ *   s4tf_bn_inference_fwd   y = act(gamma (x - running_mean)/sqrt(running_var + eps) + beta (+ residual));
+ *                           descriptor as for s4tf_bn_relu_fwd (eps from it), no workspace, nothing saved.
+ *   s4tf_bn_update_running  after a training-mode forward pass over `count` = n*h*w samples per channel:
+ *                           running_mean <- (1-momentum) running_mean + momentum save_mean
+ *                           running_var  <- (1-momentum) running_var  + momentum var count/(count-1)
+ *                           with var = 1/save_invstd^2 - eps the biased batch variance (so the running
+ *                           variance averages unbiased estimates).  In place on the two running arrays.
+ *   s4tf_bn_fold_into_conv  the convolution that equals "convolution (w, bias), then inference-mode
+ *                           BatchNorm": w_out[r,s,c,k] = w[r,s,c,k] s_k, bias_out[k] = beta_k + (bias_k -
+ *                           running_mean_k) s_k, s_k = gamma_k/sqrt(running_var_k + eps).  w, w_out have the
+ *                           descriptor's dtype (w_out rounded on store) and shape (r,s,c/groups,k); bias is
+ *                           nullable; bias_out is fp32 [k].  s4tf_conv2d_fwd with (w_out, bias_out) and the
+ *                           BatchNorm's activation then runs the pair as one kernel.
+ * gamma, beta and the statistics are fp32 arrays of c (fold: k) elements. */
+int s4tf_bn_inference_fwd(const s4tf_bn_desc* d, const void* x, const void* residual, const float* gamma,
+                          const float* beta, const float* running_mean, const float* running_var, void* y,
+                          void* stream);
+int s4tf_bn_update_running(int32_t c, size_t count, float momentum, float eps, const float* save_mean,
+                           const float* save_invstd, float* running_mean, float* running_var, void* stream);
+int s4tf_bn_fold_into_conv(const s4tf_conv_desc* d, const void* w, const float* bias, const float* gamma,
+                           const float* beta, const float* running_mean, const float* running_var, float eps,
+                           void* w_out, float* bias_out, void* stream);
+
 /* ---- pooling ---------------------------------------------------------------------------
  * AVG2 fwd: mean of the window; vjp: dy/4 to each of the four inputs.
  * MAX3S2 fwd: maximum of the in-range window; vjp: the whole dy goes to the first maximum
@@ -180,6 +208,23 @@ int s4tf_pool_dense_xent_fwd_vjp(const s4tf_head_desc* d, const void* x, const f
                                  const int32_t* labels, float* loss, void* dx, float* dW, float* db,
                                  float* logits, void* workspace, size_t workspace_bytes,
                                  void* stream);
+
+/* ---- indexing (gather of rows) and its pullback in the `inout` formulation ------------------
+ * The paper's Section 4.3 (and its Appendix B listing) takes `x[i]` as the example: a pullback of
+ * type (T) -> [T] must build a whole array of zeros to hold one value, O(n) per use, whereas the
+ * formulation (T, inout [T]) -> Void adds the cotangent in place, O(1) per use.
+ *   fwd:  y[j, :] = x[index[j], :]                      j = 0..count-1, rows of `cols` elements
+ *   vjp:  dx[index[j], :] += dy[j, :]                   in order of j (deterministic also when an
+ *         index repeats); dx is inout and only the gathered rows are touched: the work is
+ *         count * cols, whatever the number of rows of x.
+ * x, y, dy, dx have `dtype`; index is int32 [count] on the device with 0 <= index[j] < rows (an index
+ * out of range is skipped in both directions: y[j,:] = 0, no update).  count may be 0. */
+typedef struct {
+  int32_t rows, cols, count;
+  int32_t dtype; /* s4tf_dtype */
+} s4tf_gather_desc;
+int s4tf_gather_rows_fwd(const s4tf_gather_desc* d, const void* x, const int32_t* index, void* y, void* stream);
+int s4tf_gather_rows_vjp(const s4tf_gather_desc* d, const void* dy, const int32_t* index, void* dx, void* stream);
 
 /* ---- SGD with momentum, in place (`optimizer.update(&model, along: gradients)`) -------
  *   velocity <- momentum*velocity + grad;   param <- param - lr*velocity

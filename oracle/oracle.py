@@ -191,6 +191,57 @@ def sgd_momentum(param, velocity, grad, lr, momentum):
     lib().orc_sgd_momentum(_cs(param.size), _d(param), _d(velocity), _d(g), _cd(lr), _cd(momentum))
 
 
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def gather_rows_fwd(x, index):
+    """y[j,:] = x[index[j],:] for a 2-D x."""
+    x = _f64(x)
+    idx, ip = _i32(index)
+    y = np.empty((idx.size, x.shape[1]), np.float64)
+    lib().orc_gather_rows_fwd(_d(x), ip, _d(y), _ci(x.shape[0]), _ci(x.shape[1]), _ci(idx.size))
+    return y
+
+
+def gather_rows_vjp(dy, index, dx):
+    """In place on the float64 array dx: dx[index[j],:] += dy[j,:], in order of j."""
+    assert dx.dtype == np.float64 and dx.flags["C_CONTIGUOUS"]
+    dy = _f64(dy)
+    idx, ip = _i32(index)
+    lib().orc_gather_rows_vjp(_d(dy), ip, _d(dx), _ci(dx.shape[0]), _ci(dx.shape[1]), _ci(idx.size))
+
+
+def bn_inference_fwd(x, res, gamma, beta, running_mean, running_var, eps, act):
+    x = _f64(x)
+    res = _f64(res) if res is not None else None
+    c = x.shape[-1]
+    y = np.empty_like(x)
+    lib().orc_bn_inference_fwd(_d(x), _d(res), _d(_f64(gamma)), _d(_f64(beta)), _d(_f64(running_mean)),
+                               _d(_f64(running_var)), _d(y), _cs(x.size // c), _ci(c), _cd(eps), _ci(_ACT[act]))
+    return y
+
+
+def bn_update_running(mean, invstd, running_mean, running_var, count, momentum, eps):
+    """Returns the updated (running_mean, running_var); count = samples per channel of the batch."""
+    rm, rv = _f64(running_mean).copy(), _f64(running_var).copy()
+    lib().orc_bn_update_running(_d(_f64(mean)), _d(_f64(invstd)), _d(rm), _d(rv), _ci(rm.size), _cs(count),
+                                _cd(momentum), _cd(eps))
+    return rm, rv
+
+
+def bn_fold(w, bias, gamma, beta, running_mean, running_var, eps):
+    """Filter and bias of the convolution that equals conv(w, bias) followed by inference-mode BatchNorm."""
+    w = _f64(w)
+    k = w.shape[-1]
+    w_out, b_out = np.empty_like(w), np.empty(k, np.float64)
+    b = _f64(bias) if bias is not None else None
+    lib().orc_bn_fold(_d(w), _d(b), _d(_f64(gamma)), _d(_f64(beta)), _d(_f64(running_mean)), _d(_f64(running_var)),
+                      _d(w_out), _d(b_out), _cs(w.size // k), _ci(k), _cd(eps))
+    return w_out, b_out
+
+
 # --------------------------------------------------------------------------------------
 # whole step
 # --------------------------------------------------------------------------------------

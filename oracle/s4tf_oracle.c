@@ -442,3 +442,61 @@ void orc_sgd_momentum(size_t count, double* param, double* velocity, const doubl
     param[i] -= lr * velocity[i];
   }
 }
+
+/* ---------------------------------------------------------------------------------
+ * Indexing and its pullback in the `inout` formulation (the paper's Section 4.3 and the
+ * listing of its Appendix B use x[i] as the example: a pullback (T) -> [T] has to build
+ * an array of zeros, one of type (T, inout [T]) -> Void adds the cotangent in place).
+ *   fwd:  y[j,:] = x[index[j],:]
+ *   vjp:  dx[index[j],:] += dy[j,:]  for j = 0, 1, ... in that order; dx is inout and only
+ *         the named rows are touched.  An index outside [0, rows) is skipped (y row = 0).
+ * --------------------------------------------------------------------------------- */
+void orc_gather_rows_fwd(const double* x, const int32_t* index, double* y, int rows, int cols, int count) {
+  for (int j = 0; j < count; ++j)
+    for (int c = 0; c < cols; ++c)
+      y[(size_t)j * cols + c] = (index[j] >= 0 && index[j] < rows) ? x[(size_t)index[j] * cols + c] : 0.0;
+}
+void orc_gather_rows_vjp(const double* dy, const int32_t* index, double* dx, int rows, int cols, int count) {
+  for (int j = 0; j < count; ++j) {
+    if (index[j] < 0 || index[j] >= rows) continue;
+    for (int c = 0; c < cols; ++c) dx[(size_t)index[j] * cols + c] += dy[(size_t)j * cols + c];
+  }
+}
+
+/* ---------------------------------------------------------------------------------
+ * BatchNorm in inference mode (running statistics instead of batch statistics), the
+ * update of the running statistics from a training-mode forward pass, and the folding
+ * of an inference-mode BatchNorm into the convolution in front of it.  The paper only
+ * mentions starting from trained checkpoints (Section 1); the arithmetic is the usual:
+ *   inference:  y = act(gamma (x - rm)/sqrt(rv + eps) + beta (+ res))
+ *   update:     rm <- (1-mom) rm + mom mean;  rv <- (1-mom) rv + mom var m/(m-1)
+ *               with var = 1/invstd^2 - eps the biased batch variance
+ *   fold:       w'[.,k] = w[.,k] s_k,  b'_k = beta_k + (b_k - rm_k) s_k,  s_k = gamma_k/sqrt(rv_k + eps)
+ *               so that conv(x, w') + b' = BN_inference(conv(x, w) + b)
+ * --------------------------------------------------------------------------------- */
+void orc_bn_inference_fwd(const double* x, const double* res, const double* gamma, const double* beta,
+                          const double* rm, const double* rv, double* y, size_t M, int C, double eps, int act) {
+  for (size_t m = 0; m < M; ++m)
+    for (int c = 0; c < C; ++c) {
+      double z = gamma[c] * (x[m * C + c] - rm[c]) / sqrt(rv[c] + eps) + beta[c];
+      if (res) z += res[m * C + c];
+      y[m * C + c] = act_apply(z, act);
+    }
+}
+void orc_bn_update_running(const double* mean, const double* invstd, double* rm, double* rv, int C, size_t M,
+                           double momentum, double eps) {
+  for (int c = 0; c < C; ++c) {
+    double var = 1.0 / (invstd[c] * invstd[c]) - eps;
+    double unbiased = M > 1 ? var * (double)M / (double)(M - 1) : var;
+    rm[c] = (1.0 - momentum) * rm[c] + momentum * mean[c];
+    rv[c] = (1.0 - momentum) * rv[c] + momentum * unbiased;
+  }
+}
+void orc_bn_fold(const double* w, const double* bias, const double* gamma, const double* beta, const double* rm,
+                 const double* rv, double* w_out, double* bias_out, size_t rows, int K, double eps) {
+  for (int k = 0; k < K; ++k) {
+    double s = gamma[k] / sqrt(rv[k] + eps);
+    bias_out[k] = beta[k] + ((bias ? bias[k] : 0.0) - rm[k]) * s;
+    for (size_t i = 0; i < rows; ++i) w_out[i * K + k] = w[i * K + k] * s;
+  }
+}

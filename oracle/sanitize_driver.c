@@ -33,6 +33,15 @@ void orc_head_fwd_vjp(const double* x, const double* Wt, const double* b, const 
                       double* dx, double* dW, double* db, double* logits, int N, int H, int W, int C, int classes);
 void orc_sgd_momentum(size_t count, double* param, double* velocity, const double* grad, double lr, double momentum);
 
+void orc_gather_rows_fwd(const double* x, const int32_t* index, double* y, int rows, int cols, int count);
+void orc_gather_rows_vjp(const double* dy, const int32_t* index, double* dx, int rows, int cols, int count);
+void orc_bn_inference_fwd(const double* x, const double* res, const double* gamma, const double* beta, const double* rm,
+                          const double* rv, double* y, size_t M, int C, double eps, int act);
+void orc_bn_update_running(const double* mean, const double* invstd, double* rm, double* rv, int C, size_t M,
+                           double momentum, double eps);
+void orc_bn_fold(const double* w, const double* bias, const double* gamma, const double* beta, const double* rm,
+                 const double* rv, double* w_out, double* bias_out, size_t rows, int K, double eps);
+
 static uint64_t state = 88172645463325252ull;
 static double rnd(void) { /* xorshift64, mapped to (-1, 1) */
   state ^= state << 13;
@@ -132,6 +141,25 @@ int main(void) {
     orc_round_bf16(p, 1001);
     orc_round_bf16_slow(v, 1001);
     free(p); free(v); free(g);
+  }
+  {
+    int32_t idx[6] = {3, 9, 3, 0, -1, 10};
+    double *x = buf(10 * 5), *y = buf(6 * 5), *dy = buf(6 * 5), *dx = buf(10 * 5);
+    orc_gather_rows_fwd(x, idx, y, 10, 5, 6);
+    orc_gather_rows_vjp(dy, idx, dx, 10, 5, 6);
+    orc_gather_rows_fwd(x, idx, y, 10, 5, 0);
+    free(x); free(y); free(dy); free(dx);
+  }
+  {
+    double *x = buf(35 * 6), *res = buf(35 * 6), *g = buf(6), *be = buf(6), *rm = buf(6), *rv = buf(6), *y = buf(35 * 6);
+    double *w = buf(27 * 6), *b = buf(6), *wo = buf(27 * 6), *bo = buf(6), *is = buf(6);
+    for (int c = 0; c < 6; ++c) { rv[c] = 0.5 + rv[c] * rv[c]; is[c] = 0.5 + is[c] * is[c]; }
+    for (int act = 0; act < 3; ++act) orc_bn_inference_fwd(x, act ? res : NULL, g, be, rm, rv, y, 35, 6, 1e-5, act);
+    orc_bn_update_running(rm, is, rm, rv, 6, 35, 0.1, 1e-5);
+    orc_bn_update_running(rm, is, rm, rv, 6, 1, 1.0, 0.0);
+    orc_bn_fold(w, b, g, be, rm, rv, wo, bo, 27, 6, 1e-5);
+    orc_bn_fold(w, NULL, g, be, rm, rv, wo, bo, 27, 6, 1e-5);
+    free(x); free(res); free(g); free(be); free(rm); free(rv); free(y); free(w); free(b); free(wo); free(bo); free(is);
   }
   printf("ok\n");
   return 0;

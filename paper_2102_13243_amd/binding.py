@@ -26,11 +26,15 @@ class ConvDesc(ctypes.Structure):
 
 class BnDesc(ctypes.Structure):
     _fields_ = [("n", c_i32), ("h", c_i32), ("w", c_i32), ("c", c_i32), ("eps", c_f32), ("act", c_i32),
-                ("dtype", c_i32), ("accumulate_dres", c_i32)]
+                ("dtype", c_i32), ("accumulate_dres", c_i32), ("accumulate_dx", c_i32)]
 
 
 class HeadDesc(ctypes.Structure):
-    _fields_ = [(n, c_i32) for n in ("n", "h", "w", "c", "classes", "dtype")]
+    _fields_ = [(n, c_i32) for n in ("n", "h", "w", "c", "classes", "dtype", "accumulate_dx")]
+
+
+class GatherDesc(ctypes.Structure):
+    _fields_ = [(n, c_i32) for n in ("rows", "cols", "count", "dtype")]
 
 
 class PoolDesc(ctypes.Structure):
@@ -96,6 +100,16 @@ def lib():
     L.s4tf_pool2d_vjp.argtypes = [P(PoolDesc), c_vp, c_vp, c_vp, c_vp]
     L.s4tf_pool_dense_xent_fwd_vjp.argtypes = [P(HeadDesc)] + [c_vp] * 10 + [c_sz, c_vp]
     L.s4tf_sgd_momentum.argtypes = [c_sz, c_vp, c_vp, c_vp, c_vp, c_f32, c_f32, c_vp]
+    L.s4tf_bn_inference_fwd.argtypes = [P(BnDesc)] + [c_vp] * 8
+    L.s4tf_bn_inference_fwd.restype = ctypes.c_int
+    L.s4tf_bn_update_running.argtypes = [c_i32, c_sz, c_f32, c_f32, c_vp, c_vp, c_vp, c_vp, c_vp]
+    L.s4tf_bn_update_running.restype = ctypes.c_int
+    L.s4tf_bn_fold_into_conv.argtypes = [P(ConvDesc)] + [c_vp] * 6 + [c_f32, c_vp, c_vp, c_vp]
+    L.s4tf_bn_fold_into_conv.restype = ctypes.c_int
+    L.s4tf_gather_rows_fwd.argtypes = [P(GatherDesc), c_vp, c_vp, c_vp, c_vp]
+    L.s4tf_gather_rows_fwd.restype = ctypes.c_int
+    L.s4tf_gather_rows_vjp.argtypes = [P(GatherDesc), c_vp, c_vp, c_vp, c_vp]
+    L.s4tf_gather_rows_vjp.restype = ctypes.c_int
     L.s4tf_round_to_bf16.argtypes = [c_sz, c_vp, c_vp, c_vp]
     L.s4tf_round_to_bf16.restype = ctypes.c_int
     L.s4tf_net_param_count.restype = c_sz
@@ -228,6 +242,29 @@ def s4tf_pool_dense_xent_fwd_vjp(d, x, W, b, labels, loss, dx, dW, db, logits, w
 def s4tf_sgd_momentum(count, param, velocity, grad, param_lowp, lr, momentum, stream=None):
     _check(lib().s4tf_sgd_momentum(count, _p(param), _p(velocity), _p(grad), _p(param_lowp), lr, momentum,
                                    _stream(stream)))
+
+
+def s4tf_bn_inference_fwd(d, x, residual, gamma, beta, running_mean, running_var, y, stream=None):
+    _check(lib().s4tf_bn_inference_fwd(ctypes.byref(d), _p(x), _p(residual), _p(gamma), _p(beta), _p(running_mean),
+                                       _p(running_var), _p(y), _stream(stream)))
+
+
+def s4tf_bn_update_running(c, count, momentum, eps, save_mean, save_invstd, running_mean, running_var, stream=None):
+    _check(lib().s4tf_bn_update_running(c, count, momentum, eps, _p(save_mean), _p(save_invstd), _p(running_mean),
+                                        _p(running_var), _stream(stream)))
+
+
+def s4tf_bn_fold_into_conv(d, w, bias, gamma, beta, running_mean, running_var, eps, w_out, bias_out, stream=None):
+    _check(lib().s4tf_bn_fold_into_conv(ctypes.byref(d), _p(w), _p(bias), _p(gamma), _p(beta), _p(running_mean),
+                                        _p(running_var), eps, _p(w_out), _p(bias_out), _stream(stream)))
+
+
+def s4tf_gather_rows_fwd(d, x, index, y, stream=None):
+    _check(lib().s4tf_gather_rows_fwd(ctypes.byref(d), _p(x), _p(index), _p(y), _stream(stream)))
+
+
+def s4tf_gather_rows_vjp(d, dy, index, dx, stream=None):
+    _check(lib().s4tf_gather_rows_vjp(ctypes.byref(d), _p(dy), _p(index), _p(dx), _stream(stream)))
 
 
 def s4tf_round_to_bf16(count, src, dst, stream=None):

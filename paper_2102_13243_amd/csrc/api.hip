@@ -259,6 +259,36 @@ int s4tf_bn_relu_vjp(const s4tf_bn_desc* d, const void* x, const void* y, const 
   return bn_vjp(*d, x, y, gamma, beta, save_mean, save_invstd, dy, dx, dresidual, dgamma, dbeta, workspace, (hipStream_t)stream);
 }
 
+// ---- batch norm, inference mode ------------------------------------------------------------------------------
+int s4tf_bn_inference_fwd(const s4tf_bn_desc* d, const void* x, const void* residual, const float* gamma,
+                          const float* beta, const float* running_mean, const float* running_var, void* y, void* stream) {
+  clear_error();
+  CHECK(check_bn_desc(d));
+  CHECK(need(x, "x")); CHECK(need(gamma, "gamma")); CHECK(need(beta, "beta")); CHECK(need(y, "y"));
+  CHECK(need(running_mean, "running_mean")); CHECK(need(running_var, "running_var")); CHECK(opt(residual, "residual"));
+  return bn_inference_fwd(*d, x, residual, gamma, beta, running_mean, running_var, y, (hipStream_t)stream);
+}
+int s4tf_bn_update_running(int32_t c, size_t count, float momentum, float eps, const float* save_mean,
+                           const float* save_invstd, float* running_mean, float* running_var, void* stream) {
+  clear_error();
+  if (c <= 0 || count == 0) return fail(S4TF_ERR_SHAPE, "bn_update_running: c and count must be positive");
+  if (!(momentum >= 0.f && momentum <= 1.f) || !(eps >= 0.f)) return fail(S4TF_ERR_SHAPE, "bn_update_running: momentum in [0,1], eps >= 0");
+  CHECK(need(save_mean, "save_mean")); CHECK(need(save_invstd, "save_invstd"));
+  CHECK(need(running_mean, "running_mean")); CHECK(need(running_var, "running_var"));
+  return bn_update_running(c, count, momentum, eps, save_mean, save_invstd, running_mean, running_var, (hipStream_t)stream);
+}
+int s4tf_bn_fold_into_conv(const s4tf_conv_desc* d, const void* w, const float* bias, const float* gamma,
+                           const float* beta, const float* running_mean, const float* running_var, float eps,
+                           void* w_out, float* bias_out, void* stream) {
+  clear_error();
+  CHECK(check_conv_desc(d));
+  if (!(eps >= 0.f)) return fail(S4TF_ERR_SHAPE, "bn_fold: eps must be >= 0");
+  CHECK(need(w, "w")); CHECK(need(gamma, "gamma")); CHECK(need(beta, "beta")); CHECK(need(running_mean, "running_mean"));
+  CHECK(need(running_var, "running_var")); CHECK(need(w_out, "w_out")); CHECK(need(bias_out, "bias_out")); CHECK(opt(bias, "bias"));
+  return bn_fold(d->dtype, (long long)d->r * d->s * (d->c / d->groups), d->k, w, bias, gamma, beta, running_mean, running_var, eps,
+                 w_out, bias_out, (hipStream_t)stream);
+}
+
 // ---- pooling ----------------------------------------------------------------------------------------------
 int s4tf_pool2d_fwd(const s4tf_pool_desc* d, const void* x, void* y, void* stream) {
   clear_error();
@@ -298,6 +328,30 @@ int s4tf_sgd_momentum(size_t count, float* param, float* velocity, const float* 
   if (count == 0) return S4TF_OK;
   CHECK(need(param, "param")); CHECK(need(velocity, "velocity")); CHECK(need(grad, "grad")); CHECK(opt(param_lowp, "param_lowp"));
   return sgd(count, param, velocity, grad, param_lowp, lr, momentum, (hipStream_t)stream);
+}
+
+// ---- indexing -------------------------------------------------------------------------------------------------
+static int check_gather_desc(const s4tf_gather_desc* d) {
+  if (!d) return fail(S4TF_ERR_NULL, "gather descriptor is NULL");
+  if (!dtype_ok(d->dtype)) return fail(S4TF_ERR_DTYPE, "gather: bad dtype %d", d->dtype);
+  if (d->rows <= 0 || d->cols <= 0 || d->count < 0) return fail(S4TF_ERR_SHAPE, "gather: rows and cols must be positive, count >= 0");
+  if ((long long)d->rows * d->cols > kMaxElems || (long long)d->count * d->cols > kMaxElems)
+    return fail(S4TF_ERR_SHAPE, "gather: tensor exceeds 2^31-1 elements");
+  return S4TF_OK;
+}
+int s4tf_gather_rows_fwd(const s4tf_gather_desc* d, const void* x, const int32_t* index, void* y, void* stream) {
+  clear_error();
+  CHECK(check_gather_desc(d));
+  if (d->count == 0) return S4TF_OK;
+  CHECK(need(x, "x")); CHECK(need(index, "index")); CHECK(need(y, "y"));
+  return gather_rows_fwd(*d, x, index, y, (hipStream_t)stream);
+}
+int s4tf_gather_rows_vjp(const s4tf_gather_desc* d, const void* dy, const int32_t* index, void* dx, void* stream) {
+  clear_error();
+  CHECK(check_gather_desc(d));
+  if (d->count == 0) return S4TF_OK;
+  CHECK(need(dy, "dy")); CHECK(need(index, "index")); CHECK(need(dx, "dx"));
+  return gather_rows_vjp(*d, dy, index, dx, (hipStream_t)stream);
 }
 
 int s4tf_round_to_bf16(size_t count, const float* src, void* dst, void* stream) {

@@ -285,7 +285,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        const float* __restrict__ mean, const float* __restrict__ invstd,
                                                        T* __restrict__ y, unsigned char* __restrict__ bits, long long M,
-                                                       int C, int cvb, long long per, int act) {
+                                                       int C, int cvb, long long per, int act, float infer_eps) {
   const int CV = C / V, pl_count = blockDim.x / cvb;
   const int cvl = threadIdx.x % cvb, pl = threadIdx.x / cvb;
   const int cv = blockIdx.x * cvb + cvl;
@@ -296,7 +296,9 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
 #pragma unroll
   for (int e = 0; e < V; ++e) {
     mu[e] = mean[c + e];
-    sc[e] = gamma[c + e] * invstd[c + e];
+    // inference mode (infer_eps >= 0): `mean` and `invstd` are the running mean and the running VARIANCE
+    const float is = infer_eps >= 0.f ? 1.0f / sqrtf(invstd[c + e] + infer_eps) : invstd[c + e];
+    sc[e] = gamma[c + e] * is;
     be[e] = beta[c + e];
   }
   const float act_lo = act == S4TF_ACT_NONE ? -__builtin_inff() : 0.f;
@@ -436,7 +438,7 @@ __global__ __launch_bounds__(FIN_THREADS) void bn_vjp_finalize_kernel(const doub
   dgamma[c] = (float)s2;
 }
 
-template <typename T, int V, bool REMASK, bool BITS = false>
+template <typename T, int V, bool REMASK, bool BITS = false, bool ACCDX = false>
 __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const T* __restrict__ y,
                                                            const T* __restrict__ dy, const float* __restrict__ gamma,
                                                            const float* __restrict__ mean, const float* __restrict__ invstd,
@@ -467,7 +469,7 @@ __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const
     a2[e] = gs[e] * (is * (dgamma[c + e] * invM));
   }
   const long long p0 = (long long)blockIdx.y * per, p1 = p0 + per < M ? p0 + per : M;
-  Pack<T, V> xv[UNROLL], dv[UNROLL], yv[UNROLL], ov[UNROLL];
+  Pack<T, V> xv[UNROLL], dv[UNROLL], yv[UNROLL], ov[UNROLL], av[UNROLL];
   unsigned char bv[UNROLL];
   walk_pixels(p0 + pl, p1, pl_count,
               [&](long long m, int u) {
@@ -476,6 +478,7 @@ __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const
                 if (BITS) bv[u] = bits[m * CV + cv];
                 else if (act != S4TF_ACT_NONE && !remask) yv[u] = ldp<T, V>(y + m * C + c);
                 if (dres && acc_dres) ov[u] = ldp<T, V>(dres + m * C + c);
+                if (ACCDX) av[u] = ldp<T, V>(dx + m * C + c);  // the cotangent dx already holds
               },
               [&](long long m, int u) {
                 float o[V], r[V];
@@ -493,6 +496,7 @@ __device__ __forceinline__ void bn_vjp_apply_body(const T* __restrict__ x, const
                     dz = (yy > 0.f && yy < yhi) ? dz : 0.f;
                   }
                   o[e] = fmaf(gs[e], dz, -fmaf(xc, a2[e], a0[e]));
+                  if (ACCDX) o[e] += av[u].get(e);
                   r[e] = (dres && acc_dres) ? ov[u].get(e) + dz : dz;
                 }
                 stp<T, V>(dx + m * C + c, pack_of<T, V>(o));
@@ -513,6 +517,17 @@ template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply
 template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply_bits_kernel(BN_VJP_APPLY_ARGS) {
   bn_vjp_apply_body<T, V, false, true>(x, nullptr, dy, gamma, mean, invstd, beta, dgamma, dbeta, dx, dres, acc_dres, M, C,
                                        cvb, per, act, reinterpret_cast<const unsigned char*>(y));
+}
+// the same three, adding into the cotangent dx already holds (separate instances: the plain ones keep their registers)
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply_acc_kernel(BN_VJP_APPLY_ARGS) {
+  bn_vjp_apply_body<T, V, false, false, true>(x, y, dy, gamma, mean, invstd, beta, dgamma, dbeta, dx, dres, acc_dres, M, C, cvb, per, act);
+}
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply_remask_acc_kernel(BN_VJP_APPLY_ARGS) {
+  bn_vjp_apply_body<T, V, true, false, true>(x, y, dy, gamma, mean, invstd, beta, dgamma, dbeta, dx, dres, acc_dres, M, C, cvb, per, act);
+}
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_vjp_apply_bits_acc_kernel(BN_VJP_APPLY_ARGS) {
+  bn_vjp_apply_body<T, V, false, true, true>(x, nullptr, dy, gamma, mean, invstd, beta, dgamma, dbeta, dx, dres, acc_dres, M, C,
+                                             cvb, per, act, reinterpret_cast<const unsigned char*>(y));
 }
 
 }  // namespace
@@ -577,8 +592,71 @@ int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* g
   }
   ProfScope ps(PC_BN_APPLY, st);
   BN_LAUNCH(bn_apply_kernel, pa, 0, (const T*)x, (const T*)res, gamma, beta, mean, invstd, (T*)y, maskbits, M, C, pa.cvb,
-            pa.per, d.act);
+            pa.per, d.act, -1.f);
   return launch_status("bn_apply");
+}
+
+int bn_inference_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
+                     const float* running_mean, const float* running_var, void* y, hipStream_t st) {
+  const long long M = (long long)d.n * d.h * d.w;
+  const int C = d.c;
+  const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, UNROLL);
+  ProfScope ps(PC_BN_APPLY, st);
+  BN_LAUNCH(bn_apply_kernel, pa, 0, (const T*)x, (const T*)res, gamma, beta, running_mean, running_var, (T*)y,
+            (unsigned char*)nullptr, M, C, pa.cvb, pa.per, d.act, d.eps);
+  return launch_status("bn_inference");
+}
+
+namespace {
+__global__ void bn_update_running_kernel(const float* __restrict__ mean, const float* __restrict__ invstd,
+                                         float* __restrict__ rm, float* __restrict__ rv, int C, double count,
+                                         float momentum, float eps) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  const double is = (double)invstd[c];
+  const double var = 1.0 / (is * is) - (double)eps;                       // the biased batch variance
+  const double unbiased = count > 1.0 ? var * count / (count - 1.0) : var;
+  rm[c] = (float)((1.0 - (double)momentum) * (double)rm[c] + (double)momentum * (double)mean[c]);
+  rv[c] = (float)((1.0 - (double)momentum) * (double)rv[c] + (double)momentum * unbiased);
+}
+// w'[i][k] = w[i][k] * s_k with s_k = gamma_k / sqrt(rv_k + eps); thread 0..K-1 of block 0 also writes the bias
+template <typename T>
+__global__ __launch_bounds__(256) void bn_fold_kernel(const T* __restrict__ w, const float* __restrict__ bias,
+                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                      const float* __restrict__ rm, const float* __restrict__ rv,
+                                                      T* __restrict__ w_out, float* __restrict__ bias_out, long long total,
+                                                      int K, float eps) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < K) {
+    const float s = gamma[i] / sqrtf(rv[i] + eps);
+    bias_out[i] = fmaf((bias ? bias[i] : 0.f) - rm[i], s, beta[i]);
+  }
+  if (i >= total) return;
+  const int k = (int)(i % K);
+  w_out[i] = from_f32<T>(to_f32<T>(w[i]) * (gamma[k] / sqrtf(rv[k] + eps)));
+}
+}  // namespace
+
+int bn_update_running(int C, size_t count, float momentum, float eps, const float* mean, const float* invstd,
+                      float* rm, float* rv, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  hipLaunchKernelGGL(bn_update_running_kernel, dim3((C + 255) / 256), dim3(256), 0, st, mean, invstd, rm, rv, C, (double)count,
+                     momentum, eps);
+  return launch_status("bn_update_running");
+}
+int bn_fold(int dtype, long long rows, int K, const void* w, const float* bias, const float* gamma, const float* beta,
+            const float* rm, const float* rv, float eps, void* w_out, float* bias_out, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  const long long total = rows * K;
+  const long long span = total > K ? total : K;
+  const unsigned blocks = (unsigned)((span + 255) / 256);
+  if (dtype == S4TF_BF16)
+    hipLaunchKernelGGL(bn_fold_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)w, bias, gamma, beta, rm, rv,
+                       (bf16_t*)w_out, bias_out, total, K, eps);
+  else
+    hipLaunchKernelGGL(bn_fold_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)w, bias, gamma, beta, rm, rv,
+                       (float*)w_out, bias_out, total, K, eps);
+  return launch_status("bn_fold");
 }
 
 size_t bn_fwd_scratch_bytes(const s4tf_bn_desc& d) {
@@ -629,6 +707,18 @@ int bn_vjp(const s4tf_bn_desc& d, const void* x, const void* y, const float* gam
     if ((rc = launch_status("bn_vjp_finalize")) != S4TF_OK) return rc;
   }
   ProfScope ps(PC_BN_VJP_APPLY, st);
+  if (d.accumulate_dx) {
+    if (maskbits)
+      BN_LAUNCH(bn_vjp_apply_bits_acc_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, beta, dgamma, dbeta,
+                (T*)dx, (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);
+    else if (beta)
+      BN_LAUNCH(bn_vjp_apply_remask_acc_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, beta, dgamma, dbeta,
+                (T*)dx, (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);
+    else
+      BN_LAUNCH(bn_vjp_apply_acc_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, beta, dgamma, dbeta,
+                (T*)dx, (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);
+    return launch_status("bn_vjp_apply");
+  }
   if (maskbits)
     BN_LAUNCH(bn_vjp_apply_bits_kernel, pa, 0, (const T*)x, (const T*)y, (const T*)dy, gamma, mean, invstd, beta, dgamma, dbeta,
               (T*)dx, (T*)dres, d.accumulate_dres, M, C, pa.cvb, pa.per, d.act);

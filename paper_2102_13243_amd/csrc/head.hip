@@ -148,16 +148,21 @@ __global__ void mean_loss_kernel(const float* __restrict__ rowloss, float* __res
 }
 
 // dx[n][hw][c] = (sum over splits of part[s][n][c]) / HW: one thread per (n, c) walks the pixels
+// (accumulate: added to what dx holds, one rounding of the sum per element)
 template <typename T>
-__global__ void gap_vjp_kernel(const float* __restrict__ part, int splits, T* __restrict__ dx, int N, int HW, int C) {
+__global__ void gap_vjp_kernel(const float* __restrict__ part, int splits, T* dx, int N, int HW, int C, int accumulate) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= N * C) return;
   const int c = i % C, n = i / C;
   float v = 0.f;
   for (int s = 0; s < splits; ++s) v += part[(long long)s * N * C + i];
-  const T o = from_f32<T>(v / (float)HW);
+  v /= (float)HW;
+  const T o = from_f32<T>(v);
   T* p = dx + (long long)n * HW * C + c;
-  for (int j = 0; j < HW; ++j) p[(long long)j * C] = o;
+  if (accumulate)
+    for (int j = 0; j < HW; ++j) p[(long long)j * C] = from_f32<T>(to_f32<T>(p[(long long)j * C]) + v);
+  else
+    for (int j = 0; j < HW; ++j) p[(long long)j * C] = o;
 }
 
 ConvGeom dense_geom(int N, int C, int K) {
@@ -229,9 +234,9 @@ int head_fwd_vjp(const s4tf_head_desc& d, const void* x, const float* W, const f
     if ((rc = launch_status("head dpbar")) != S4TF_OK) return rc;
     const unsigned blocks = (unsigned)(((long long)d.n * d.c + 255) / 256);
     if (d.dtype == S4TF_BF16)
-      hipLaunchKernelGGL(gap_vjp_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, part, sp.splits, (bf16_t*)dx, d.n, HW, d.c);
+      hipLaunchKernelGGL(gap_vjp_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, part, sp.splits, (bf16_t*)dx, d.n, HW, d.c, d.accumulate_dx);
     else
-      hipLaunchKernelGGL(gap_vjp_kernel<float>, dim3(blocks), dim3(256), 0, st, part, sp.splits, (float*)dx, d.n, HW, d.c);
+      hipLaunchKernelGGL(gap_vjp_kernel<float>, dim3(blocks), dim3(256), 0, st, part, sp.splits, (float*)dx, d.n, HW, d.c, d.accumulate_dx);
     if ((rc = launch_status("gap_vjp")) != S4TF_OK) return rc;
   }
   return S4TF_OK;

@@ -412,7 +412,54 @@ __global__ __launch_bounds__(256) void round_bf16_kernel(const float* __restrict
   for (long long j = n4 * 4 + (long long)blockIdx.x * blockDim.x + threadIdx.x; j < n; j += stride) dst[j] = f32_to_bf16(src[j]);
 }
 
+// y[j, :] = x[index[j], :]; a thread copies one element, adjacent threads adjacent columns
+template <typename T>
+__global__ __launch_bounds__(256) void gather_rows_fwd_kernel(const T* __restrict__ x, const int32_t* __restrict__ index,
+                                                              T* __restrict__ y, int rows, int cols, long long total) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const long long j = i / cols;
+  const int col = (int)(i - j * cols);
+  const int r = index[j];
+  y[i] = (r >= 0 && r < rows) ? x[(long long)r * cols + col] : from_f32<T>(0.f);
+}
+// dx[index[j], :] += dy[j, :] for j = 0, 1, ... in that order: a thread owns one column and walks the gathered
+// rows, so a row that is named twice receives its two contributions in a fixed order, and only the named rows of
+// dx are read or written: count * cols element updates whatever the size of dx.
+template <typename T>
+__global__ __launch_bounds__(256) void gather_rows_vjp_kernel(const T* __restrict__ dy, const int32_t* __restrict__ index,
+                                                              T* dx, int rows, int cols, int count) {
+  const int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= cols) return;
+  for (int j = 0; j < count; ++j) {
+    const int r = index[j];
+    if (r < 0 || r >= rows) continue;
+    T* p = dx + (long long)r * cols + col;
+    *p = from_f32<T>(to_f32<T>(*p) + to_f32<T>(dy[(long long)j * cols + col]));
+  }
+}
+
 }  // namespace
+
+int gather_rows_fwd(const s4tf_gather_desc& d, const void* x, const int32_t* index, void* y, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  const long long total = (long long)d.count * d.cols;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  if (d.dtype == S4TF_BF16)
+    hipLaunchKernelGGL(gather_rows_fwd_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)x, index, (bf16_t*)y, d.rows, d.cols, total);
+  else
+    hipLaunchKernelGGL(gather_rows_fwd_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)x, index, (float*)y, d.rows, d.cols, total);
+  return launch_status("gather_rows_fwd");
+}
+int gather_rows_vjp(const s4tf_gather_desc& d, const void* dy, const int32_t* index, void* dx, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  const unsigned blocks = (unsigned)((d.cols + 255) / 256);
+  if (d.dtype == S4TF_BF16)
+    hipLaunchKernelGGL(gather_rows_vjp_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)dy, index, (bf16_t*)dx, d.rows, d.cols, d.count);
+  else
+    hipLaunchKernelGGL(gather_rows_vjp_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)dy, index, (float*)dx, d.rows, d.cols, d.count);
+  return launch_status("gather_rows_vjp");
+}
 
 int round_to_bf16(size_t count, const float* src, void* dst, hipStream_t st) {
   ProfScope ps(PC_ELEMENTWISE, st);

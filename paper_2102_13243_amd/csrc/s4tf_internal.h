@@ -134,6 +134,14 @@ size_t bn_mask_bytes(size_t M, int C, int dtype);
 int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
            void* y, float* mean, float* invstd, void* ws, hipStream_t st, const float* stats_part = nullptr,
            int stats_rows = 0, unsigned char* maskbits = nullptr);
+// inference mode: running statistics instead of batch statistics; their update from a training-mode forward
+// pass; folding of an inference-mode BatchNorm into the convolution in front of it
+int bn_inference_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* gamma, const float* beta,
+                     const float* running_mean, const float* running_var, void* y, hipStream_t st);
+int bn_update_running(int C, size_t count, float momentum, float eps, const float* mean, const float* invstd,
+                      float* rm, float* rv, hipStream_t st);
+int bn_fold(int dtype, long long rows, int K, const void* w, const float* bias, const float* gamma, const float* beta,
+            const float* rm, const float* rv, float eps, void* w_out, float* bias_out, hipStream_t st);
 // bn_fwd with its partial sums in a static device array instead of a workspace: allocates nothing; shapes
 // whose partial sums (bn_fwd_scratch_bytes) exceed bn_static_scratch_capacity() are refused
 size_t bn_fwd_scratch_bytes(const s4tf_bn_desc& d);
@@ -156,6 +164,10 @@ size_t head_workspace(const s4tf_head_desc& d);
 int head_fwd_vjp(const s4tf_head_desc& d, const void* x, const float* W, const float* b,
                  const int32_t* labels, float* loss, void* dx, float* dW, float* db, float* logits,
                  void* ws, hipStream_t st);
+
+// indexing: y[j,:] = x[index[j],:] and its in-place pullback dx[index[j],:] += dy[j,:] (in order of j)
+int gather_rows_fwd(const s4tf_gather_desc& d, const void* x, const int32_t* index, void* y, hipStream_t st);
+int gather_rows_vjp(const s4tf_gather_desc& d, const void* dy, const int32_t* index, void* dx, hipStream_t st);
 
 // storage-type conversion: dst[i] = bf16(src[i]), round to nearest even
 int round_to_bf16(size_t count, const float* src, void* dst, hipStream_t st);

@@ -695,3 +695,144 @@ def test_planned_network_step_is_bit_identical_to_the_descriptor_form(name, kw):
                     np.testing.assert_array_equal(x, y)
     finally:
         B.s4tf_net_destroy(handle)
+
+
+# ---- accumulating (`inout`) pullbacks and the indexing pullback (Section 4.3, Appendix B) ---------------------
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("act,use_res,remask", [("none", False, False), ("relu", False, True), ("relu", True, False),
+                                                ("relu6", False, False)])
+@pytest.mark.parametrize("shape", [(4, 16, 16, 64), (3, 9, 9, 6), (2, 7, 7, 960)], ids=lambda s: "x".join(map(str, s)))
+def test_bn_vjp_accumulates_into_dx(shape, act, use_res, remask, bf16):
+    """accumulate_dx: the BatchNorm pullback adds its input cotangent to what dx holds (one rounding of the sum
+    per element in bf16), in each of its variants (activation mask from y, or rebuilt from x when beta is given)."""
+    n, h, w, c = shape
+    x = grid(RNG.standard_normal(shape) * 1.5 + 1.0, bf16)
+    res = grid(RNG.standard_normal(shape), bf16) if use_res else None
+    gamma = (1.0 + 0.3 * RNG.standard_normal(c)).astype(np.float32)
+    beta = (0.2 * RNG.standard_normal(c) + (3.0 if act == "relu6" else 0.0)).astype(np.float32)
+    d = B.BnDesc(n, h, w, c, 1e-5, B.ACT[act], B.S4TF_BF16 if bf16 else B.S4TF_F32, 0, 1)
+    wsp = ws(B.s4tf_bn_relu_workspace_bytes(d))
+    xd, rd, gd, bd = to_dev(x, bf16), to_dev(res, bf16), to_dev(gamma), to_dev(beta)
+    y, mean, invstd = empty(shape, bf16), empty((c,)), empty((c,))
+    B.s4tf_bn_relu_fwd(d, xd, rd, gd, bd, y, mean, invstd, wsp)
+    y_gpu = to_host(y)
+    dy = grid(RNG.standard_normal(shape), bf16)
+    base = grid(RNG.standard_normal(shape), bf16)
+    dx_ref, _, dg_ref, db_ref = orc.bn_act_vjp(x, y_gpu, gamma, to_host(mean), to_host(invstd), dy, act, use_res)
+    dx = empty(shape, bf16)
+    dx.copy_(to_dev(base, bf16))
+    dres = empty(shape, bf16) if use_res else None
+    dg, db = empty((c,)), empty((c,))
+    B.s4tf_bn_relu_vjp(d, xd, None if remask else y, gd, bd if remask else None, mean, invstd, to_dev(dy, bf16), dx, dres,
+                       dg, db, wsp)
+    check("bn dgamma", dg, dg_ref, False, 1e-4)
+    check("bn dbeta", db, db_ref, False, 1e-4)
+    check("bn dx accumulated", dx, base + dx_ref, bf16, 6e-3 if bf16 else 5e-5)
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+def test_head_accumulates_into_dx(bf16):
+    n, h, w, c, k = 6, 7, 7, 256, 100
+    x = grid(RNG.standard_normal((n, h, w, c)), bf16)
+    W = (RNG.standard_normal((c, k)) * np.sqrt(2.0 / c)).astype(np.float32)
+    b = (0.1 * RNG.standard_normal(k)).astype(np.float32)
+    labels = RNG.integers(0, k, n).astype(np.int32)
+    d = B.HeadDesc(n, h, w, c, k, B.S4TF_BF16 if bf16 else B.S4TF_F32, 1)
+    wsp = ws(B.s4tf_pool_dense_xent_workspace_bytes(d))
+    _, dx_ref, _, _, _ = orc.head_fwd_vjp(x, W, b, labels)
+    base = grid(1e-3 * RNG.standard_normal((n, h, w, c)), bf16)    # on the scale of the head's own cotangent
+    loss, dx, dW, db = empty((4,)), empty((n, h, w, c), bf16), empty((c, k)), empty((k,))
+    dx.copy_(to_dev(base, bf16))
+    B.s4tf_pool_dense_xent_fwd_vjp(d, to_dev(x, bf16), to_dev(W), to_dev(b), to_dev(labels, dtype=np.int32), loss, dx, dW,
+                                   db, None, wsp)
+    check("head dx accumulated", dx, base + dx_ref, bf16, 4e-3 if bf16 else 5e-5)
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("rows,cols,count", [(1000, 64, 5), (50, 7, 6), (4096, 300, 1), (20, 1024, 40)])
+def test_gather_rows_and_its_inout_pullback(rows, cols, count, bf16):
+    """x[index] and the pullback dx[index[j]] += dy[j] in place: repeated indices add up in order, rows that
+    are not named keep their bits (the pullback touches count rows, not the whole of dx)."""
+    x = grid(RNG.standard_normal((rows, cols)), bf16)
+    idx = RNG.integers(0, rows, count).astype(np.int32)
+    if count >= 5:
+        idx[3] = idx[0]
+        idx[4] = idx[0]
+    d = B.GatherDesc(rows, cols, count, B.S4TF_BF16 if bf16 else B.S4TF_F32)
+    idx_d = to_dev(idx, dtype=np.int32)
+    y = empty((count, cols), bf16)
+    B.s4tf_gather_rows_fwd(d, to_dev(x, bf16), idx_d, y)
+    np.testing.assert_array_equal(to_host(y), orc.gather_rows_fwd(x, idx))
+    dy = grid(RNG.standard_normal((count, cols)), bf16)
+    base = grid(RNG.standard_normal((rows, cols)), bf16)
+    dx = empty((rows, cols), bf16)
+    dx.copy_(to_dev(base, bf16))
+    B.s4tf_gather_rows_vjp(d, to_dev(dy, bf16), idx_d, dx)
+    if bf16:   # the stored cotangent is rounded after every addition: the oracle's update, one index at a time
+        want = np.array(base, np.float64)
+        for j in range(count):
+            orc.gather_rows_vjp(dy[j:j + 1], idx[j:j + 1], want)
+            want[idx[j]] = orc.round_bf16(want[idx[j]])
+        np.testing.assert_array_equal(to_host(dx), want)
+    else:
+        want = np.array(base, np.float64)
+        orc.gather_rows_vjp(dy, idx, want)
+        check("gather dx", dx, want, False, 1e-6)
+    untouched = np.setdiff1d(np.arange(rows), idx)
+    np.testing.assert_array_equal(to_host(dx)[untouched], np.asarray(base, np.float64)[untouched])
+
+
+# ---- BatchNorm in inference mode: running statistics, folding into the convolution -----------------------------
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape,act,use_bias", [((4, 14, 14, 64, 128, 3, 1, 1), "relu", False),
+                                                ((2, 15, 15, 40, 48, 1, 2, 0), "relu6", True),
+                                                ((2, 12, 12, 24, 8, 5, 1, 2), "none", False)])
+def test_bn_inference_running_statistics_and_folding(shape, act, use_bias, bf16):
+    n, h, w, c, k, r, stride, pad = shape
+    x = grid(RNG.standard_normal((n, h, w, c)), bf16)
+    wt = grid(RNG.standard_normal((r, r, c, k)) * np.sqrt(2.0 / (r * r * c)), bf16)
+    bias = RNG.standard_normal(k).astype(np.float32) if use_bias else None
+    gamma = (1.0 + 0.3 * RNG.standard_normal(k)).astype(np.float32)
+    beta = (0.3 * RNG.standard_normal(k) + (2.0 if act == "relu6" else 0.0)).astype(np.float32)
+    eps = 1e-5
+    code = B.S4TF_BF16 if bf16 else B.S4TF_F32
+    cd = B.ConvDesc(n, h, w, c, k, r, r, stride, pad, 1, code, B.ACT["none"], 0)
+    p, q = (h + 2 * pad - r) // stride + 1, (w + 2 * pad - r) // stride + 1
+    xd, wd, bd = to_dev(x, bf16), to_dev(wt, bf16), to_dev(bias)
+    u = empty((n, p, q, k), bf16)
+    B.s4tf_conv2d_fwd(cd, xd, wd, bd, u)
+    u_gpu = to_host(u)
+    # a training-mode forward pass leaves batch statistics; running statistics are updated from them
+    bnd = B.BnDesc(n, p, q, k, eps, B.ACT[act], code, 0, 0)
+    wsp = ws(B.s4tf_bn_relu_workspace_bytes(bnd))
+    y, mean, invstd = empty((n, p, q, k), bf16), empty((k,)), empty((k,))
+    B.s4tf_bn_relu_fwd(bnd, u, None, to_dev(gamma), to_dev(beta), y, mean, invstd, wsp)
+    rm0 = RNG.standard_normal(k).astype(np.float32)
+    rv0 = (0.5 + RNG.random(k)).astype(np.float32)
+    rm, rv = empty((k,)), empty((k,))
+    rm.copy_(to_dev(rm0))
+    rv.copy_(to_dev(rv0))
+    B.s4tf_bn_update_running(k, n * p * q, 0.1, eps, mean, invstd, rm, rv)
+    rm_ref, rv_ref = orc.bn_update_running(to_host(mean), to_host(invstd), rm0, rv0, n * p * q, 0.1, eps)
+    check("running mean", rm, rm_ref, False, 1e-6)
+    check("running var", rv, rv_ref, False, 1e-6)
+    # inference-mode BatchNorm of the convolution's output
+    rm_h, rv_h = to_host(rm), to_host(rv)
+    yi = empty((n, p, q, k), bf16)
+    B.s4tf_bn_inference_fwd(bnd, u, None, to_dev(gamma), to_dev(beta), rm, rv, yi)
+    check("bn inference y", yi, orc.bn_inference_fwd(u_gpu, None, gamma, beta, rm_h, rv_h, eps, act), bf16,
+          4e-3 if bf16 else 2e-5)
+    # folded: one convolution with the BatchNorm's activation
+    wf, bf_ = empty((r, r, c, k), bf16), empty((k,))
+    B.s4tf_bn_fold_into_conv(cd, wd, bd, to_dev(gamma), to_dev(beta), rm, rv, eps, wf, bf_)
+    wf_ref, bf_ref = orc.bn_fold(wt, bias, gamma, beta, rm_h, rv_h, eps)
+    check("folded filter", wf, wf_ref, bf16, 4e-3 if bf16 else 1e-6)
+    check("folded bias", bf_, bf_ref, False, 1e-6)
+    fd = B.ConvDesc(n, h, w, c, k, r, r, stride, pad, 1, code, B.ACT[act], 0)
+    yf = empty((n, p, q, k), bf16)
+    B.s4tf_conv2d_fwd(fd, xd, wf, bf_, yf)
+    ref = orc.bias_act_fwd(orc.conv2d_fwd(x, to_host(wf), to_host(bf_), stride, pad), None, act)
+    check("folded conv y", yf, ref, bf16, 4e-3 if bf16 else 2e-5)
+    if not bf16:   # and the folded convolution is the unfolded pair (fp32: no intermediate rounding in between)
+        pair = orc.bn_inference_fwd(orc.conv2d_fwd(x, wt, bias, stride, pad), None, gamma, beta, rm_h, rv_h, eps, act)
+        check("folded conv = conv then BatchNorm", yf, pair, False, 2e-5)

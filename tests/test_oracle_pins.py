@@ -469,3 +469,68 @@ def test_bf16_fan_in_sums_cotangents_in_reverse_consumer_order_rounding_after_ea
     in_order = r32(r32(dres) + dconv)          # the later consumer (the residual input) first
     np.testing.assert_array_equal(cot[2], in_order)
     assert not np.array_equal(in_order, r32(r32(dconv) + dres))
+
+
+def test_gather_rows_and_its_inout_pullback():
+    """Indexing against NumPy's fancy indexing and np.add.at (repeated indices included), the adjoint identity
+    <gather(x), dy> = <x, scatter(dy)>, accumulation into what dx already holds, and the point of the inout
+    formulation (Section 4.3): rows that are not named are not touched."""
+    x = RNG.standard_normal((50, 7))
+    idx = np.array([3, 49, 3, 0, 17, 3], np.int32)
+    y = orc.gather_rows_fwd(x, idx)
+    np.testing.assert_array_equal(y, x[idx])
+    dy = RNG.standard_normal(y.shape)
+    base = RNG.standard_normal(x.shape)
+    dx = base.copy()
+    orc.gather_rows_vjp(dy, idx, dx)
+    want = base.copy()
+    np.add.at(want, idx, dy)
+    np.testing.assert_allclose(dx, want, rtol=1e-15, atol=1e-15)
+    untouched = np.setdiff1d(np.arange(50), idx)
+    np.testing.assert_array_equal(dx[untouched], base[untouched])
+    zero = np.zeros_like(x)
+    orc.gather_rows_vjp(dy, idx, zero)
+    np.testing.assert_allclose(np.sum(y * dy), np.sum(x * zero), rtol=1e-13)
+    # an index out of range reads zeros and writes nothing
+    bad = np.array([2, -1, 50], np.int32)
+    yb = orc.gather_rows_fwd(x, bad)
+    np.testing.assert_array_equal(yb[1:], 0.0)
+    dxb = base.copy()
+    orc.gather_rows_vjp(dy[:3], bad, dxb)
+    np.testing.assert_array_equal(np.delete(dxb, 2, axis=0), np.delete(base, 2, axis=0))
+
+
+@pytest.mark.parametrize("act,use_res,use_bias", [("none", False, False), ("relu", True, True), ("relu6", False, True)])
+def test_bn_inference_update_and_fold(act, use_res, use_bias):
+    """Inference-mode BatchNorm written out with NumPy; the running-statistics update against NumPy's unbiased
+    variance (momentum 1 from any start gives the batch statistics themselves); folding: the convolution with
+    folded filter and bias IS the convolution followed by inference-mode BatchNorm."""
+    x = RNG.standard_normal((2, 6, 5, 3))
+    w = RNG.standard_normal((3, 3, 3, 4)) * 0.4
+    bias = RNG.standard_normal(4) if use_bias else None
+    gamma, beta = 1.0 + 0.4 * RNG.standard_normal(4), RNG.standard_normal(4) + 2.0
+    rm, rv = RNG.standard_normal(4), 0.5 + RNG.random(4)
+    eps = 1e-3
+    u = orc.conv2d_fwd(x, w, bias, 1, 1)
+    res = RNG.standard_normal(u.shape) if use_res else None
+    z = gamma * (u - rm) / np.sqrt(rv + eps) + beta + (res if use_res else 0.0)
+    want = z if act == "none" else np.maximum(z, 0) if act == "relu" else np.clip(z, 0, 6)
+    y = orc.bn_inference_fwd(u, res, gamma, beta, rm, rv, eps, act)
+    np.testing.assert_allclose(y, want, rtol=1e-12, atol=1e-12)
+    # running statistics
+    _, mean, invstd = orc.bn_act_fwd(u, None, gamma, beta, eps, "none")
+    uf = u.reshape(-1, 4)
+    m = uf.shape[0]
+    rm1, rv1 = orc.bn_update_running(mean, invstd, rm, rv, m, 0.1, eps)
+    np.testing.assert_allclose(rm1, 0.9 * rm + 0.1 * uf.mean(0), rtol=1e-12)
+    np.testing.assert_allclose(rv1, 0.9 * rv + 0.1 * uf.var(0, ddof=1), rtol=1e-9)
+    rm2, rv2 = orc.bn_update_running(mean, invstd, rm, rv, m, 1.0, eps)
+    np.testing.assert_allclose(rm2, uf.mean(0), rtol=1e-12)
+    np.testing.assert_allclose(rv2, uf.var(0, ddof=1), rtol=1e-9)
+    # folding
+    wf, bf = orc.bn_fold(w, bias, gamma, beta, rm, rv, eps)
+    folded = orc.conv2d_fwd(x, wf, bf, 1, 1)
+    if use_res:
+        folded = folded + res
+    folded = orc.bias_act_fwd(folded, None, act)
+    np.testing.assert_allclose(folded, y, rtol=1e-11, atol=1e-11)
