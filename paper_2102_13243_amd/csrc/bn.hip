@@ -280,12 +280,14 @@ template <typename T> __device__ inline float remask_hi(int act) {
   return act == S4TF_ACT_RELU6 ? (sizeof(T) == 2 ? 5.984375f : 6.f) : __builtin_inff();
 }
 
-template <typename T, int V>
-__global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
-                                                       const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                       const float* __restrict__ mean, const float* __restrict__ invstd,
-                                                       T* __restrict__ y, unsigned char* __restrict__ bits, long long M,
-                                                       int C, int cvb, long long per, int act, float infer_eps) {
+// INFER: `mean` and `invstd` are the running mean and the running VARIANCE (inference mode); a template
+// parameter so that the training-mode kernel does not carry the square roots and divisions
+template <typename T, int V, bool INFER>
+__device__ __forceinline__ void bn_apply_body(const T* __restrict__ x, const T* __restrict__ res,
+                                              const float* __restrict__ gamma, const float* __restrict__ beta,
+                                              const float* __restrict__ mean, const float* __restrict__ invstd,
+                                              T* __restrict__ y, unsigned char* __restrict__ bits, long long M,
+                                              int C, int cvb, long long per, int act, float infer_eps) {
   const int CV = C / V, pl_count = blockDim.x / cvb;
   const int cvl = threadIdx.x % cvb, pl = threadIdx.x / cvb;
   const int cv = blockIdx.x * cvb + cvl;
@@ -296,8 +298,8 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
 #pragma unroll
   for (int e = 0; e < V; ++e) {
     mu[e] = mean[c + e];
-    // inference mode (infer_eps >= 0): `mean` and `invstd` are the running mean and the running VARIANCE
-    const float is = infer_eps >= 0.f ? 1.0f / sqrtf(invstd[c + e] + infer_eps) : invstd[c + e];
+    float is = invstd[c + e];
+    if constexpr (INFER) is = 1.0f / sqrtf(is + infer_eps);
     sc[e] = gamma[c + e] * is;
     be[e] = beta[c + e];
   }
@@ -324,6 +326,17 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ x, 
                 // act'(y) of this thread's V outputs, one bit each (see remask_hi), for the pullback
                 if (bits) bits[m * CV + cv] = (unsigned char)b;
               });
+}
+
+#define BN_APPLY_ARGS                                                                                                \
+  const T *__restrict__ x, const T *__restrict__ res, const float *__restrict__ gamma, const float *__restrict__ beta, \
+      const float *__restrict__ mean, const float *__restrict__ invstd, T *__restrict__ y,                            \
+      unsigned char *__restrict__ bits, long long M, int C, int cvb, long long per, int act, float infer_eps
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_apply_kernel(BN_APPLY_ARGS) {
+  bn_apply_body<T, V, false>(x, res, gamma, beta, mean, invstd, y, bits, M, C, cvb, per, act, infer_eps);
+}
+template <typename T, int V> __global__ __launch_bounds__(256) void bn_apply_infer_kernel(BN_APPLY_ARGS) {
+  bn_apply_body<T, V, true>(x, res, gamma, beta, mean, invstd, y, bits, M, C, cvb, per, act, infer_eps);
 }
 
 // dbeta and dgamma are sums of cotangents whose terms largely cancel (the cotangent reaching a
@@ -602,7 +615,7 @@ int bn_inference_fwd(const s4tf_bn_desc& d, const void* x, const void* res, cons
   const int C = d.c;
   const Plan pa = make_plan((size_t)M, C, d.dtype, 2048, UNROLL);
   ProfScope ps(PC_BN_APPLY, st);
-  BN_LAUNCH(bn_apply_kernel, pa, 0, (const T*)x, (const T*)res, gamma, beta, running_mean, running_var, (T*)y,
+  BN_LAUNCH(bn_apply_infer_kernel, pa, 0, (const T*)x, (const T*)res, gamma, beta, running_mean, running_var, (T*)y,
             (unsigned char*)nullptr, M, C, pa.cvb, pa.per, d.act, d.eps);
   return launch_status("bn_inference");
 }
