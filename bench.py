@@ -61,6 +61,31 @@ def conv_flops(net, shapes):
     return out
 
 
+def conv_layerwise_roofline(net, shapes):
+    """Per convolution pass, the time the roofline allows it: max(FLOPs / MFMA peak, minimum bytes / HBM peak)
+    with the minimum bytes |x| + |w| + |y| at storage width (filter gradient: |x| + |dy| + |dw| in fp32), summed
+    over the layers of each class.  Most layers of these nets at their batch sizes are bound by the HBM term."""
+    es = 2 if net["dtype"] == "bf16" else 4
+    peak = PEAK[net["dtype"]] * 1e12
+    out = {"conv_fwd_igemm": 0.0, "conv_dgrad_igemm": 0.0, "conv_wgrad_igemm": 0.0}
+    hbm_bound = 0
+    layers = 0
+    for i, op in enumerate(net["ops"]):
+        if op["kind"] != "conv" or op["groups"] > 1:
+            continue
+        n, h, w, c = shapes[op["in"]]
+        _, p, q, k = shapes[i + 1]
+        f = 2.0 * n * p * q * k * op["r"] * op["s"] * c
+        xb, yb, wn = n * h * w * c * es, n * p * q * k * es, op["r"] * op["s"] * c * k
+        layers += 1
+        hbm_bound += 1 if (xb + yb + wn * es) / (HBM_PEAK_TBPS * 1e12) > f / peak else 0
+        out["conv_fwd_igemm"] += max(f / peak, (xb + yb + wn * es) / (HBM_PEAK_TBPS * 1e12))
+        out["conv_wgrad_igemm"] += max(f / peak, (xb + yb + wn * 4) / (HBM_PEAK_TBPS * 1e12))
+        if op["in"] != 0:
+            out["conv_dgrad_igemm"] += max(f / peak, (xb + yb + wn * es) / (HBM_PEAK_TBPS * 1e12))
+    return {k: v * 1e3 for k, v in out.items()}, hbm_bound, layers
+
+
 def class_bytes(net, shapes, n_params):
     """Algorithmic HBM bytes of one step for the classes that no contraction bounds: every operand a
     kernel class must read or write once, at the storage width (es) of activations; fp32 elsewhere.
@@ -233,6 +258,7 @@ def main():
                    "params": nets.param_count(wl["params"]), "loss_after": m["loss_after"]},
         "roofline": m["roofline"], "cpu_baseline": cpu,
         "mfma_util_convs": m["mfma_util_convs"],
+        "conv_layers_bound_by_hbm": m["conv_layers_bound_by_hbm"],
         "host_enqueue_ms_per_step": m["host_enqueue_ms_per_step"],
         "event_pair_overhead_us": m["event_pair_overhead_us"],
         "kernel_classes": m["kernel_classes"],
@@ -329,6 +355,12 @@ def measure(net, wl, steps, warmup, workload):
         roofline = {"bound": "latency", "kernel": dom, "achieved": None, "peak": None, "unit": None, "frac": None, "traffic": None,
                     "launches_per_step": classes[dom]["launches_per_step"],
                     "avg_launch_ms": classes[dom]["ms_per_step"] / classes[dom]["launches_per_step"]}
+    # each convolution class against the sum of its layers' own rooflines (MFMA or HBM, whichever binds the layer)
+    roof_ms, hbm_layers, conv_layers = conv_layerwise_roofline(net, shapes)
+    for name, ms in roof_ms.items():
+        if name in classes and classes[name]["ms_per_step"] > 0 and ms > 0:
+            classes[name]["layerwise_roofline_ms"] = ms
+            classes[name]["layerwise_roofline_frac"] = ms / classes[name]["ms_per_step"]
     conv_ms = sum(classes[k]["ms_per_step"] for k in ("conv_fwd_igemm", "conv_dgrad_igemm", "conv_wgrad_igemm") if k in classes)
     conv_fl = sum(flops[k] for k in ("conv_fwd_igemm", "conv_dgrad_igemm", "conv_wgrad_igemm"))
     mfma_util = conv_fl / (conv_ms * 1e-3) / 1e12 / PEAK[dtype] if conv_ms else None
@@ -337,6 +369,7 @@ def measure(net, wl, steps, warmup, workload):
     return {"ms_per_step": round(ms_per_step, 4), "images_per_s": round(batch / (ms_per_step * 1e-3), 1),
             "host_enqueue_ms_per_step": round(t_enq / steps * 1e3, 4), "loss_after": round(loss, 5), "roofline": roofline,
             "mfma_util_convs": None if mfma_util is None else round(mfma_util, 4),
+            "conv_layers_bound_by_hbm": "%d of %d" % (hbm_layers, conv_layers),
             "event_pair_overhead_us": round(bracket_ms * 1e3, 3),
             "kernel_classes": {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in sorted(classes.items())}}
 
