@@ -172,3 +172,31 @@ def test_descriptor_calls_reuse_their_plan():
         d, k = B.make_net_desc(nets.lenet5(batch=batch))
         assert B.s4tf_net_param_count(d) == 61720   # 61 706 parameters, each tensor padded to a multiple of 8
     assert B.s4tf_train_step_workspace_bytes(desc) == want
+
+
+def test_new_entry_points_reject_bad_arguments_on_the_host():
+    L = B.lib()
+    g = B.GatherDesc(10, 4, 3, B.S4TF_F32)
+    assert L.s4tf_gather_rows_fwd(ctypes.byref(g), None, 16, 16, None) == -1
+    assert L.s4tf_gather_rows_vjp(ctypes.byref(g), 16, 16, 8, None) == -7              # misaligned dx
+    assert L.s4tf_gather_rows_fwd(ctypes.byref(B.GatherDesc(0, 4, 3, B.S4TF_F32)), 16, 16, 16, None) == -2
+    assert L.s4tf_gather_rows_fwd(ctypes.byref(B.GatherDesc(10, 4, 0, B.S4TF_F32)), None, None, None, None) == 0   # nothing to gather
+    assert L.s4tf_gather_rows_fwd(ctypes.byref(B.GatherDesc(10, 4, 3, 9)), 16, 16, 16, None) == -3
+    assert L.s4tf_gather_rows_fwd(ctypes.byref(B.GatherDesc(1 << 20, 1 << 12, 3, B.S4TF_F32)), 16, 16, 16, None) == -2  # 2^32 elements
+    bn = B.BnDesc(2, 4, 4, 8, 1e-5, 1, B.S4TF_F32, 0, 0)
+    assert L.s4tf_bn_inference_fwd(ctypes.byref(bn), 16, None, 16, 16, None, 16, 16, None) == -1      # running_mean missing
+    assert L.s4tf_bn_update_running(0, 10, 0.1, 1e-5, 16, 16, 16, 16, None) == -2
+    assert L.s4tf_bn_update_running(8, 10, 1.5, 1e-5, 16, 16, 16, 16, None) == -2                     # momentum out of [0, 1]
+    cd = B.ConvDesc(1, 8, 8, 4, 4, 3, 3, 1, 1, 1, B.S4TF_F32, 0, 0)
+    assert L.s4tf_bn_fold_into_conv(ctypes.byref(cd), 16, None, 16, 16, 16, 16, -1.0, 16, 16, None) == -2   # eps < 0
+    assert L.s4tf_bn_fold_into_conv(ctypes.byref(cd), 16, None, 16, 16, 16, 16, 1e-5, None, 16, None) == -1
+    assert L.s4tf_round_to_bf16(0, None, None, None) == 0
+    assert L.s4tf_round_to_bf16(4, None, 16, None) == -1
+    # tensors beyond the kernels' 32-bit element indices are refused, not wrapped
+    huge = B.ConvDesc(1 << 10, 1 << 10, 1 << 10, 4, 4, 1, 1, 1, 0, 1, B.S4TF_F32, 0, 0)
+    assert L.s4tf_conv2d_fwd(ctypes.byref(huge), 16, 16, None, 16, None, 0, None) == -2 and "2^31" in B.last_error()
+    # the allocation-free BatchNorm forward: capacity query needs no device, the refusal comes before any launch
+    big = B.BnDesc(64, 56, 56, 512, 1e-5, 1, B.S4TF_BF16, 0, 0)
+    cap, needed = B.s4tf_bn_relu_fwd_static_limit(big)
+    assert cap == 1 << 20 and needed > cap
+    assert L.s4tf_bn_relu_fwd_static(ctypes.byref(big), 16, None, 16, 16, 16, 16, 16, None) == -5

@@ -836,3 +836,41 @@ def test_bn_inference_running_statistics_and_folding(shape, act, use_bias, bf16)
     if not bf16:   # and the folded convolution is the unfolded pair (fp32: no intermediate rounding in between)
         pair = orc.bn_inference_fwd(orc.conv2d_fwd(x, wt, bias, stride, pad), None, gamma, beta, rm_h, rv_h, eps, act)
         check("folded conv = conv then BatchNorm", yf, pair, False, 2e-5)
+
+
+def test_two_host_threads_step_on_one_device_like_one_after_the_other():
+    """Two-stream steps on one device take a lock while they enqueue, so host threads that step different nets at
+    the same time (each on a stream of its own, with its own workspace) do not interleave their use of the
+    library's second stream and events: every loss equals that of the same steps made one after the other."""
+    import threading
+    cases = [nets.resnet50(batch=4, hw=64, stages=(2, 1, 1, 1), classes=24, dtype="f32"),
+             nets.mobilenetv2(batch=4, hw=64, classes=16)]
+    wls = [nets.make_workload(n, perturb=True) for n in cases]
+
+    def run(net, wl, stream, out):
+        st = B.TrainState(net, wl["params"], DEV)
+        xd, ld = st.upload_batch(wl["x"], wl["labels"])
+        torch.cuda.synchronize()
+        losses = []
+        for _ in range(6):
+            st.step(xd, ld, stream=stream)
+            stream.synchronize()
+            losses.append(float(st.loss[0].item()))
+        out.append((losses, st.results()))
+
+    want = []
+    for net, wl in zip(cases, wls):
+        run(net, wl, torch.cuda.Stream(), want)
+    got = [[], []]
+    threads = [threading.Thread(target=run, args=(net, wl, torch.cuda.Stream(), got[i]))
+               for i, (net, wl) in enumerate(zip(cases, wls))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    for (wl_, wr), g in zip(want, got):
+        gl, gr = g[0]
+        assert gl == wl_, (gl, wl_)
+        for pa, pb in zip(gr["params"], wr["params"]):
+            for x, y in zip(pa, pb):
+                np.testing.assert_array_equal(x, y)
