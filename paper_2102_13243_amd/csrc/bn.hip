@@ -228,42 +228,47 @@ __global__ __launch_bounds__(FIN_THREADS) void bn_stats_finalize_kernel(const T*
 // Statistics from the partial sums a convolution left behind: run i covers rows [i*rows, min(M, (i+1)*rows))
 // and holds per channel s_i = sum x and q_i = sum (x - s_i/n_i)^2.  With S = sum s_i:
 //   mean = S/M,   M*var = sum q_i + sum s_i^2/n_i - S^2/M      (all in double)
-// There are thousands of runs and few channels, so a block takes only CPB channels and spreads the runs
-// over 1024/CPB lanes; lanes are added by a shuffle butterfly, the 16 wavefronts through LDS, in a
-// fixed order.
+// The table is laid out channel by channel, part[(which*C + c)*runs + i]: the runs of a channel are adjacent,
+// so the 1024/CPB lanes that a block gives each of its CPB channels read whole cache lines (run-major, the
+// table of a 64-channel layer with thousands of runs cost every block a fetch of every line: 31 us for the
+// first layer of a ResNet-50 at batch 64, 10 us for each 56x56 layer).  The lanes of a wavefront are added by
+// a shuffle butterfly, the wavefronts of a channel through LDS, in a fixed order.
 template <int CPB>
 __global__ __launch_bounds__(1024) void bn_stats_from_runs_kernel(const float* __restrict__ part, int runs, int rows,
                                                                   long long M, int C, float eps, float* __restrict__ mean,
                                                                   float* __restrict__ invstd) {
-  constexpr int ZL = 1024 / CPB;
-  __shared__ double sh[16][3][CPB];
-  const int cl = threadIdx.x % CPB, c = xcd_channel_block() * CPB + cl, zl = threadIdx.x / CPB;
+  constexpr int ZL = 1024 / CPB, WPC = ZL / 64;  // lanes and wavefronts per channel
+  static_assert(ZL % 64 == 0, "a wavefront serves one channel");
+  __shared__ double sh[16][3];
+  const int cl = threadIdx.x / ZL, zl = threadIdx.x % ZL, c = xcd_channel_block() * CPB + cl;
   const double inv_rows = 1.0 / (double)rows;
   const double inv_last = 1.0 / (double)(M - (long long)(runs - 1) * rows);
   double v[3] = {0.0, 0.0, 0.0};
   if (c < C) {
+    const float* __restrict__ srow = part + (long long)c * runs;
+    const float* __restrict__ qrow = part + ((long long)C + c) * runs;
 #pragma unroll 4
     for (int i = zl; i < runs; i += ZL) {
-      const double s = (double)part[((long long)i * 2) * C + c];
-      const double q = (double)part[((long long)i * 2 + 1) * C + c];
+      const double s = (double)srow[i];
+      const double q = (double)qrow[i];
       v[0] += s;
       v[1] += q;
       v[2] += s * s * (i == runs - 1 ? inv_last : inv_rows);
     }
   }
-  for (int off = CPB; off < 64; off <<= 1) {
+  for (int off = 1; off < 64; off <<= 1) {
 #pragma unroll
     for (int e = 0; e < 3; ++e) v[e] += __shfl_xor(v[e], off, 64);
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (lane < CPB) {
+  if (lane == 0) {
 #pragma unroll
-    for (int e = 0; e < 3; ++e) sh[wave][e][cl] = v[e];
+    for (int e = 0; e < 3; ++e) sh[wave][e] = v[e];
   }
   __syncthreads();
-  if (threadIdx.x >= CPB || c >= C) return;
+  if (zl != 0 || c >= C) return;
   double S = 0.0, Q = 0.0, W = 0.0;
-  for (int w = 0; w < 16; ++w) { S += sh[w][0][cl]; Q += sh[w][1][cl]; W += sh[w][2][cl]; }
+  for (int w = cl * WPC; w < (cl + 1) * WPC; ++w) { S += sh[w][0]; Q += sh[w][1]; W += sh[w][2]; }
   double var = (Q + W - S * S / (double)M) / (double)M;
   if (var < 0.0) var = 0.0;
   mean[c] = (float)(S / (double)M);
@@ -586,11 +591,15 @@ int bn_fwd(const s4tf_bn_desc& d, const void* x, const void* res, const float* g
   if (stats_part && stats_rows > 0) {
     ProfScope ps(PC_BN_STATS, st);
     const int runs = (int)((M + stats_rows - 1) / stats_rows);
-    if (C >= 256)
+    // lanes per channel by the length of its row of the table: 128 up to 512 runs, 512 up to 2048, else 1024
+    if (runs <= 512)
       hipLaunchKernelGGL(bn_stats_from_runs_kernel<8>, dim3((C + 7) / 8), dim3(1024), 0, st, stats_part, runs, stats_rows, M, C,
                          d.eps, mean, invstd);
-    else
+    else if (runs <= 2048)
       hipLaunchKernelGGL(bn_stats_from_runs_kernel<2>, dim3((C + 1) / 2), dim3(1024), 0, st, stats_part, runs, stats_rows, M, C,
+                         d.eps, mean, invstd);
+    else
+      hipLaunchKernelGGL(bn_stats_from_runs_kernel<1>, dim3(C), dim3(1024), 0, st, stats_part, runs, stats_rows, M, C,
                          d.eps, mean, invstd);
     if ((rc = launch_status("bn_stats_from_runs")) != S4TF_OK) return rc;
   } else {

@@ -591,7 +591,8 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
       for (int i = 0; i < FM; ++i) {
         const int rbase = m0 + arow + i * 32;
         const int cnt = min(max(a.Mg - rbase, 0), 32);
-        float* part = a.stats + (long long)(rbase / 32) * 2 * a.Ng;
+        const long long runs = (a.Mg + 31) / 32;  // the table is channel-major: [sum | squared deviations][column][run]
+        float* part = a.stats + rbase / 32;
         const float inv_cnt = cnt > 0 ? 1.f / (float)cnt : 0.f;
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
@@ -610,8 +611,8 @@ __global__ __launch_bounds__(NT) void igemm_kernel(const Args a) {
           const float m2 = fmaxf(q1 - s1 * s1 * inv_cnt, 0.f);
           const int col = n0 + brow + j * 32 + (lane & 31);
           if (lane < 32 && col < a.Ng && cnt > 0) {  // a run with no valid row has no slot
-            part[col] = fmaf((float)cnt, pivot, s1);
-            part[a.Ng + col] = m2;
+            part[col * runs] = fmaf((float)cnt, pivot, s1);
+            part[(a.Ng + col) * runs] = m2;
           }
         }
       }

@@ -656,15 +656,17 @@ __global__ __launch_bounds__(NT, STAGES == 1 ? 4 : STAGES >= 4 ? 1 : 2) void ige
         const float fa = (float)wcnt, fb = (float)nb;
         const float inv_a = wcnt > 0 ? 1.f / fa : 0.f, inv_b = nb > 0 ? 1.f / fb : 0.f;
         const float wgt = nb > 0 ? fa * fb / (fa + fb) : 0.f;
-        float* part = a.stats + (long long)(m0 / BM) * 2 * a.Ng;
+        // the table is channel-major: [sum | squared deviations][column][run]
+        const long long runs = (a.Mg + BM - 1) / BM;
+        float* part = a.stats + m0 / BM;
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
           const float sb = ex[(j * 32 + lane) * 2], qb = ex[(j * 32 + lane) * 2 + 1];
           const float dm = ssum[j] * inv_a - sb * inv_b;
           const int col = n0 + brow + j * 32 + lane;
           if (col < a.Ng && cnt > 0) {  // a run with no valid row has no slot
-            part[col] = ssum[j] + sb;
-            part[a.Ng + col] = sqsum[j] + qb + dm * dm * wgt;
+            part[col * runs] = ssum[j] + sb;
+            part[(a.Ng + col) * runs] = sqsum[j] + qb + dm * dm * wgt;
           }
         }
       }

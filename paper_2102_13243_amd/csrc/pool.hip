@@ -367,6 +367,54 @@ __global__ void unpad_axis_kernel(const float* __restrict__ src, float* __restri
   }
 }
 
+// ---- a stride-2 first layer as a stride-1 layer over 2x2 pixel blocks ---------------------------------
+// A filter of odd size (R,S) with stride 2 over a batch of C <= 4 channels, padded by `pad` with H + 2 pad and
+// W + 2 pad even, is the same sum as a filter of size ((R+1)/2, (S+1)/2) with stride 1 and no padding over the
+// folded batch xf[n][hf][wf][(eh*2 + ew)*4 + c] = xpad[n][2 hf + eh][2 wf + ew][c] (xpad: the batch with its
+// zero border; channels c >= C are zero), with wf[r'][s'][(eh*2 + ew)*4 + c][k] = w[2r' + eh][2s' + ew][c][k]
+// (zero where 2r' + eh = R or 2s' + ew = S).  For a 7x7 filter on 3 channels the reduction axis is 4*4*16 = 256
+// long instead of 7*7*8 = 392 (channels padded to the 16-byte loaders' 8), and every operand chunk holds two pixels.
+__global__ __launch_bounds__(256) void fold2_pixels_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int N, int H,
+                                                           int W, int C, int pad, int Hf, int Wf) {
+  const long long total = (long long)N * Hf * Wf * 2;  // one 16-byte chunk (eh fixed, both ew) per thread
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int eh = (int)(i & 1);
+    const long long pix = i >> 1;
+    const int wf = (int)(pix % Wf);
+    const long long t = pix / Wf;
+    const int hf = (int)(t % Hf), n = (int)(t / Hf);
+    const int h = 2 * hf + eh - pad;
+    uint32_t v[8];
+#pragma unroll
+    for (int ew = 0; ew < 2; ++ew) {
+      const int w = 2 * wf + ew - pad;
+      const bool in = h >= 0 && h < H && w >= 0 && w < W;
+      const long long base = (((long long)n * H + h) * W + w) * C;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) v[ew * 4 + c] = (in && c < C) ? (uint32_t)src[base + c] : 0u;
+    }
+    uint4 o;
+    o.x = v[0] | (v[1] << 16); o.y = v[2] | (v[3] << 16); o.z = v[4] | (v[5] << 16); o.w = v[6] | (v[7] << 16);
+    reinterpret_cast<uint4*>(dst)[i] = o;
+  }
+}
+__global__ void fold2_filter_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wf, int R, int S, int C, int K) {
+  const int Sf = (S + 1) / 2, total = ((R + 1) / 2) * Sf * 16 * K;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    const int k = i % K, t = i / K, cf = t % 16, tap = t / 16;
+    const int r = 2 * (tap / Sf) + (cf >> 3), s = 2 * (tap % Sf) + ((cf >> 2) & 1), c = cf & 3;
+    wf[i] = (r < R && s < S && c < C) ? w[((r * S + s) * C + c) * K + k] : (bf16_t)0;
+  }
+}
+// the filter gradient back: dw[r][s][c][k] = dwf[r/2][s/2][((r&1)*2 + (s&1))*4 + c][k]
+__global__ void unfold2_filter_grad_kernel(const float* __restrict__ dwf, float* __restrict__ dw, int R, int S, int C, int K) {
+  const int Sf = (S + 1) / 2, total = R * S * C * K;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    const int k = i % K, t = i / K, c = t % C, tap = t / C, r = tap / S, s = tap % S;
+    dw[i] = dwf[(((r >> 1) * Sf + (s >> 1)) * 16 + ((r & 1) * 2 + (s & 1)) * 4 + c) * K + k];
+  }
+}
+
 // ---- SGD with momentum ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ param, float* __restrict__ vel,
                                                   const float* __restrict__ grad, bf16_t* __restrict__ lowp,
@@ -585,6 +633,25 @@ int unpad_channels_f32(const float* src, float* dst, long long outer, int C, int
   ProfScope ps(PC_ELEMENTWISE, st);
   hipLaunchKernelGGL(unpad_axis_kernel, dim3(blocks_for(outer * C * inner)), dim3(256), 0, st, src, dst, outer, C, Cp, inner);
   return launch_status("unpad_channels");
+}
+
+int fold2_pixels(const void* x, void* xf, int N, int H, int W, int C, int pad, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  const int Hf = (H + 2 * pad) / 2, Wf = (W + 2 * pad) / 2;
+  hipLaunchKernelGGL(fold2_pixels_kernel, dim3(blocks_for((long long)N * Hf * Wf * 2)), dim3(256), 0, st, (const bf16_t*)x,
+                     (bf16_t*)xf, N, H, W, C, pad, Hf, Wf);
+  return launch_status("fold2_pixels");
+}
+int fold2_filter(const void* w, void* wf, int R, int S, int C, int K, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  hipLaunchKernelGGL(fold2_filter_kernel, dim3(blocks_for((long long)((R + 1) / 2) * ((S + 1) / 2) * 16 * K)), dim3(256), 0, st,
+                     (const bf16_t*)w, (bf16_t*)wf, R, S, C, K);
+  return launch_status("fold2_filter");
+}
+int unfold2_filter_grad(const float* dwf, float* dw, int R, int S, int C, int K, hipStream_t st) {
+  ProfScope ps(PC_ELEMENTWISE, st);
+  hipLaunchKernelGGL(unfold2_filter_grad_kernel, dim3(blocks_for((long long)R * S * C * K)), dim3(256), 0, st, dwf, dw, R, S, C, K);
+  return launch_status("unfold2_filter_grad");
 }
 
 int sgd(size_t count, float* param, float* vel, const float* grad, void* lowp, float lr, float mu,

@@ -86,8 +86,8 @@ inline ConvGeom conv_geom(const s4tf_conv_desc& d) {
 // dense (groups == 1) convolution as implicit GEMM on MFMA
 // stats_part (optional, with bias == NULL and act == none): the kernel also writes, for every run of
 // *stats_rows consecutive output rows (pixels) r and every channel, the sum of the stored outputs and the
-// sum of their squared deviations from that run's own mean: stats_part[(r*2 + 0)*K + k], [(r*2 + 1)*K + k];
-// ceil(N*P*Q / *stats_rows) runs.  *stats_rows comes back 0 when the kernel that ran does not do this.
+// sum of their squared deviations from that run's own mean, channel-major: stats_part[k*runs + r] and
+// stats_part[(K + k)*runs + r] with runs = ceil(N*P*Q / *stats_rows).  *stats_rows comes back 0 when the kernel that ran does not do this.
 int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, int act,
               void* y, hipStream_t st, float* stats_part = nullptr, int* stats_rows = nullptr);
 size_t igemm_fwd_stats_bytes(const ConvGeom& g);  // upper bound on the size of stats_part
@@ -122,6 +122,11 @@ int colsum(int dtype, const void* a, size_t rows, int cols, float* out, hipStrea
 // zero-pad / strip the channel axis of [outer][C][inner] tensors
 int pad_channels(int dtype, const void* src, void* dst, long long outer, int C, int Cp, int inner, hipStream_t st);
 int unpad_channels_f32(const float* src, float* dst, long long outer, int C, int Cp, int inner, hipStream_t st);
+// bf16 stride-2 first layer as a stride-1 layer over 2x2 pixel blocks (see pool.hip): the folded batch
+// (N, (H+2pad)/2, (W+2pad)/2, 16), the folded filter ((R+1)/2, (S+1)/2, 16, K), and the filter gradient back
+int fold2_pixels(const void* x, void* xf, int N, int H, int W, int C, int pad, hipStream_t st);
+int fold2_filter(const void* w, void* wf, int R, int S, int C, int K, hipStream_t st);
+int unfold2_filter_grad(const float* dwf, float* dw, int R, int S, int C, int K, hipStream_t st);
 
 // batch norm
 size_t bn_workspace(size_t M, int C);

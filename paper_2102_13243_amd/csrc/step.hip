@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "s4tf_internal.h"
+#include "igemm_args.h"
 
 namespace s4tf {
 namespace {
@@ -83,6 +84,10 @@ struct NetPlan {
   // a convolution on the batch itself whose channel count is not a multiple of 8 (bf16) or 4 (fp32) runs
   // on zero-padded copies of the batch and of its filter (pad_c channels)
   std::vector<int> pad_c;
+  // ... or, bf16 with stride 2, an odd filter and at most 4 channels, as a stride-1 convolution over 2x2 pixel
+  // blocks of 16 channels (fold[op] = 1, pad_c = 16; fold2_pixels and its companions): a shorter reduction axis
+  // than channel padding gives, and every 16-byte operand chunk holds two pixels
+  std::vector<char> fold;
   std::vector<size_t> xpad_off, wpad_off, dwpad_off;
   size_t param_count;
   size_t scratch_off, scratch_bytes, total_bytes;
@@ -103,6 +108,21 @@ struct NetPlan {
 
 bool dtype_ok(int t) { return t == S4TF_F32 || t == S4TF_BF16; }
 
+// The stride-1 geometry over 2x2 pixel blocks that stands for a stride-2 convolution of geometry g (see fold2_pixels)
+ConvGeom folded_geom(const ConvGeom& g, int pad) {
+  ConvGeom f = g;
+  f.H = (g.H + 2 * pad) / 2; f.W = (g.W + 2 * pad) / 2; f.C = 16;
+  f.R = (g.R + 1) / 2; f.S = (g.S + 1) / 2; f.stride = 1; f.pad = 0;
+  f.P = f.H - f.R + 1; f.Q = f.W - f.S + 1;
+  return f;
+}
+s4tf_conv_desc folded_desc(const s4tf_conv_desc& d) {
+  s4tf_conv_desc f = d;
+  f.h = (d.h + 2 * d.pad) / 2; f.w = (d.w + 2 * d.pad) / 2; f.c = 16;
+  f.r = (d.r + 1) / 2; f.s = (d.s + 1) / 2; f.stride = 1; f.pad = 0;
+  return f;
+}
+
 int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
   if (!net) return fail(S4TF_ERR_NULL, "net descriptor is NULL");
   if (!net->ops || net->n_ops <= 0) return fail(S4TF_ERR_NULL, "net has no ops");
@@ -117,6 +137,7 @@ int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
   pl.mask_off.assign(nops, 0);
   pl.defer_conv.assign(nops, -1);
   pl.pad_c.assign(nops, 0);
+  pl.fold.assign(nops, 0);
   pl.xpad_off.assign(nops, 0);
   pl.wpad_off.assign(nops, 0);
   pl.dwpad_off.assign(nops, 0);
@@ -150,6 +171,15 @@ int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
             (net->dtype == S4TF_BF16 || (op.k % 4 == 0 && (long long)g.N * g.P * g.Q >= 32768))) {
           pl.pad_c[i] = (int)align_up((size_t)in.c, vecw);
           g.C = pl.pad_c[i];
+          if (net->dtype == S4TF_BF16 && op.stride == 2 && in.c <= 4 && op.r >= 3 && op.s >= 3 && (op.r & 1) && (op.s & 1) &&
+              (in.h + 2 * op.pad) % 2 == 0 && (in.w + 2 * op.pad) % 2 == 0 && op.k % 8 == 0) {
+            const ConvGeom gf = folded_geom(g, op.pad);
+            if (gf.P == g.P && gf.Q == g.Q && igemm_dma_geom_ok(PASS_FWD, gf) && igemm_dma_geom_ok(PASS_WGRAD, gf)) {
+              pl.fold[i] = 1;
+              pl.pad_c[i] = 16;
+              g = gf;
+            }
+          }
         }
         size_t ws = op.groups == 1 ? igemm_wgrad_workspace(g, net->dtype) : dwconv_wgrad_workspace(g);
         if (ws > wscratch) wscratch = ws;
@@ -252,9 +282,12 @@ int plan_net(const s4tf_net_desc* net, NetPlan& pl) {
     if (pl.pad_c[i]) {
       const s4tf_op& op = net->ops[i];
       const TensorPlan& in = pl.t[op.in];
-      pl.xpad_off[i] = off; off += align_up((size_t)in.n * in.h * in.w * pl.pad_c[i] * es, 256);
-      pl.wpad_off[i] = off; off += align_up((size_t)op.r * op.s * pl.pad_c[i] * op.k * es, 256);
-      pl.dwpad_off[i] = off; off += align_up((size_t)op.r * op.s * pl.pad_c[i] * op.k * sizeof(float), 256);
+      // folded: (h + 2 pad)/2 x (w + 2 pad)/2 pixels of 16 channels, (r+1)/2 x (s+1)/2 taps
+      const size_t px = pl.fold[i] ? (size_t)in.n * ((in.h + 2 * op.pad) / 2) * ((in.w + 2 * op.pad) / 2) : (size_t)in.n * in.h * in.w;
+      const size_t taps = pl.fold[i] ? (size_t)((op.r + 1) / 2) * ((op.s + 1) / 2) : (size_t)op.r * op.s;
+      pl.xpad_off[i] = off; off += align_up(px * pl.pad_c[i] * es, 256);
+      pl.wpad_off[i] = off; off += align_up(taps * pl.pad_c[i] * op.k * es, 256);
+      pl.dwpad_off[i] = off; off += align_up(taps * pl.pad_c[i] * op.k * sizeof(float), 256);
     }
   double conv_flops = 0.0;  // forward pass
   for (int i = 0; i < nops; ++i)
@@ -676,6 +709,12 @@ int run_step(const s4tf_net& N, s4tf_params* params, const s4tf_batch* batch, fl
         const float* bias = op.has_bias ? params->master + pl.poff[2 * i + 1] : nullptr;
         float* sp = c.a ? static_cast<float*>(scr) : nullptr;
         int* sr = c.a ? &stats_rows[c.scr] : nullptr;
+        if (pl.fold[i]) {
+          CHECK(fold2_pixels(act_ptr(op.in), ws + pl.xpad_off[i], in.n, in.h, in.w, in.c, op.pad, s));
+          CHECK(fold2_filter(conv_w(i), ws + pl.wpad_off[i], op.r, op.s, in.c, op.k, s));
+          CHECK(conv_fwd_impl(folded_desc(d), ws + pl.xpad_off[i], ws + pl.wpad_off[i], bias, out_ptr(i + 1), s, sp, sr));
+          break;
+        }
         if (pl.pad_c[i]) {  // zero-padded channels contribute nothing: same result, 16-byte loaders
           CHECK(pad_channels(dt, act_ptr(op.in), ws + pl.xpad_off[i], (long long)in.n * in.h * in.w, in.c, pl.pad_c[i], 1, s));
           CHECK(pad_channels(dt, conv_w(i), ws + pl.wpad_off[i], (long long)op.r * op.s, in.c, pl.pad_c[i], op.k, s));
@@ -737,6 +776,12 @@ int run_step(const s4tf_net& N, s4tf_params* params, const s4tf_batch* batch, fl
         s4tf_conv_desc d = conv_desc(i, 0);
         void* dyj = grad_ptr(i + 1);
         float* dbias = cv.has_bias ? params->grad + pl.poff[2 * i + 1] : nullptr;
+        if (pl.fold[i]) {  // on the folded batch the forward pass left; the gradient of the folded filter is unfolded
+          float* dwp = reinterpret_cast<float*>(ws + pl.dwpad_off[i]);
+          CHECK(conv_param_grads_impl(folded_desc(d), ws + pl.xpad_off[i], dyj, dwp, dbias, wscratch, pl.wscratch_bytes, s));
+          CHECK(unfold2_filter_grad(dwp, params->grad + pl.poff[2 * i], cv.r, cv.s, cin.c, cv.k, s));
+          break;
+        }
         if (pl.pad_c[i]) {  // the batch has no cotangent; the filter gradient of the padded channels is dropped
           d.c = pl.pad_c[i];
           float* dwp = reinterpret_cast<float*>(ws + pl.dwpad_off[i]);

@@ -490,6 +490,31 @@ def test_train_step_small_bf16(name, kw):
     assert abs(gpu["loss"] - ref["loss"]) <= 5e-3 * abs(ref["loss"]), (gpu["loss"], ref["loss"])
 
 
+def _first_layer_variant(which):
+    if which == "odd_image":        # 63 + 2*3 is odd: the first layer runs on channel-padded copies, not folded
+        return nets.resnet50(batch=4, hw=63, stages=(1, 1, 1, 1), classes=12)
+    net = nets.resnet50(batch=4, hw=64, stages=(1, 1, 1, 1), classes=12)
+    if which == "non_square_filter":   # 5x3 filter, stride 2, padding 1: folded to 3x2 taps of 16 channels, 31x32 outputs
+        net["ops"][0].update(r=5, s=3, pad=1)
+    elif which == "wide_filter":       # 9x9, padding 4: 5x5 folded taps
+        net["ops"][0].update(r=9, s=9, pad=4)
+    return net
+
+
+@pytest.mark.parametrize("which", ["odd_image", "non_square_filter", "wide_filter"])
+def test_train_step_bf16_first_layer_variants(which):
+    """The bf16 first layer (3 channels, stride 2) runs as a stride-1 convolution over 2x2 pixel blocks when the
+    padded image has even sides, else on copies padded to 8 channels: both ways, and filters that fold unevenly,
+    every op checked locally and the loss to the workload's 5e-3."""
+    net = dict(_first_layer_variant(which), dtype="bf16")
+    wl = nets.make_workload(net, perturb=True)
+    wl["x"] = nets.to_bf16_grid(wl["x"])
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+    gpu = run_gpu_steps(net, wl, local=True)
+    say("resnet50 bf16, first layer %s: loss gpu %.7g oracle %.7g" % (which, gpu["loss"], ref["loss"]))
+    assert abs(gpu["loss"] - ref["loss"]) <= 5e-3 * abs(ref["loss"]), (gpu["loss"], ref["loss"])
+
+
 def test_train_step_is_deterministic_and_in_place_equals_functional():
     net = nets.resnet56(batch=8, blocks_per_stage=1, hw=16)
     wl = kink_free_workload(net, False)
