@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libs4tf.so")
-SOURCES = ["igemm.hip", "igemm_dma.hip", "dwconv.hip", "bn.hip", "pool.hip", "head.hip", "api.hip", "step.hip"]
+SOURCES = ["igemm.hip", "igemm_dma.hip", "patchconv.hip", "dwconv.hip", "bn.hip", "pool.hip", "head.hip", "api.hip", "step.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

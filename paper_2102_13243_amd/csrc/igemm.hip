@@ -876,17 +876,18 @@ int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const 
     }
     return launch<bf16_t, PASS_FWD>(a, 1, st);
   }
+  const bool with_stats = stats_part && stats_rows && !bias && act == S4TF_ACT_NONE;
+  if (patchconv_fwd_ok(g, dtype) && aligned16(x) && aligned16(w) && aligned16(y))  // few channels, 3x3: out of an LDS patch
+    return patchconv_fwd(g, x, w, bias, act, y, with_stats ? stats_part : nullptr, with_stats ? stats_rows : nullptr, st);
+  if (with_stats) *stats_rows = 32;
   fill_tiles_f32(a, false);
-  if (stats_part && stats_rows && !bias && act == S4TF_ACT_NONE) {
-    a.stats = stats_part;
-    *stats_rows = 32;
-  }
+  if (with_stats) a.stats = stats_part;
   return launch<float, PASS_FWD>(a, 1, st);
 }
 
-size_t igemm_fwd_stats_bytes(const ConvGeom& g) {  // the finest runs any tile uses are 32 rows
+size_t igemm_fwd_stats_bytes(const ConvGeom& g) {  // the finest runs any kernel uses are 16 rows
   const size_t M = (size_t)g.N * g.P * g.Q;
-  return (M + 31) / 32 * 2 * g.K * sizeof(float);
+  return (M + 15) / 16 * 2 * g.K * sizeof(float);
 }
 
 // Can igemm_dgrad add a (masked) tensor other than the old contents of dx?  Only the stride-1 case of the
@@ -956,6 +957,8 @@ int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, voi
     fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
     return launch<bf16_t, PASS_DGRAD>(a, 1, st);
   }
+  if (patchconv_dgrad_ok(g, dtype) && aligned16(dy) && aligned16(w) && aligned16(dx))
+    return patchconv_dgrad(g, dy, w, dx, accumulate, st);
   fill_tiles_f32(a, false);
   return launch<float, PASS_DGRAD>(a, 1, st);
 }

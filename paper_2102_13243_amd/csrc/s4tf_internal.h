@@ -91,6 +91,13 @@ inline ConvGeom conv_geom(const s4tf_conv_desc& d) {
 int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, int act,
               void* y, hipStream_t st, float* stats_part = nullptr, int* stats_rows = nullptr);
 size_t igemm_fwd_stats_bytes(const ConvGeom& g);  // upper bound on the size of stats_part
+// fp32 3x3 / stride 1 / padding 1 layers of 16 or 32 channels (and 4 -> 16) whose images are 16 or 32 wide: a
+// kernel that multiplies out of an LDS patch (patchconv.hip); igemm_fwd and igemm_dgrad hand such shapes over
+bool patchconv_fwd_ok(const ConvGeom& g, int dtype);
+bool patchconv_dgrad_ok(const ConvGeom& g, int dtype);
+int patchconv_fwd(const ConvGeom& g, const void* x, const void* w, const float* bias, int act, void* y, float* stats,
+                  int* stats_rows, hipStream_t st);
+int patchconv_dgrad(const ConvGeom& g, const void* dy, const void* w, void* dx, int accumulate, hipStream_t st);
 // acc_src (optional; only where igemm_dgrad_adds_other says so): the result is dgrad + acc_src instead of
 // dgrad (+ old dx); acc_bits (optional): activation bits as bn_fwd leaves them, one per element of acc_src,
 // elements whose bit is clear add nothing.

@@ -161,6 +161,10 @@ CONV_SHAPES = [
     (2, 13, 12, 64, 64, 3, 1, 1, 1),  # 3x1, fast path
     (2, 14, 15, 64, 128, 5, 2, 2, 3), # 5x3 with stride 2: parity classes with different tap counts per axis
     (2, 10, 11, 3, 8, 3, 1, 1, 5),    # 3x5, element-wise loader
+    (3, 32, 32, 16, 16, 3, 1, 1),     # fp32: few channels, 3x3: the kernel that multiplies out of an LDS patch (4 rows a tile)
+    (2, 16, 16, 32, 32, 3, 1, 1),     # ... 32 channels, 8 rows a tile, two tiles an image
+    (5, 8, 32, 16, 16, 3, 1, 1),      # ... images that are not square, an odd number of them
+    (2, 16, 16, 4, 16, 3, 1, 1),      # ... a first layer padded to 4 channels (forward there; its pullbacks elsewhere)
 ]
 
 
