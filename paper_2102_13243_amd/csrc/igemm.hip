@@ -885,9 +885,9 @@ int igemm_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const 
   return launch<float, PASS_FWD>(a, 1, st);
 }
 
-size_t igemm_fwd_stats_bytes(const ConvGeom& g) {  // the finest runs any kernel uses are 16 rows
+size_t igemm_fwd_stats_bytes(const ConvGeom& g) {  // the finest runs any kernel uses are 32 rows
   const size_t M = (size_t)g.N * g.P * g.Q;
-  return (M + 15) / 16 * 2 * g.K * sizeof(float);
+  return (M + 31) / 32 * 2 * g.K * sizeof(float);
 }
 
 // Can igemm_dgrad add a (masked) tensor other than the old contents of dx?  Only the stride-1 case of the
@@ -965,7 +965,8 @@ int igemm_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, voi
 
 size_t igemm_wgrad_workspace(const ConvGeom& g, int dtype) {
   int splits, per;
-  wgrad_split(g, dtype, splits, per);
+  if (patchconv_wgrad_ok(g, dtype)) splits = patchconv_wgrad_splits(g);
+  else wgrad_split(g, dtype, splits, per);
   if (splits <= 1) return 0;
   return (size_t)splits * g.R * g.S * g.C * g.K * sizeof(float);
 }
@@ -977,18 +978,24 @@ int igemm_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, flo
   a.Mg = g.R * g.S * g.C; a.Ng = g.K; a.Kg = g.N * g.P * g.Q;
   a.simple = (g.R == 1 && g.S == 1 && g.stride == 1 && g.pad == 0);
   fill_sizes(a, PASS_WGRAD, dtype);
-  int splits, per;
-  wgrad_split(g, dtype, splits, per);
+  // few channels, 3x3, small images: out of an LDS patch
+  const bool patch = patchconv_wgrad_ok(g, dtype) && aligned16(x) && aligned16(dy) && aligned16(dw) && aligned16(ws);
+  int splits, per = 0;
+  if (patch) splits = patchconv_wgrad_splits(g);
+  else wgrad_split(g, dtype, splits, per);
   const long long n = (long long)a.Mg * a.Ng;
   if (splits > 1 && ws_bytes < (size_t)splits * n * sizeof(float))
     return fail(S4TF_ERR_WORKSPACE, "wgrad needs %zu workspace bytes, got %zu", (size_t)splits * n * sizeof(float), ws_bytes);
-  if (dtype == S4TF_BF16) fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
-  else fill_tiles_f32(a, true);
-  a.nk_per_split = per;
-  a.split_stride = n;
-  a.out = splits > 1 ? ws : (void*)dw;
   int rc;
-  {
+  if (patch) {
+    ProfScope ps(PC_CONV_WGRAD, st);
+    rc = patchconv_wgrad(g, x, dy, splits > 1 ? static_cast<float*>(ws) : dw, splits, st);
+  } else {
+    if (dtype == S4TF_BF16) fill_tiles(a, 128, 128, Cfg<bf16_t>::BK);
+    else fill_tiles_f32(a, true);
+    a.nk_per_split = per;
+    a.split_stride = n;
+    a.out = splits > 1 ? ws : (void*)dw;
     ProfScope ps(PC_CONV_WGRAD, st);
     rc = dtype == S4TF_BF16 ? launch<bf16_t, PASS_WGRAD>(a, splits, st) : launch<float, PASS_WGRAD>(a, splits, st);
   }

@@ -1,11 +1,12 @@
-// fp32 3x3 / stride 1 / padding 1 convolution for layers of few channels (16 or 32 in and out, or the 4
-// padded channels of a first layer): the layers of a CIFAR ResNet.
+// fp32 3x3 / stride 1 / padding 1 convolution for layers of few channels (16, 32 or 64 in and out, or the 4
+// padded channels of a first layer) on small images (8, 16 or 32 wide): the layers of a CIFAR ResNet.
 //
 // The implicit-GEMM kernel of igemm.hip gathers every k-tile of the im2col matrix from global memory, nine
 // times the input in all, and pays a block barrier per 32 values of k: on a 131072 x 16 x 144 GEMM that is
 // ~20 us, of which the matrix cores need 4.  Here a workgroup owns 128 consecutive output pixels (whole rows
-// of one image), brings their input patch (the rows plus a one-pixel border, zeros outside the image) and the
-// whole filter into LDS once, and multiplies out of LDS with no further barrier:
+// of one image, or two whole 8x8 images) and a block of 16 or 32 output channels, brings the pixels' input
+// patch (their rows plus a one-pixel border, zeros outside the image) and its slice of the filter into LDS
+// once, and multiplies out of LDS with no further barrier:
 //   * v_mfma_f32_16x16x4_f32: 16 pixels x 16 outputs, 4 values of k = 4 adjacent channels of one tap, so a
 //     16-channel layer spends nothing on padding; A: lane l = pixel l%16, channel l/16; B: lane l = channel
 //     l/16, output l%16; D: register v of lane l = pixel 4*(l/16) + v, output l%16;
@@ -24,61 +25,73 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int G32 = 2;  // pixel blocks per wavefront of the 32-channel kernel
+constexpr int TILE = 128;          // output pixels per workgroup: 4 wavefronts x 2 blocks of 16
+constexpr int PATCH_PIXELS = 204;  // the largest patch: 4 rows of a 32-wide image, (4 + 2) x (32 + 2)
 
 struct PatchArgs {
   const float* x;     // (N, H, W, CI)
   const float* w;     // forward: (3, 3, CI, CO); FLIP: (3, 3, CO, CI), read turned and transposed
   float* y;           // (N, H, W, CO)
   const float* bias;  // forward only, optional
-  float* stats;       // forward only, optional: [sum | squared deviations][CO][runs of 32 pixels]
+  float* stats;       // forward only, optional: [sum | squared deviations][KT][runs of 32 pixels]
   int N, H, W, act, accumulate;
+  int KT;             // channels of y; workgroup (x, j) computes channels j*CO .. j*CO + CO-1
+  int RH, IMGS;       // a tile is IMGS images x RH rows each (IMGS > 1: whole images)
 };
 
-// G: blocks of 16 pixels per wavefront (2: 128 pixels per workgroup, 1: 64)
-template <int CI, int CO, bool FLIP, int G>
+template <int CI, int CO, bool FLIP>
 __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
-  constexpr int TILE = 64 * G;
+  constexpr int G = 2;  // blocks of 16 pixels per wavefront
   constexpr int CS = CI + 4;                     // floats per patch pixel
   constexpr int WS = CO >= 32 ? CO + 16 : CO;    // floats per filter row
   constexpr int NB = CO / 16;
   constexpr int C4 = CI / 4;
-  constexpr int PATCH_PIXELS = G == 2 ? 204 : 136;  // (TILE/W + 2) * (W + 2) at its largest, W = 32
   __shared__ __attribute__((aligned(16))) float wl[9 * CI * WS];
   __shared__ __attribute__((aligned(16))) float patch[PATCH_PIXELS * CS];
-  const int H = a.H, W = a.W, TH = TILE / W, PW = W + 2;
-  const int tiles_per_image = H / TH;
-  const int n = blockIdx.x / tiles_per_image, p0 = (blockIdx.x - n * tiles_per_image) * TH;
+  const int H = a.H, W = a.W, PW = W + 2, RH = a.RH, PR = RH + 2, KT = a.KT, n0 = blockIdx.y * CO;
+  int n, p0;  // first image and first row of the tile
+  if (a.IMGS == 1) {
+    const int tiles_per_image = H / RH;
+    n = blockIdx.x / tiles_per_image;
+    p0 = (blockIdx.x - n * tiles_per_image) * RH;
+  } else {
+    n = blockIdx.x * a.IMGS;
+    p0 = 0;
+  }
 
   // Every global load of the prologue is issued before the first LDS store: one memory latency, not one per loop.
-  // filter -> registers, 16 bytes at a time.  Forward: as it lies, (tap, ci) rows of CO.  FLIP: the filter lies
-  // (tap, co) rows of CI; chunk i is 4 adjacent ci of row (8 - tap, co), with pairs of lanes on adjacent chunks
-  // and co running over the lanes next (32-byte pieces of global memory; LDS stores two lanes to a bank)
+  // filter -> registers, 16 bytes at a time.  Forward: (tap, ci) rows of KT, of which CO from n0 on.  FLIP: the filter
+  // lies (tap, co) rows of CI with KT rows per tap; chunk i is 4 adjacent ci of row (8 - tap, n0 + co), with pairs of
+  // lanes on adjacent chunks and co running over the lanes next (32-byte pieces of global memory; LDS stores two
+  // lanes to a bank)
   constexpr int WCH = 9 * CI * CO / 4;
   constexpr int WV = (WCH + 255) / 256;
   float4 wq[WV];
 #pragma unroll
   for (int k = 0; k < WV; ++k) {
     const int i = threadIdx.x + k * 256;
-    int src = i;
+    int src;
     if constexpr (FLIP) {
       const int lo = i % 2, co = (i / 2) % CO, hi = (i / (2 * CO)) % (CI / 8), tap = i / (CO * (CI / 4));
-      src = ((8 - tap) * CO + co) * (CI / 4) + hi * 2 + lo;
+      src = ((8 - tap) * KT + n0 + co) * (CI / 4) + hi * 2 + lo;
+    } else {
+      src = ((i / (CO / 4)) * KT + n0) / 4 + i % (CO / 4);
     }
     wq[k] = i < WCH ? reinterpret_cast<const float4*>(a.w)[src] : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  // input rows p0-1 .. p0+TH, columns -1 .. W -> registers, 16 bytes (4 channels) at a time; zeros outside the image
+  // per image of the tile, input rows p0-1 .. p0+RH, columns -1 .. W -> registers, 16 bytes (4 channels) at a
+  // time; zeros outside the image
   constexpr int PV = (PATCH_PIXELS * C4 + 255) / 256;
-  const int chunks = (TH + 2) * PW * C4;
+  const int chunks = a.IMGS * PR * PW * C4;
   float4 pv[PV];
 #pragma unroll
   for (int k = 0; k < PV; ++k) {
     const int i = threadIdx.x + k * 256;
-    const int c4 = i % C4, t = i / C4, pw = t % PW, pr = t / PW;
+    const int c4 = i % C4, t = i / C4, pw = t % PW, prow = t / PW, img = prow / PR, pr = prow - img * PR;
     const int h = p0 + pr - 1, wc = pw - 1;
     pv[k] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (i < chunks && h >= 0 && h < H && wc >= 0 && wc < W)
-      pv[k] = *reinterpret_cast<const float4*>(a.x + (((long long)n * H + h) * W + wc) * CI + c4 * 4);
+      pv[k] = *reinterpret_cast<const float4*>(a.x + (((long long)(n + img) * H + h) * W + wc) * CI + c4 * 4);
   }
   // registers -> LDS: filter row (tap, ci), column co
 #pragma unroll
@@ -107,8 +120,8 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     const int m = wave * 16 * G + g * 16 + (lane & 15);  // tile-local output pixel
-    const int pr = m / W, pq = m - pr * W;
-    abase[g] = (pr * PW + pq) * CS + (lane >> 4);
+    const int row = m / W, pq = m - row * W, img = row / RH;
+    abase[g] = ((row + 2 * img) * PW + pq) * CS + (lane >> 4);  // patch row img*(RH + 2) + (row - img*RH)
   }
   const int bbase = (lane >> 4) * WS + (lane & 15);
   f32x4 acc[G][NB];
@@ -164,8 +177,8 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
       s += __shfl_xor(s, 32, 64); q += __shfl_xor(q, 32, 64);
       if (lane < 16) {
         const int col = nb * 16 + lane;
-        a.stats[col * runs + run] = fmaf((float)RUN, pivot, s);
-        a.stats[(CO + col) * runs + run] = fmaxf(q - s * s * (1.f / (float)RUN), 0.f);
+        a.stats[(n0 + col) * runs + run] = fmaf((float)RUN, pivot, s);
+        a.stats[(KT + n0 + col) * runs + run] = fmaxf(q - s * s * (1.f / (float)RUN), 0.f);
       }
     }
   }
@@ -174,12 +187,12 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int col = nb * 16 + (lane & 15);
-    const float bias = (!FLIP && a.bias) ? a.bias[col] : 0.f;
+    const float bias = (!FLIP && a.bias) ? a.bias[n0 + col] : 0.f;
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        float* dst = a.y + (row0 + g * 16 + 4 * (lane >> 4) + v) * CO + col;
+        float* dst = a.y + (row0 + g * 16 + 4 * (lane >> 4) + v) * KT + n0 + col;
         float val = acc[g][nb][v] + bias;
         if (FLIP && a.accumulate) val += *dst;
         *dst = fminf(fmaxf(val, act_lo), act_hi);
@@ -187,51 +200,238 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
   }
 }
 
-template <int CI, int CO, bool FLIP, int G>
+// ---- filter gradient ------------------------------------------------------------------------------------
+// dw[tap][c][k] = sum over pixels m of x[m + tap][c] * dy[m][k]: per tap a (CI x pixels) x (pixels x CO) product,
+// with the MFMA's k axis running over 4 adjacent pixels of an image row: A: lane l = channel l%16, pixel l/16 (read
+// from the patch, 16 adjacent channels per pixel); B: lane l = pixel l/16, output l%16 (from the tile's rows of dy);
+// D: register v of lane l = channel 4*(l/16) + v, output l%16.  A wavefront keeps one accumulator block per tap
+// through all the tiles its workgroup walks; the workgroup then writes one partial filter gradient (its slab), and
+// a reduction kernel adds the slabs in a fixed order.
+// Patch pixels are 16 (48, 80) floats apart for 16 (32, 64) channels and rows of dy 16 (48) floats: 4 adjacent
+// pixels x 16 adjacent channels then cover the 64 LDS banks once.
+struct WgradArgs {
+  const float* x;   // (N, H, W, CI)
+  const float* dy;  // (N, H, W, KT)
+  float* out;       // gridDim.x slabs of (3, 3, CI, KT)
+  int N, H, W, KT, RH, IMGS, tiles;
+  long long slab;   // floats per slab
+};
+
+template <int CI, int CO>
+__global__ __launch_bounds__(256) void patchconv_wgrad_kernel(const WgradArgs a) {
+  constexpr int CS = CI == 16 ? 16 : CI == 32 ? 48 : 80;
+  constexpr int DS = CO == 16 ? 16 : 48;
+  constexpr int NCB = CI / 16, NKB = CO / 16, C4 = CI / 4, K4 = CO / 4;
+  // Four blocks of 16 x 16 outputs: a wavefront owns one of them over all 128 pixels (nothing to add across
+  // wavefronts).  One block: a wavefront owns 32 of the pixels, and the four are added through LDS at the end.
+  constexpr bool OWN_BLOCK = NCB * NKB == 4;
+  static_assert(OWN_BLOCK || NCB * NKB == 1, "one or four output blocks per workgroup");
+  constexpr int STEPS = OWN_BLOCK ? TILE / 4 : TILE / 16;  // k-steps of 4 pixels per wavefront and tile
+  constexpr int TILE_FLOATS = PATCH_PIXELS * CS + TILE * DS, RED_FLOATS = OWN_BLOCK ? 0 : 9 * CI * CO;
+  __shared__ __attribute__((aligned(16))) float smem[TILE_FLOATS > RED_FLOATS ? TILE_FLOATS : RED_FLOATS];
+  float* patch = smem;
+  float* dyt = smem + PATCH_PIXELS * CS;
+  const int H = a.H, W = a.W, PW = W + 2, RH = a.RH, PR = RH + 2, KT = a.KT, n0 = blockIdx.y * CO;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int cb0 = OWN_BLOCK ? wave / NKB : 0, kb0 = OWN_BLOCK ? wave % NKB : 0;
+  const int m0 = (OWN_BLOCK ? 0 : wave * 32) + (lane >> 4);  // this lane's pixel of k-step 0
+  const int lw = 31 - __clz(W), lrh = a.IMGS > 1 ? 31 - __clz(RH) : 30;  // W and RH (if several images) are powers of two
+  // patch offset of tile pixel m at this lane's channel: patch row = row + 2*image
+  auto pix_off = [&](int m) {
+    const int row = m >> lw;
+    return ((row + 2 * (row >> lrh)) * PW + (m & (W - 1))) * CS + cb0 * 16 + (lane & 15);
+  };
+  const int bbase = m0 * DS + kb0 * 16 + (lane & 15);
+  f32x4 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  constexpr int PV = (PATCH_PIXELS * C4 + 255) / 256, DV = (TILE * K4 + 255) / 256;
+  const int chunks = a.IMGS * PR * PW * C4;
+  for (int tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+    int n, p0;
+    if (a.IMGS == 1) {
+      const int tiles_per_image = H / RH;
+      n = tile / tiles_per_image;
+      p0 = (tile - n * tiles_per_image) * RH;
+    } else {
+      n = tile * a.IMGS;
+      p0 = 0;
+    }
+    float4 pv[PV], dv[DV];
+#pragma unroll
+    for (int k = 0; k < PV; ++k) {
+      const int i = threadIdx.x + k * 256;
+      const int c4 = i % C4, t = i / C4, pw = t % PW, prow = t / PW, img = prow / PR, pr = prow - img * PR;
+      const int h = p0 + pr - 1, wc = pw - 1;
+      pv[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < chunks && h >= 0 && h < H && wc >= 0 && wc < W)
+        pv[k] = *reinterpret_cast<const float4*>(a.x + (((long long)(n + img) * H + h) * W + wc) * CI + c4 * 4);
+    }
+#pragma unroll
+    for (int k = 0; k < DV; ++k) {
+      const int i = threadIdx.x + k * 256;
+      const int k4 = i % K4, m = i / K4;
+      dv[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < TILE * K4) dv[k] = *reinterpret_cast<const float4*>(a.dy + ((long long)tile * TILE + m) * KT + n0 + k4 * 4);
+    }
+    __syncthreads();  // everyone is done with the previous tile
+#pragma unroll
+    for (int k = 0; k < PV; ++k) {
+      const int i = threadIdx.x + k * 256;
+      if (i < chunks) *reinterpret_cast<float4*>(patch + (i / C4) * CS + (i % C4) * 4) = pv[k];
+    }
+#pragma unroll
+    for (int k = 0; k < DV; ++k) {
+      const int i = threadIdx.x + k * 256;
+      if (i < TILE * K4) *reinterpret_cast<float4*>(dyt + (i / K4) * DS + (i % K4) * 4) = dv[k];
+    }
+    __syncthreads();
+    // the fragments of k-step j+1 are read while step j is multiplied
+    float af[2][9], bf[2];
+    auto read_step = [&](int j, int buf) {
+      bf[buf] = dyt[bbase + 4 * j * DS];
+      const int ab = pix_off(m0 + 4 * j);
+#pragma unroll
+      for (int t = 0; t < 9; ++t) af[buf][t] = patch[ab + ((t / 3) * PW + (t % 3)) * CS];
+    };
+    // (a rolled loop of two steps: unrolled all the way, the compiler reads every step's fragments up front and
+    // the registers they fill leave one wavefront per SIMD)
+    static_assert(STEPS % 2 == 0, "steps go in pairs");
+    read_step(0, 0);
+#pragma unroll 1
+    for (int j = 0; j < STEPS; j += 2) {
+      read_step(j + 1, 1);
+#pragma unroll
+      for (int t = 0; t < 9; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[0][t], bf[0], acc[t], 0, 0, 0);
+      if (j + 2 < STEPS) read_step(j + 2, 0);
+#pragma unroll
+      for (int t = 0; t < 9; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[1][t], bf[1], acc[t], 0, 0, 0);
+    }
+  }
+  float* slab = a.out + (long long)blockIdx.x * a.slab;
+  if constexpr (OWN_BLOCK) {
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        slab[(long long)(t * CI + cb0 * 16 + 4 * (lane >> 4) + v) * KT + n0 + kb0 * 16 + (lane & 15)] = acc[t][v];
+  } else {
+    // the four wavefronts' sums, added in wavefront order
+    __syncthreads();
+    float* red = smem;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      if (wave == w) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            float* r = red + (t * CI + 4 * (lane >> 4) + v) * CO + (lane & 15);
+            *r = w == 0 ? acc[t][v] : *r + acc[t][v];
+          }
+      }
+      __syncthreads();
+    }
+    for (int i = threadIdx.x; i < 9 * CI * K4; i += 256) {
+      const int row = i / K4, k4 = i - row * K4;  // row = (tap, c)
+      *reinterpret_cast<float4*>(slab + (long long)row * KT + n0 + k4 * 4) = *reinterpret_cast<const float4*>(red + row * CO + k4 * 4);
+    }
+  }
+}
+
+template <int CI, int CO, bool FLIP>
 int launch_patch(const PatchArgs& a, hipStream_t st) {
-  const unsigned tiles = (unsigned)((long long)a.N * a.H * a.W / (64 * G));
-  hipLaunchKernelGGL((patchconv_kernel<CI, CO, FLIP, G>), dim3(tiles), dim3(256), 0, st, a);
+  const unsigned tiles = (unsigned)((long long)a.N * a.H * a.W / TILE);
+  hipLaunchKernelGGL((patchconv_kernel<CI, CO, FLIP>), dim3(tiles, a.KT / CO), dim3(256), 0, st, a);
   return launch_status("patchconv");
 }
 
-// pixel blocks per wavefront for a layer of C input channels
-int groups_for(int C) { return C == 32 ? G32 : 2; }
+// How the 128-pixel tiles lie in the images: whole rows of one image, or whole images.  False when they do not fit.
+bool tiling(int N, int H, int W, int& RH, int& IMGS) {
+  if (W != 8 && W != 16 && W != 32) return false;
+  const int hw = H * W;
+  if (hw >= TILE) {
+    if (hw % TILE) return false;
+    RH = TILE / W; IMGS = 1;
+  } else {
+    if (TILE % hw || N % (TILE / hw)) return false;
+    RH = H; IMGS = TILE / hw;
+  }
+  return IMGS * (RH + 2) * (W + 2) <= PATCH_PIXELS;
+}
 
 bool shape_ok(const ConvGeom& g) {
-  if (g.R != 3 || g.S != 3 || g.stride != 1 || g.pad != 1) return false;
-  if (g.W != 16 && g.W != 32) return false;
-  const int TH = 64 * groups_for(g.C) / g.W;  // rows of an image per workgroup
-  return g.H % TH == 0 && (long long)g.N * g.H * g.W * (g.C > g.K ? g.C : g.K) < (1LL << 31);
+  int RH, IMGS;
+  if (g.R != 3 || g.S != 3 || g.stride != 1 || g.pad != 1 || !tiling(g.N, g.H, g.W, RH, IMGS)) return false;
+  return (long long)g.N * g.H * g.W * (g.C > g.K ? g.C : g.K) < (1LL << 31);
+}
+bool channels_ok(int C, int K) { return (C == 16 && K == 16) || (C == 32 && K == 32) || (C == 64 && K == 64); }
+
+PatchArgs make_args(const ConvGeom& g, const void* in, const void* w, void* out, int out_channels) {
+  PatchArgs a = {};
+  a.x = static_cast<const float*>(in); a.w = static_cast<const float*>(w); a.y = static_cast<float*>(out);
+  a.N = g.N; a.H = g.H; a.W = g.W; a.KT = out_channels;
+  tiling(g.N, g.H, g.W, a.RH, a.IMGS);
+  return a;
 }
 
 }  // namespace
 
 bool patchconv_fwd_ok(const ConvGeom& g, int dtype) {
-  return dtype == S4TF_F32 && shape_ok(g) && ((g.C == 16 && g.K == 16) || (g.C == 32 && g.K == 32) || (g.C == 4 && g.K == 16));
+  return dtype == S4TF_F32 && shape_ok(g) && (channels_ok(g.C, g.K) || (g.C == 4 && g.K == 16));
 }
-bool patchconv_dgrad_ok(const ConvGeom& g, int dtype) {
-  return dtype == S4TF_F32 && shape_ok(g) && ((g.C == 16 && g.K == 16) || (g.C == 32 && g.K == 32));
-}
+bool patchconv_dgrad_ok(const ConvGeom& g, int dtype) { return dtype == S4TF_F32 && shape_ok(g) && channels_ok(g.C, g.K); }
 
 // y = act(conv(x, w) + bias); with `stats`, also the BatchNorm partial sums of igemm_fwd, per run of *stats_rows pixels
 int patchconv_fwd(const ConvGeom& g, const void* x, const void* w, const float* bias, int act, void* y, float* stats,
                   int* stats_rows, hipStream_t st) {
   if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return fail(S4TF_ERR_SHAPE, "patchconv: operands must be 16-byte aligned");
-  PatchArgs a = {static_cast<const float*>(x), static_cast<const float*>(w), static_cast<float*>(y), bias, stats,
-                 g.N, g.H, g.W, act, 0};
-  if (stats_rows) *stats_rows = 16 * groups_for(g.C);
-  if (g.C == 16) return launch_patch<16, 16, false, 2>(a, st);
-  if (g.C == 32) return launch_patch<32, 32, false, G32>(a, st);
-  return launch_patch<4, 16, false, 2>(a, st);
+  PatchArgs a = make_args(g, x, w, y, g.K);
+  a.bias = bias; a.stats = stats; a.act = act;
+  if (stats_rows) *stats_rows = 32;
+  if (g.C == 16) return launch_patch<16, 16, false>(a, st);
+  if (g.C == 32) return launch_patch<32, 32, false>(a, st);
+  if (g.C == 64) return launch_patch<64, 16, false>(a, st);  // four workgroups of 16 output channels per tile
+  return launch_patch<4, 16, false>(a, st);
 }
 
 // dx (+)= the pullback of the same layer to its input
 int patchconv_dgrad(const ConvGeom& g, const void* dy, const void* w, void* dx, int accumulate, hipStream_t st) {
   if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return fail(S4TF_ERR_SHAPE, "patchconv: operands must be 16-byte aligned");
-  PatchArgs a = {static_cast<const float*>(dy), static_cast<const float*>(w), static_cast<float*>(dx), nullptr, nullptr,
-                 g.N, g.H, g.W, S4TF_ACT_NONE, accumulate};
-  if (g.C == 16) return launch_patch<16, 16, true, 2>(a, st);
-  return launch_patch<32, 32, true, G32>(a, st);
+  PatchArgs a = make_args(g, dy, w, dx, g.C);
+  a.accumulate = accumulate;
+  if (g.C == 16) return launch_patch<16, 16, true>(a, st);
+  if (g.C == 32) return launch_patch<32, 32, true>(a, st);
+  return launch_patch<64, 16, true>(a, st);
+}
+
+bool patchconv_wgrad_ok(const ConvGeom& g, int dtype) { return dtype == S4TF_F32 && shape_ok(g) && channels_ok(g.C, g.K); }
+
+// Workgroups along the pixel axis = partial filter gradients (slabs) the kernel leaves: enough workgroups to fill
+// the chip, each walking at most a few tiles
+int patchconv_wgrad_splits(const ConvGeom& g) {
+  const int tiles = (int)((long long)g.N * g.H * g.W / TILE);
+  const int per_tile = g.C == 64 ? 4 : 1;  // workgroups per tile: blocks of 16 output channels for 64-channel layers
+  int want = 512 / per_tile;
+  if (want > tiles) want = tiles;
+  const int walk = (tiles + want - 1) / want;
+  return (tiles + walk - 1) / walk;
+}
+
+// `splits` slabs of (3, 3, C, K) partial sums into out (the filter gradient itself when splits == 1)
+int patchconv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* out, int splits, hipStream_t st) {
+  if (!aligned16(x) || !aligned16(dy) || !aligned16(out)) return fail(S4TF_ERR_SHAPE, "patchconv: operands must be 16-byte aligned");
+  WgradArgs a = {};
+  a.x = static_cast<const float*>(x); a.dy = static_cast<const float*>(dy); a.out = out;
+  a.N = g.N; a.H = g.H; a.W = g.W; a.KT = g.K;
+  tiling(g.N, g.H, g.W, a.RH, a.IMGS);
+  a.tiles = (int)((long long)g.N * g.H * g.W / TILE);
+  a.slab = (long long)9 * g.C * g.K;
+  if (g.C == 16) hipLaunchKernelGGL((patchconv_wgrad_kernel<16, 16>), dim3(splits, 1), dim3(256), 0, st, a);
+  else if (g.C == 32) hipLaunchKernelGGL((patchconv_wgrad_kernel<32, 32>), dim3(splits, 1), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((patchconv_wgrad_kernel<64, 16>), dim3(splits, 4), dim3(256), 0, st, a);
+  return launch_status("patchconv_wgrad");
 }
 
 }  // namespace s4tf

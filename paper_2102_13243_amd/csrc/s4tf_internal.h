@@ -98,6 +98,9 @@ bool patchconv_dgrad_ok(const ConvGeom& g, int dtype);
 int patchconv_fwd(const ConvGeom& g, const void* x, const void* w, const float* bias, int act, void* y, float* stats,
                   int* stats_rows, hipStream_t st);
 int patchconv_dgrad(const ConvGeom& g, const void* dy, const void* w, void* dx, int accumulate, hipStream_t st);
+bool patchconv_wgrad_ok(const ConvGeom& g, int dtype);
+int patchconv_wgrad_splits(const ConvGeom& g);  // partial filter gradients the kernel leaves for the reduction
+int patchconv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* out, int splits, hipStream_t st);
 // acc_src (optional; only where igemm_dgrad_adds_other says so): the result is dgrad + acc_src instead of
 // dgrad (+ old dx); acc_bits (optional): activation bits as bn_fwd leaves them, one per element of acc_src,
 // elements whose bit is clear add nothing.

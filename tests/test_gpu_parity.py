@@ -165,6 +165,9 @@ CONV_SHAPES = [
     (2, 16, 16, 32, 32, 3, 1, 1),     # ... 32 channels, 8 rows a tile, two tiles an image
     (5, 8, 32, 16, 16, 3, 1, 1),      # ... images that are not square, an odd number of them
     (2, 16, 16, 4, 16, 3, 1, 1),      # ... a first layer padded to 4 channels (forward there; its pullbacks elsewhere)
+    (6, 8, 8, 64, 64, 3, 1, 1),       # ... 64 channels in four blocks of 16 outputs, two whole 8x8 images a tile
+    (3, 16, 8, 32, 32, 3, 1, 1),      # ... 8 wide, one image a tile
+    (4, 8, 8, 16, 16, 3, 1, 1),
 ]
 
 
