@@ -18,6 +18,11 @@
 // 180 degrees and its channel axes swapped: the same kernel, told to read the filter that way (FLIP).
 // The forward pass can leave the partial sums of a BatchNorm that follows, per run of 32 pixels, exactly as
 // igemm_fwd does.
+// 1x1 / stride 1 layers whose reduction axis is 16, 24, 32 or 64 channels (forward of an expansion layer, input
+// pullback of a projection layer) take the same kernel with a single tap: 128 pixels and a block of 16, 32 or 48
+// output channels per workgroup, one round of loads, a few MFMAs, the stores.  They are bound by the bytes they
+// move; the implicit-GEMM kernel's fixed cost per workgroup (row decomposition, staged k-loop) was most of
+// their time.
 #include "s4tf_internal.h"
 
 namespace s4tf {
@@ -39,18 +44,24 @@ struct PatchArgs {
   int RH, IMGS;       // a tile is IMGS images x RH rows each (IMGS > 1: whole images)
 };
 
-template <int CI, int CO, bool FLIP>
+// TAPS = 9: the 3x3 layers above.  TAPS = 1: a 1x1 / stride 1 layer with a short reduction axis (the expansion
+// layers of an inverted-residual block and, with FLIP, the pullback of its projection layers): the "patch" is the
+// tile's 128 pixels themselves, whatever the image shape.
+template <int CI, int CO, bool FLIP, int TAPS = 9>
 __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
   constexpr int G = 2;  // blocks of 16 pixels per wavefront
-  constexpr int CS = CI + 4;                     // floats per patch pixel
-  constexpr int WS = CO >= 32 ? CO + 16 : CO;    // floats per filter row
+  constexpr int CS = CI + 4;                                 // floats per patch pixel
+  constexpr int WS = CO == 16 ? 16 : CO == 32 ? 48 : 80;     // floats per filter row: 16 or 48 modulo the 64 banks
+  static_assert(CO == 16 || CO == 32 || CO == 48, "output blocks of 16, 32 or 48 channels");
   constexpr int NB = CO / 16;
   constexpr int C4 = CI / 4;
-  __shared__ __attribute__((aligned(16))) float wl[9 * CI * WS];
-  __shared__ __attribute__((aligned(16))) float patch[PATCH_PIXELS * CS];
+  constexpr int PPIX = TAPS == 1 ? TILE : PATCH_PIXELS;
+  __shared__ __attribute__((aligned(16))) float wl[TAPS * CI * WS];
+  __shared__ __attribute__((aligned(16))) float patch[PPIX * CS];
   const int H = a.H, W = a.W, PW = W + 2, RH = a.RH, PR = RH + 2, KT = a.KT, n0 = blockIdx.y * CO;
-  int n, p0;  // first image and first row of the tile
-  if (a.IMGS == 1) {
+  int n = 0, p0 = 0;  // first image and first row of the tile
+  if constexpr (TAPS == 1) {
+  } else if (a.IMGS == 1) {
     const int tiles_per_image = H / RH;
     n = blockIdx.x / tiles_per_image;
     p0 = (blockIdx.x - n * tiles_per_image) * RH;
@@ -61,10 +72,10 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
 
   // Every global load of the prologue is issued before the first LDS store: one memory latency, not one per loop.
   // filter -> registers, 16 bytes at a time.  Forward: (tap, ci) rows of KT, of which CO from n0 on.  FLIP: the filter
-  // lies (tap, co) rows of CI with KT rows per tap; chunk i is 4 adjacent ci of row (8 - tap, n0 + co), with pairs of
+  // lies (tap, co) rows of CI with KT rows per tap; chunk i is 4 adjacent ci of row (TAPS-1 - tap, n0 + co), with pairs of
   // lanes on adjacent chunks and co running over the lanes next (32-byte pieces of global memory; LDS stores two
   // lanes to a bank)
-  constexpr int WCH = 9 * CI * CO / 4;
+  constexpr int WCH = TAPS * CI * CO / 4;
   constexpr int WV = (WCH + 255) / 256;
   float4 wq[WV];
 #pragma unroll
@@ -73,7 +84,7 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
     int src;
     if constexpr (FLIP) {
       const int lo = i % 2, co = (i / 2) % CO, hi = (i / (2 * CO)) % (CI / 8), tap = i / (CO * (CI / 4));
-      src = ((8 - tap) * KT + n0 + co) * (CI / 4) + hi * 2 + lo;
+      src = ((TAPS - 1 - tap) * KT + n0 + co) * (CI / 4) + hi * 2 + lo;
     } else {
       src = ((i / (CO / 4)) * KT + n0) / 4 + i % (CO / 4);
     }
@@ -81,17 +92,21 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
   }
   // per image of the tile, input rows p0-1 .. p0+RH, columns -1 .. W -> registers, 16 bytes (4 channels) at a
   // time; zeros outside the image
-  constexpr int PV = (PATCH_PIXELS * C4 + 255) / 256;
-  const int chunks = a.IMGS * PR * PW * C4;
+  constexpr int PV = (PPIX * C4 + 255) / 256;
+  const int chunks = TAPS == 1 ? TILE * C4 : a.IMGS * PR * PW * C4;
   float4 pv[PV];
 #pragma unroll
   for (int k = 0; k < PV; ++k) {
     const int i = threadIdx.x + k * 256;
-    const int c4 = i % C4, t = i / C4, pw = t % PW, prow = t / PW, img = prow / PR, pr = prow - img * PR;
-    const int h = p0 + pr - 1, wc = pw - 1;
     pv[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < chunks && h >= 0 && h < H && wc >= 0 && wc < W)
-      pv[k] = *reinterpret_cast<const float4*>(a.x + (((long long)(n + img) * H + h) * W + wc) * CI + c4 * 4);
+    if constexpr (TAPS == 1) {
+      if (i < chunks) pv[k] = reinterpret_cast<const float4*>(a.x + (long long)blockIdx.x * TILE * CI)[i];
+    } else {
+      const int c4 = i % C4, t = i / C4, pw = t % PW, prow = t / PW, img = prow / PR, pr = prow - img * PR;
+      const int h = p0 + pr - 1, wc = pw - 1;
+      if (i < chunks && h >= 0 && h < H && wc >= 0 && wc < W)
+        pv[k] = *reinterpret_cast<const float4*>(a.x + (((long long)(n + img) * H + h) * W + wc) * CI + c4 * 4);
+    }
   }
   // registers -> LDS: filter row (tap, ci), column co
 #pragma unroll
@@ -120,8 +135,12 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     const int m = wave * 16 * G + g * 16 + (lane & 15);  // tile-local output pixel
-    const int row = m / W, pq = m - row * W, img = row / RH;
-    abase[g] = ((row + 2 * img) * PW + pq) * CS + (lane >> 4);  // patch row img*(RH + 2) + (row - img*RH)
+    if constexpr (TAPS == 1) {
+      abase[g] = m * CS + (lane >> 4);
+    } else {
+      const int row = m / W, pq = m - row * W, img = row / RH;
+      abase[g] = ((row + 2 * img) * PW + pq) * CS + (lane >> 4);  // patch row img*(RH + 2) + (row - img*RH)
+    }
   }
   const int bbase = (lane >> 4) * WS + (lane & 15);
   f32x4 acc[G][NB];
@@ -132,7 +151,7 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
   // the fragments of tap t+1 are read while tap t is multiplied (the loop is unrolled: both sets are registers)
   float af[2][G][C4], bfr[2][C4][NB];
   auto read_tap = [&](int tap, int buf) {
-    const int toff = ((tap / 3) * PW + (tap % 3)) * CS;
+    const int toff = TAPS == 1 ? 0 : ((tap / 3) * PW + (tap % 3)) * CS;
 #pragma unroll
     for (int cg = 0; cg < C4; ++cg) {
 #pragma unroll
@@ -143,8 +162,8 @@ __global__ __launch_bounds__(256) void patchconv_kernel(const PatchArgs a) {
   };
   read_tap(0, 0);
 #pragma unroll
-  for (int tap = 0; tap < 9; ++tap) {
-    if (tap + 1 < 9) read_tap(tap + 1, (tap + 1) & 1);
+  for (int tap = 0; tap < TAPS; ++tap) {
+    if (tap + 1 < TAPS) read_tap(tap + 1, (tap + 1) & 1);
 #pragma unroll
     for (int cg = 0; cg < C4; ++cg)
 #pragma unroll
@@ -340,11 +359,35 @@ __global__ __launch_bounds__(256) void patchconv_wgrad_kernel(const WgradArgs a)
   }
 }
 
-template <int CI, int CO, bool FLIP>
+template <int CI, int CO, bool FLIP, int TAPS = 9>
 int launch_patch(const PatchArgs& a, hipStream_t st) {
   const unsigned tiles = (unsigned)((long long)a.N * a.H * a.W / TILE);
-  hipLaunchKernelGGL((patchconv_kernel<CI, CO, FLIP>), dim3(tiles, a.KT / CO), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((patchconv_kernel<CI, CO, FLIP, TAPS>), dim3(tiles, a.KT / CO), dim3(256), 0, st, a);
   return launch_status("patchconv");
+}
+
+// 1x1 layers: the widest block of output channels that divides their number
+template <int CI, bool FLIP>
+int launch_point(const PatchArgs& a, hipStream_t st) {
+  if (a.KT % 48 == 0) return launch_patch<CI, 48, FLIP, 1>(a, st);
+  if (a.KT % 32 == 0) return launch_patch<CI, 32, FLIP, 1>(a, st);
+  return launch_patch<CI, 16, FLIP, 1>(a, st);
+}
+template <bool FLIP>
+int launch_point(int reduce_channels, const PatchArgs& a, hipStream_t st) {
+  switch (reduce_channels) {
+    case 16: return launch_point<16, FLIP>(a, st);
+    case 24: return launch_point<24, FLIP>(a, st);
+    case 32: return launch_point<32, FLIP>(a, st);
+    default: return launch_point<64, FLIP>(a, st);
+  }
+}
+// a 1x1 / stride 1 layer whose reduction axis has `reduce` channels and whose result has `out` channels
+bool point_ok(const ConvGeom& g, int reduce, int out) {
+  if (g.R != 1 || g.S != 1 || g.stride != 1 || g.pad != 0) return false;
+  if (reduce != 16 && reduce != 24 && reduce != 32 && reduce != 64) return false;
+  const long long M = (long long)g.N * g.H * g.W;
+  return out % 16 == 0 && M % TILE == 0 && M * (reduce > out ? reduce : out) < (1LL << 31);
 }
 
 // How the 128-pixel tiles lie in the images: whole rows of one image, or whole images.  False when they do not fit.
@@ -372,16 +415,21 @@ PatchArgs make_args(const ConvGeom& g, const void* in, const void* w, void* out,
   PatchArgs a = {};
   a.x = static_cast<const float*>(in); a.w = static_cast<const float*>(w); a.y = static_cast<float*>(out);
   a.N = g.N; a.H = g.H; a.W = g.W; a.KT = out_channels;
-  tiling(g.N, g.H, g.W, a.RH, a.IMGS);
+  a.RH = 1; a.IMGS = 1;  // (unused by 1x1 layers)
+  if (g.R == 3) tiling(g.N, g.H, g.W, a.RH, a.IMGS);
   return a;
 }
 
 }  // namespace
 
 bool patchconv_fwd_ok(const ConvGeom& g, int dtype) {
-  return dtype == S4TF_F32 && shape_ok(g) && (channels_ok(g.C, g.K) || (g.C == 4 && g.K == 16));
+  if (dtype != S4TF_F32) return false;
+  return point_ok(g, g.C, g.K) || (shape_ok(g) && (channels_ok(g.C, g.K) || (g.C == 4 && g.K == 16)));
 }
-bool patchconv_dgrad_ok(const ConvGeom& g, int dtype) { return dtype == S4TF_F32 && shape_ok(g) && channels_ok(g.C, g.K); }
+bool patchconv_dgrad_ok(const ConvGeom& g, int dtype) {
+  if (dtype != S4TF_F32) return false;
+  return point_ok(g, g.K, g.C) || (shape_ok(g) && channels_ok(g.C, g.K));
+}
 
 // y = act(conv(x, w) + bias); with `stats`, also the BatchNorm partial sums of igemm_fwd, per run of *stats_rows pixels
 int patchconv_fwd(const ConvGeom& g, const void* x, const void* w, const float* bias, int act, void* y, float* stats,
@@ -390,6 +438,7 @@ int patchconv_fwd(const ConvGeom& g, const void* x, const void* w, const float* 
   PatchArgs a = make_args(g, x, w, y, g.K);
   a.bias = bias; a.stats = stats; a.act = act;
   if (stats_rows) *stats_rows = 32;
+  if (g.R == 1) return launch_point<false>(g.C, a, st);
   if (g.C == 16) return launch_patch<16, 16, false>(a, st);
   if (g.C == 32) return launch_patch<32, 32, false>(a, st);
   if (g.C == 64) return launch_patch<64, 16, false>(a, st);  // four workgroups of 16 output channels per tile
@@ -401,6 +450,7 @@ int patchconv_dgrad(const ConvGeom& g, const void* dy, const void* w, void* dx, 
   if (!aligned16(dy) || !aligned16(w) || !aligned16(dx)) return fail(S4TF_ERR_SHAPE, "patchconv: operands must be 16-byte aligned");
   PatchArgs a = make_args(g, dy, w, dx, g.C);
   a.accumulate = accumulate;
+  if (g.R == 1) return launch_point<true>(g.K, a, st);
   if (g.C == 16) return launch_patch<16, 16, true>(a, st);
   if (g.C == 32) return launch_patch<32, 32, true>(a, st);
   return launch_patch<64, 16, true>(a, st);

@@ -168,6 +168,12 @@ CONV_SHAPES = [
     (6, 8, 8, 64, 64, 3, 1, 1),       # ... 64 channels in four blocks of 16 outputs, two whole 8x8 images a tile
     (3, 16, 8, 32, 32, 3, 1, 1),      # ... 8 wide, one image a tile
     (4, 8, 8, 16, 16, 3, 1, 1),
+    (2, 16, 16, 16, 96, 1, 1, 0),     # fp32 1x1 with a short reduction axis: one tap of the same kernel; blocks of 48 outputs
+    (1, 8, 16, 24, 144, 1, 1, 0),     # ... 24 channels in
+    (4, 8, 8, 32, 32, 1, 1, 0),       # ... a block of 32 outputs; the input pullback takes the kernel too
+    (2, 8, 8, 64, 80, 1, 1, 0),       # ... blocks of 16 outputs
+    (2, 16, 16, 96, 16, 1, 1, 0),     # ... a projection layer: its input pullback (16 -> 96 channels) takes the kernel
+    (2, 8, 8, 144, 24, 1, 1, 0),
 ]
 
 
