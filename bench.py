@@ -194,7 +194,7 @@ def main():
                          "synchronisation after every op (the paper's eager mode), and print one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+        sys.exit("bench.py: the library runs on one GPU only (no sharding, no collectives); use --gpus 1")
 
     import torch
     from paper_2102_13243_amd import binding as B

@@ -94,9 +94,10 @@ def canaries():
 
 @pytest.fixture(scope="module", autouse=True)
 def report_file():
-    """The measured errors of every comparison, for the record (gpurun_out/ is where GPU runs leave files)."""
+    """The measured errors of every comparison, for the record: written as parity_report.txt into the directory
+    S4TF_REPORT_DIR names (default: the scratch output directory at the repository root), if it exists."""
     yield
-    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    out = os.environ.get("S4TF_REPORT_DIR") or os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
     if os.path.isdir(out) and _REPORT:
         with open(os.path.join(out, "parity_report.txt"), "w") as f:
             f.write("\n".join(_REPORT) + "\n")
