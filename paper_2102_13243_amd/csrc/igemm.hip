@@ -28,32 +28,36 @@ __device__ inline uint4 ldg16(const void* p) { return *reinterpret_cast<const ui
 __device__ inline uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
 
 // ---- element index of operand A / B for (row, k), or -1 when it is padding ------------------
-template <int PASS> __device__ inline long long a_index(const ConvGeom& g, int row, int kk) {
+// (the element-wise loaders call these per element: every quotient is a multiply-high by a host-computed
+// reciprocal; run-time divisions had made them ~150 instructions, most of a first layer's time)
+template <int PASS> __device__ inline long long a_index(const Args& a, int row, int kk) {
+  const ConvGeom& g = a.g;
   if (PASS == PASS_FWD) {
-    int q = row % g.Q, t = row / g.Q, p = t % g.P, n = t / g.P;
-    int c = kk % g.C, t2 = kk / g.C, s = t2 % g.S, r = t2 / g.S;
+    const int t = div_magic(row, a.magicQ, a.shiftQ), q = row - t * g.Q, n = div_magic(t, a.magicP, a.shiftP), p = t - n * g.P;
+    const int t2 = div_magic(kk, a.magicC, a.shiftC), c = kk - t2 * g.C, r = div_magic(t2, a.magicS, a.shiftS), s = t2 - r * g.S;
     int h = p * g.stride + r - g.pad, w = q * g.stride + s - g.pad;
     if (h < 0 || h >= g.H || w < 0 || w >= g.W) return -1;
     return (((long long)n * g.H + h) * g.W + w) * g.C + c;
   } else if (PASS == PASS_DGRAD) {
-    int w = row % g.W, t = row / g.W, h = t % g.H, n = t / g.H;
-    int ko = kk % g.K, t2 = kk / g.K, s = t2 % g.S, r = t2 / g.S;
+    const int t = div_magic(row, a.magicW, a.shiftW), w = row - t * g.W, n = div_magic(t, a.magicH, a.shiftH), h = t - n * g.H;
+    const int t2 = div_magic(kk, a.magicK, a.shiftK), ko = kk - t2 * g.K, r = div_magic(t2, a.magicS, a.shiftS), s = t2 - r * g.S;
     int hp = h + g.pad - r, wp = w + g.pad - s;
     if (hp < 0 || wp < 0) return -1;
     int p = hp / g.stride, q = wp / g.stride;
     if (p * g.stride != hp || q * g.stride != wp || p >= g.P || q >= g.Q) return -1;
     return (((long long)n * g.P + p) * g.Q + q) * g.K + ko;
   } else {
-    int c = row % g.C, t2 = row / g.C, s = t2 % g.S, r = t2 / g.S;
-    int q = kk % g.Q, t = kk / g.Q, p = t % g.P, n = t / g.P;
+    const int t2 = div_magic(row, a.magicC, a.shiftC), c = row - t2 * g.C, r = div_magic(t2, a.magicS, a.shiftS), s = t2 - r * g.S;
+    const int t = div_magic(kk, a.magicQ, a.shiftQ), q = kk - t * g.Q, n = div_magic(t, a.magicP, a.shiftP), p = t - n * g.P;
     int h = p * g.stride + r - g.pad, w = q * g.stride + s - g.pad;
     if (h < 0 || h >= g.H || w < 0 || w >= g.W) return -1;
     return (((long long)n * g.H + h) * g.W + w) * g.C + c;
   }
 }
-template <int PASS> __device__ inline long long b_index(const ConvGeom& g, int col, int kk) {
+template <int PASS> __device__ inline long long b_index(const Args& a, int col, int kk) {
+  const ConvGeom& g = a.g;
   if (PASS == PASS_DGRAD) {
-    int ko = kk % g.K, rs = kk / g.K;
+    const int rs = div_magic(kk, a.magicK, a.shiftK), ko = kk - rs * g.K;
     return ((long long)rs * g.C + col) * g.K + ko;
   }
   return (long long)kk * g.K + col;  // filters as [(r,s,c)][ko], dy as [(n,p,q)][ko]
@@ -353,7 +357,7 @@ template <typename T, int PASS, int ROWS, bool IS_A, int BK_> struct ScalarLoade
       int row = row0 + rl, kk = kbase + kl;
       long long idx = -1;
       if (row < (IS_A ? a.Mg : a.Ng) && kk < a.Kg)
-        idx = IS_A ? a_index<PASS>(a.g, row, kk) : b_index<PASS>(a.g, row, kk);
+        idx = IS_A ? a_index<PASS>(a, row, kk) : b_index<PASS>(a, row, kk);
       v[i] = idx >= 0 ? src[idx] : (T)0;
     }
     kbase += BK;
@@ -738,6 +742,9 @@ void fill_sizes(Args& a, int pass, int dtype) {
   magic_div(g.P, a.magicP, a.shiftP);
   magic_div(g.W, a.magicW, a.shiftW);
   magic_div(g.H, a.magicH, a.shiftH);
+  magic_div(g.C, a.magicC, a.shiftC);
+  magic_div(g.K, a.magicK, a.shiftK);
+  magic_div(g.S, a.magicS, a.shiftS);
 }
 
 void fill_tiles(Args& a, int BM, int BN, int BK) {

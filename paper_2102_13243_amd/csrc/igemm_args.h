@@ -43,7 +43,14 @@ struct Args {
   int shiftQ, shiftP;
   uint32_t magicW, magicH;          // x / W and x / H (input pixel index -> n,h,w)
   int shiftW, shiftH;
+  uint32_t magicC, magicK, magicS;  // x / C, x / K, x / S (k index -> tap and channel; element-wise loaders)
+  int shiftC, shiftK, shiftS;
 };
+
+// x / d for 0 <= x < 2^31 with the host-computed (magic, shift) of d (magic_div in igemm.hip)
+__device__ inline int div_magic(int x, uint32_t magic, int shift) {
+  return (int)((__umulhi((uint32_t)x, magic) + (uint32_t)x) >> shift);
+}
 
 
 // Workgroup -> (output tile, split of the reduction axis).  Workgroup ids are dealt round-robin to the
