@@ -112,16 +112,16 @@ template <typename T, int ROWS, int BK_> struct FwdALoader : KLoaderBase<T, ROWS
     for (int i = 0; i < B_::NP; ++i) {
       int row = row0 + tid / B_::CPR + i * B_::RPP;
       rv[i] = row < a.Mg && (ROWS % B_::RPP == 0 || tid / B_::CPR + i * B_::RPP < ROWS);
-      int q = row % g.Q, t = row / g.Q, p = t % g.P, n = t / g.P;
+      const int t = div_magic(row, a.magicQ, a.shiftQ), q = row - t * g.Q, n = div_magic(t, a.magicP, a.shiftP), p = t - n * g.P;
       base[i] = (long long)n * g.H * g.W * g.C;
       h0[i] = p * g.stride - g.pad;
       w0[i] = q * g.stride - g.pad;
     }
     int kk = kt0 * B_::BK + (tid % B_::CPR) * B_::VEC;
-    c = kk % g.C;
-    int t2 = kk / g.C;
-    s = t2 % g.S;
-    r = t2 / g.S;
+    const int t2 = div_magic(kk, a.magicC, a.shiftC);
+    c = kk - t2 * g.C;
+    r = div_magic(t2, a.magicS, a.shiftS);
+    s = t2 - r * g.S;
   }
   __device__ void load(const Args& a) {
     const ConvGeom& g = a.g;
@@ -154,16 +154,16 @@ template <typename T, int ROWS, int BK_> struct DgradALoader : KLoaderBase<T, RO
     for (int i = 0; i < B_::NP; ++i) {
       int row = row0 + tid / B_::CPR + i * B_::RPP;
       rv[i] = row < a.Mg && (ROWS % B_::RPP == 0 || tid / B_::CPR + i * B_::RPP < ROWS);
-      int w = row % g.W, t = row / g.W, h = t % g.H, n = t / g.H;
+      const int t = div_magic(row, a.magicW, a.shiftW), w = row - t * g.W, n = div_magic(t, a.magicH, a.shiftH), h = t - n * g.H;
       base[i] = (long long)n * g.P * g.Q * g.K;
       hp0[i] = h + g.pad;
       wp0[i] = w + g.pad;
     }
     int kk = kt0 * B_::BK + (tid % B_::CPR) * B_::VEC;
-    ko = kk % g.K;
-    int t2 = kk / g.K;
-    s = t2 % g.S;
-    r = t2 / g.S;
+    const int t2 = div_magic(kk, a.magicK, a.shiftK);
+    ko = kk - t2 * g.K;
+    r = div_magic(t2, a.magicS, a.shiftS);
+    s = t2 - r * g.S;
   }
   __device__ void load(const Args& a) {
     const ConvGeom& g = a.g;
@@ -207,8 +207,8 @@ template <typename T, int ROWS, int BK_> struct DgradBLoader : KLoaderBase<T, RO
       rv[i] = cidx[i] < a.Ng && (ROWS % B_::RPP == 0 || tid / B_::CPR + i * B_::RPP < ROWS);
     }
     int kk = kt0 * B_::BK + (tid % B_::CPR) * B_::VEC;
-    ko = kk % a.g.K;
-    rs = kk / a.g.K;
+    rs = div_magic(kk, a.magicK, a.shiftK);
+    ko = kk - rs * a.g.K;
   }
   __device__ void load(const Args& a) {
     const ConvGeom& g = a.g;
@@ -297,18 +297,17 @@ template <typename T, int ROWS, int BK_> struct WgradALoader : RLoaderBase<T, RO
     const ConvGeom& g = a.g;
     int i0 = row0 + B_::rchunk(tid) * B_::VEC;
     rv = B_::active(tid) && i0 < a.Mg;
-    c0 = i0 % g.C;
-    int t2 = i0 / g.C;
-    s = t2 % g.S;
-    r = t2 / g.S;
+    const int t2 = div_magic(i0, a.magicC, a.shiftC);
+    c0 = i0 - t2 * g.C;
+    r = div_magic(t2, a.magicS, a.shiftS);
+    s = t2 - r * g.S;
     m = kt0 * B_::BK + B_::kgroup(tid) * B_::KP;
 #pragma unroll
     for (int u = 0; u < B_::KP; ++u) {
-      int mm = m + u;
-      pq[u] = mm % g.Q;
-      int t = mm / g.Q;
-      pp[u] = t % g.P;
-      pn[u] = t / g.P;
+      const int mm = m + u, t = div_magic(mm, a.magicQ, a.shiftQ);
+      pq[u] = mm - t * g.Q;
+      pn[u] = div_magic(t, a.magicP, a.shiftP);
+      pp[u] = t - pn[u] * g.P;
     }
   }
   __device__ void load(const Args& a) {
