@@ -178,6 +178,49 @@ CONV_SHAPES = [
 ]
 
 
+def _random_conv_shapes(count, seed):
+    """Seeded shapes drawn from the values at which the library switches kernels (channel counts around the
+    loaders' vector widths and the LDS-patch kernel's 16/24/32/64, image sizes around its 8/16/32-wide tiles,
+    1x1 / 3x3 / 5x5 filters, both strides), so that every combination of dispatch conditions gets visited."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        n = int(rng.choice([1, 2, 3, 4, 6, 8]))
+        h = int(rng.choice([4, 7, 8, 12, 16, 24, 32]))
+        w = int(rng.choice([4, 7, 8, 12, 16, 24, 32]))
+        c = int(rng.choice([3, 4, 6, 8, 16, 24, 32, 48, 64, 96]))
+        k = int(rng.choice([4, 6, 8, 16, 24, 32, 48, 64, 96]))
+        r = int(rng.choice([1, 3, 3, 5]))
+        s = r if rng.random() < 0.8 else int(rng.choice([1, 3]))
+        stride = int(rng.choice([1, 1, 2]))
+        pad = int(rng.choice([0, max(r, s) // 2]))
+        kind = rng.random()
+        if kind < 0.3:     # around the LDS-patch kernel's 3x3 shapes: some tile (rows of an image, whole images), some do not
+            c = k = int(rng.choice([16, 32, 64]))
+            r = s = 3
+            stride = pad = 1
+            w = int(rng.choice([8, 16, 32]))
+            h = int(rng.choice([4, 8, 12, 16, 32]))
+        elif kind < 0.5:   # around its 1x1 shapes: a short reduction axis on either side
+            r = s = 1
+            stride, pad = 1, 0
+            if rng.random() < 0.5:
+                c = int(rng.choice([16, 24, 32, 64]))
+            else:
+                k = int(rng.choice([16, 24, 32, 64]))
+            h, w = int(rng.choice([4, 8, 16])), int(rng.choice([8, 16, 32]))
+        if h + 2 * pad < r or w + 2 * pad < s:
+            continue
+        out.append((n, h, w, c, k, r, stride, pad, s))
+    return out
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", _random_conv_shapes(48, 20210227), ids=lambda s: "x".join(map(str, s)))
+def test_conv2d_seeded_random_shapes(shape, bf16):
+    test_conv2d_fwd_and_vjp(shape, bf16)
+
+
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
 @pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_conv2d_fwd_and_vjp(shape, bf16):
@@ -272,6 +315,29 @@ def test_depthwise_conv(shape, bf16):
 
 
 BN_SHAPES = [(2, 5, 7, 16), (4, 16, 16, 64), (3, 9, 9, 6), (2, 7, 7, 960), (64, 8, 8, 32), (1, 1, 3, 8)]
+
+
+def _random_bn_cases(count, seed):
+    """Seeded (shape, act, use_res) cases: channel counts on both sides of the vector widths (4, 8) and of the
+    64 channel vectors a block takes, pixel counts from one to a few thousand (one chunk to many)."""
+    rng = np.random.default_rng(seed)
+    acts = [("none", False), ("relu", False), ("relu", True), ("relu6", True), ("relu6", False)]
+    out = []
+    while len(out) < count:
+        shape = (int(rng.choice([1, 2, 3, 5, 8, 17])), int(rng.choice([1, 3, 7, 14, 28])), int(rng.choice([1, 3, 7, 14, 28])),
+                 int(rng.choice([1, 3, 4, 6, 8, 12, 16, 24, 64, 96, 256, 520, 960])))
+        # (with a handful of pixels xhat is +-1 up to eps and dx cancels down to eps/var of its terms: no relative
+        # bound means anything there; the fixed shapes keep one such case, 1x1x3, under its own absolute bound)
+        if shape[0] * shape[1] * shape[2] < 16:
+            continue
+        out.append((shape,) + acts[int(rng.integers(len(acts)))])
+    return out
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("case", _random_bn_cases(32, 1302), ids=lambda c: "x".join(map(str, c[0])) + "-" + c[1] + ("-res" if c[2] else ""))
+def test_bn_seeded_random_shapes(case, bf16):
+    test_bn_relu_fwd_and_vjp(case[0], case[1], case[2], bf16)
 
 
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
