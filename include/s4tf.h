@@ -66,7 +66,8 @@ typedef enum { S4TF_F32 = 0, S4TF_BF16 = 1 } s4tf_dtype;
 typedef enum { S4TF_ACT_NONE = 0, S4TF_ACT_RELU = 1, S4TF_ACT_RELU6 = 2 } s4tf_act;
 
 /* Convolution.  x is (n,h,w,c), w is (r,s,c/groups,k), y is (n,p,q,k).  groups must be 1
- * or c (depthwise, which also needs k == c).  act is applied to conv + bias in the
+ * or c (depthwise, which also needs k == c and a filter of at most 3x3; anything else is refused
+ * with S4TF_ERR_UNSUPPORTED before anything runs).  act is applied to conv + bias in the
  * forward pass (the `activation: relu` of the paper's Conv2D/Dense layers).
  * accumulate_dx != 0 makes the pullback ADD the input cotangent to what dx already holds
  * (the `inout` formulation of a pullback, Section 4.3) instead of overwriting it. */

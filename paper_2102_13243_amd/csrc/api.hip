@@ -67,6 +67,10 @@ int check_conv_desc(const s4tf_conv_desc* d) {
   if (d->c % d->groups || d->k % d->groups) return fail(S4TF_ERR_SHAPE, "conv: c and k must be multiples of groups");
   if (d->groups != 1 && !(d->groups == d->c && d->k == d->c))
     return fail(S4TF_ERR_UNSUPPORTED, "conv: groups must be 1 or c with k == c (depthwise)");
+  // (the depthwise filter gradient keeps one sum per tap in registers; refused here, for every pass, so that a
+  // pullback or a training step cannot fail after its first kernels have run)
+  if (d->groups != 1 && (d->r > 3 || d->s > 3))
+    return fail(S4TF_ERR_UNSUPPORTED, "conv: depthwise filters larger than 3x3 are not supported");
   ConvGeom g = conv_geom(*d);
   if ((long long)d->n * d->h * d->w * d->c > kMaxElems || (long long)d->n * g.P * g.Q * d->k > kMaxElems ||
       (long long)d->r * d->s * d->c * d->k > kMaxElems)

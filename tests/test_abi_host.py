@@ -69,6 +69,9 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.s4tf_conv2d_fwd(ctypes.byref(bad), 16, 16, None, 16, None, 0, None) == -2
     bad = B.ConvDesc(1, 8, 8, 4, 4, 3, 3, 1, 1, 2, B.S4TF_F32, 0, 0)                    # 1 < groups < c
     assert L.s4tf_conv2d_fwd(ctypes.byref(bad), 16, 16, None, 16, None, 0, None) == -4
+    bad = B.ConvDesc(1, 8, 8, 4, 4, 5, 5, 1, 2, 4, B.S4TF_F32, 0, 0)                    # depthwise, filter above 3x3
+    assert L.s4tf_conv2d_fwd(ctypes.byref(bad), 16, 16, None, 16, None, 0, None) == -4
+    assert "3x3" in B.last_error()
     bad = B.ConvDesc(1, 8, 8, 4, 4, 3, 3, 1, 1, 1, 7, 0, 0)                             # dtype
     assert L.s4tf_conv2d_fwd(ctypes.byref(bad), 16, 16, None, 16, None, 0, None) == -3
     bad = B.ConvDesc(1, 2, 2, 4, 4, 5, 5, 1, 0, 1, B.S4TF_F32, 0, 0)                    # filter > input

@@ -276,6 +276,23 @@ DW_SHAPES = [(2, 14, 14, 32, 3, 1, 1), (2, 15, 15, 96, 3, 2, 1), (1, 7, 7, 960, 
              (2, 11, 11, 8, 2, 2, 0)]       # 2x2 filter
 
 
+def _random_dw_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        r = int(rng.choice([3, 3, 3, 2, 1]))   # (depthwise filters above 3x3 are refused by the library)
+        shape = (int(rng.choice([1, 2, 3, 5])), int(rng.choice([5, 7, 9, 14, 17, 28])), int(rng.choice([5, 7, 9, 14, 17, 28])),
+                 int(rng.choice([4, 6, 8, 12, 24, 32, 96, 144])), r, int(rng.choice([1, 2])), int(rng.choice([0, r // 2])))
+        out.append(shape)
+    return out
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", _random_dw_shapes(24, 4404), ids=lambda s: "x".join(map(str, s)))
+def test_depthwise_seeded_random_shapes(shape, bf16):
+    test_depthwise_conv(shape, bf16)
+
+
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
 @pytest.mark.parametrize("shape", DW_SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_depthwise_conv(shape, bf16):
