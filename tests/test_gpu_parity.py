@@ -441,6 +441,37 @@ def test_pool2d(kind, shape, bf16):
     check("pool dx accumulated", dx2, base + dx_ref, bf16, tol)
 
 
+def _random_pool_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        kind = int(rng.choice([B.POOL_AVG2, B.POOL_MAX3S2]))
+        shape = (int(rng.choice([1, 2, 3, 7])), int(rng.choice([1, 2, 3, 5, 8, 9, 28])), int(rng.choice([1, 2, 3, 5, 8, 9, 28])),
+                 int(rng.choice([1, 3, 4, 6, 8, 16, 20, 64])))
+        if kind == B.POOL_AVG2 and min(shape[1], shape[2]) < 2:
+            continue
+        out.append((kind, shape))
+    return out
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("case", _random_pool_cases(24, 909), ids=lambda c: ("avg" if c[0] == B.POOL_AVG2 else "max") + "x".join(map(str, c[1])))
+def test_pool2d_seeded_random_shapes(case, bf16):
+    test_pool2d(case[0], case[1], bf16)
+
+
+def _random_head_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.choice([1, 2, 5, 16, 33])), int(rng.choice([1, 2, 4, 7])), int(rng.choice([1, 3, 4, 7])),
+             int(rng.choice([3, 8, 20, 64, 84, 320])), int(rng.choice([2, 7, 10, 100, 1000]))) for _ in range(count)]
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", _random_head_shapes(12, 31), ids=lambda s: "x".join(map(str, s)))
+def test_head_seeded_random_shapes(shape, bf16):
+    test_head(shape, bf16)
+
+
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(8, 16, 16, 16, 10), (128, 1, 1, 84, 10), (6, 7, 7, 256, 1000), (3, 2, 3, 20, 7)],
                          ids=lambda s: "x".join(map(str, s)))
