@@ -203,3 +203,90 @@ def test_new_entry_points_reject_bad_arguments_on_the_host():
     cap, needed = B.s4tf_bn_relu_fwd_static_limit(big)
     assert cap == 1 << 20 and needed > cap
     assert L.s4tf_bn_relu_fwd_static(ctypes.byref(big), 16, None, 16, 16, 16, 16, 16, None) == -5
+
+
+def test_seeded_random_descriptors_never_get_past_the_host_checks():
+    """2000 convolution, BatchNorm and pool descriptors with fields drawn from valid and invalid values, data
+    pointers NULL: every call must come back with an error status (a bad descriptor's own, else NULL) and an
+    error text, every workspace query with a size, and nothing may crash.  No device is touched."""
+    L = B.lib()
+    rng = np.random.default_rng(77)
+    vals = [-3, 0, 1, 2, 3, 4, 5, 7, 8, 16, 24, 64, 224, 1 << 12, 1 << 20, (1 << 31) - 1]
+    small = [-1, 0, 1, 2, 3, 5, 7]
+    seen = set()
+    for _ in range(2000):
+        pick = lambda v: int(rng.choice(v))
+        d = B.ConvDesc(pick(vals), pick(vals), pick(vals), pick(vals), pick(vals), pick(small), pick(small), pick(small),
+                       pick(small), pick([0, 1, 2, 4, 8, 16, 64]), pick([0, 1, 2, -1]), pick([0, 1, 2, 3]), pick([0, 1]))
+        rc = L.s4tf_conv2d_fwd(ctypes.byref(d), None, None, None, None, None, 0, None)
+        assert rc in (-1, -2, -3, -4), rc
+        assert B.last_error()
+        seen.add(rc)
+        rc = L.s4tf_conv2d_vjp(ctypes.byref(d), None, None, None, None, None, None, None, None, 0, None)
+        assert rc in (-1, -2, -3, -4), rc
+        assert B.s4tf_conv2d_vjp_workspace_bytes(d) >= 0
+        assert B.s4tf_conv2d_fwd_workspace_bytes(d) >= 0
+        bd = B.BnDesc(pick(vals), pick(vals), pick(vals), pick(vals), float(rng.choice([-1.0, 0.0, 1e-5, float("nan")])),
+                      pick([0, 1, 2, 3]), pick([0, 1, 2]), pick([0, 1]))
+        rc = L.s4tf_bn_relu_fwd(ctypes.byref(bd), None, None, None, None, None, None, None, None, 0, None)
+        assert rc in (-1, -2, -3, -4), rc
+        assert int(L.s4tf_bn_relu_workspace_bytes(ctypes.byref(bd))) >= 0
+        pd = B.PoolDesc(pick(vals), pick(vals), pick(vals), pick(vals), pick([0, 1, 2, -1]), pick([0, 1, 2]), pick([0, 1]))
+        rc = L.s4tf_pool2d_fwd(ctypes.byref(pd), None, None, None)
+        assert rc in (-1, -2, -3, -4), rc
+    assert seen == {-1, -2, -3, -4}, seen   # valid descriptors (NULL pointers) and each kind of bad one occurred
+
+
+def test_seeded_random_networks_are_planned_or_refused_without_a_crash():
+    """3000 op lists with kinds, tensor references and sizes drawn at random (mostly nonsense, some valid by
+    construction: a mutated valid net).  Planning must either give a handle whose queries are sane or refuse with an
+    error text; no crash, no handle for a net whose head is not its last op.  No device is touched."""
+    L = B.lib()
+    rng = np.random.default_rng(4242)
+    base = nets.resnet56(batch=2, blocks_per_stage=1, hw=8)
+    planned = refused = 0
+    for it in range(3000):
+        if it % 3 == 0:    # a valid net with a few fields mutated
+            ops = [dict(o) for o in base["ops"]]
+            for _ in range(int(rng.integers(1, 4))):
+                o = ops[int(rng.integers(len(ops)))]
+                key = str(rng.choice(["in", "k", "r", "stride", "pad", "res", "groups"]))
+                if key in o:
+                    o[key] = int(rng.choice([-2, -1, 0, 1, 2, 3, 5, 7, 16, 1 << 20]))
+                    if key == "r":
+                        o["s"] = o[key]
+            desc, keep = B.make_net_desc(dict(base, ops=ops))
+        else:              # raw op records
+            n_ops = int(rng.integers(1, 12))
+            ops = (B.Op * n_ops)()
+            for i, o in enumerate(ops):
+                o.kind = int(rng.integers(-1, 8))
+                o.in_ = int(rng.integers(-2, n_ops + 2))
+                o.res = int(rng.integers(-2, n_ops + 2))
+                o.k = int(rng.choice([-1, 0, 1, 4, 10, 16, 1 << 24]))
+                o.r = o.s = int(rng.choice([-1, 0, 1, 3, 5, 9]))
+                o.stride = int(rng.choice([-1, 0, 1, 2, 3]))
+                o.pad = int(rng.choice([-1, 0, 1, 2, 100]))
+                o.groups = int(rng.choice([-1, 0, 1, 2, 4, 16]))
+                o.has_bias = int(rng.integers(0, 2))
+                o.act = int(rng.integers(-1, 4))
+                o.eps = float(rng.choice([-1.0, 0.0, 1e-5]))
+            if rng.random() < 0.5:
+                ops[n_ops - 1].kind = B.OP_HEAD
+            desc = B.NetDesc(int(rng.choice([0, 1, 2, 8])), int(rng.choice([0, 1, 8, 32])), int(rng.choice([1, 8, 32])),
+                             int(rng.choice([0, 1, 3, 4])), int(rng.choice([0, 1, 5])), n_ops, ops, 0.9)
+            keep = ops
+        out = ctypes.c_void_p()
+        rc = L.s4tf_net_create(ctypes.byref(desc), ctypes.byref(out))
+        if rc == 0:
+            planned += 1
+            assert out.value
+            assert desc.ops[desc.n_ops - 1].kind == B.OP_HEAD
+            assert B.s4tf_net_param_count(desc) > 0
+            assert B.s4tf_train_step_workspace_bytes(desc) > 0
+            L.s4tf_net_destroy(out)
+        else:
+            refused += 1
+            assert rc < 0 and B.last_error()
+            assert not out.value
+    assert planned >= 50 and refused >= 1000, (planned, refused)
